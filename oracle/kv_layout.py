@@ -1,0 +1,124 @@
+"""KV-pool format and the reference copies over it (test infrastructure only).
+
+The paper fixes only that the KV cache is managed in pages of 16 tokens reached through a
+per-request page table, that it is append-only, and that checkpointing gathers scattered
+pages into one contiguous buffer (Sec. 4.4 and Sec. 5).  The byte format inside a page is
+this library's own and is restated here independently, as plain index arithmetic.
+
+Pool, in bf16 elements:   pool[layer][page][kv (0 = K, 1 = V)][kv_head][16 * D]
+so one (layer, page) is one contiguous blob of 2 * Hkv * 16 * D elements.
+
+Inside a K block (one page, one kv head; token t in 0..15, feature d in 0..D-1):
+    element index = ((d // 8) * 16 + t) * 8 + d % 8
+    i.e. [D/8 feature blocks][16 tokens][8 features]: a 16-byte unit is 8 consecutive
+    features of one token, and the 16 tokens of a feature block are adjacent.
+Inside a V block:
+    element index = (((d // 16) * 4 + t // 4) * 16 + d % 16) * 4 + t % 4
+    i.e. [D/16 feature tiles][4 token groups][16 features][4 tokens]: an 8-byte unit is one
+    feature of 4 consecutive tokens.
+
+Arrays here are numpy uint16 (bf16 bit patterns); copies are bit copies.
+"""
+import numpy as np
+
+PAGE = 16
+
+
+def k_index(t, d, D):
+    """Element index of K[token t][feature d] inside its block."""
+    t = np.asarray(t)
+    d = np.asarray(d)
+    return ((d // 8) * 16 + t) * 8 + d % 8
+
+
+def v_index(t, d, D):
+    """Element index of V[token t][feature d] inside its block."""
+    t = np.asarray(t)
+    d = np.asarray(d)
+    return (((d // 16) * 4 + t // 4) * 16 + d % 16) * 4 + t % 4
+
+
+def page_elems(Hkv, D):
+    """bf16 elements of one (layer, page): K and V of every kv head."""
+    return 2 * Hkv * PAGE * D
+
+
+def kv_bytes_per_token(Hkv, D, L):
+    """Bytes of KV cache one token occupies over L layers (bf16)."""
+    return 2 * Hkv * D * 2 * L
+
+
+def new_pool(L, P, Hkv, D, fill=0):
+    return np.full((L, P, 2, Hkv, PAGE * D), fill, dtype=np.uint16)
+
+
+def ref_append(pool, layer, block_tables, ctx_lens, cu_q_lens, k_new, v_new):
+    """Append this step's new K/V rows (paper Sec. 1 / 4.4: the cache is append-only).
+
+    New token i of request s goes to position pos = ctx_lens[s] + i, i.e. to page
+    block_tables[s][pos // 16], token slot pos % 16.  k_new / v_new: uint16 [T, Hkv, D],
+    packed in request order (cu_q_lens = prefix sums of the requests' new-token counts).
+    Every other slot of the pool is left untouched.  In place.
+    """
+    L, P, _, Hkv, BD = pool.shape
+    D = BD // PAGE
+    d = np.arange(D)
+    for s in range(len(ctx_lens)):
+        for i in range(int(cu_q_lens[s + 1]) - int(cu_q_lens[s])):
+            tok = int(cu_q_lens[s]) + i
+            pos = int(ctx_lens[s]) + i
+            page = int(block_tables[s][pos // PAGE])
+            assert 0 <= page < P, "block table entry out of range"
+            t = pos % PAGE
+            for h in range(Hkv):
+                pool[layer, page, 0, h, k_index(t, d, D)] = k_new[tok, h, :]
+                pool[layer, page, 1, h, v_index(t, d, D)] = v_new[tok, h, :]
+    return pool
+
+
+def read_logical(pool, layer, block_table_row, n):
+    """Logical K, V (uint16 [n, Hkv, D]) of a request holding n tokens, read through its
+    block table row: the inverse of the format above."""
+    L, P, _, Hkv, BD = pool.shape
+    D = BD // PAGE
+    K = np.empty((n, Hkv, D), dtype=np.uint16)
+    V = np.empty((n, Hkv, D), dtype=np.uint16)
+    d = np.arange(D)
+    t = np.arange(PAGE)
+    ki = k_index(t[:, None], d[None, :], D)      # [16, D]
+    vi = v_index(t[:, None], d[None, :], D)
+    for b in range((n + PAGE - 1) // PAGE):
+        page = int(block_table_row[b])
+        cnt = min(PAGE, n - b * PAGE)
+        kb = pool[layer, page, 0][:, ki]          # [Hkv, 16, D]
+        vb = pool[layer, page, 1][:, vi]
+        K[b * PAGE:b * PAGE + cnt] = kb.transpose(1, 0, 2)[:cnt]
+        V[b * PAGE:b * PAGE + cnt] = vb.transpose(1, 0, 2)[:cnt]
+    return K, V
+
+
+def ref_gather(pool, layer_begin, layer_end, page_ids):
+    """Checkpoint gather (paper Sec. 5: scattered pages -> one contiguous buffer):
+    staging[l - layer_begin][i] = whole page pool[l][page_ids[i]] (K and V)."""
+    L, P, _, Hkv, BD = pool.shape
+    n = len(page_ids)
+    staging = np.empty((layer_end - layer_begin, n, 2 * Hkv * BD), dtype=np.uint16)
+    for l in range(layer_begin, layer_end):
+        for i in range(n):
+            staging[l - layer_begin, i, :] = pool[l, int(page_ids[i])].reshape(-1)
+    return staging
+
+
+def ref_restore(pool, layer_begin, layer_end, page_ids, staging):
+    """Restore (paper Sec. 4.4, prefetch on resume): pool[l][page_ids[i]] = staging[l][i].
+    In place; the ids are distinct."""
+    L, P, _, Hkv, BD = pool.shape
+    for l in range(layer_begin, layer_end):
+        for i in range(len(page_ids)):
+            pool[l, int(page_ids[i])] = staging[l - layer_begin, i].reshape(2, Hkv, BD)
+    return pool
+
+
+def bf16_bits_to_f32(bits):
+    """Widen bf16 bit patterns (uint16) to float32 exactly."""
+    return (np.asarray(bits).astype(np.uint32) << 16).view(np.float32)
