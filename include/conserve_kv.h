@@ -1,0 +1,149 @@
+/*
+ * conserve_kv.h -- C ABI of the MI355X (gfx950) kernels for the per-layer GPU hot path of
+ * online/offline LLM co-serving: KV append, paged attention over a mixed batch of decode
+ * and chunked-prefill tokens, and the gather / restore copies of incremental KV
+ * checkpointing (paper Sec. 4.2, 4.3, 4.4, 5).
+ *
+ * Conventions for every call
+ *   - returns a cs_status (0 = CS_OK, negative = error); all checks that need only host
+ *     data are made before anything is enqueued, and a failed call enqueues nothing;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
+ *     calls never synchronise, never allocate or free, and keep no state between calls;
+ *   - every pointer is owned by the caller and must stay valid until the enqueued work has
+ *     run.  "device" pointers are HIP device memory of the current device, "host" pointers
+ *     are ordinary host memory read during the call only;
+ *   - bf16 data only, 16 tokens per page (the paper's page granularity, Sec. 5),
+ *     head_dim 64 or 128, num_q_heads / num_kv_heads <= 16;
+ *   - each call works on ONE decoder layer (attention, append) or a layer range (gather,
+ *     restore), so that a scheduler can stop between layers (layer-wise preemption,
+ *     Sec. 4.3): sequences are expected online-first, and passing a smaller num_seqs /
+ *     num_tokens with the same arrays drops the offline tail without rebuilding metadata;
+ *   - device index arrays (block tables, page id lists) are not validated on the host (that
+ *     would need a synchronisation); kernels skip any page id outside [0, num_pages).
+ *
+ * KV pool format (this library's own; the paper fixes only the 16-token page and the
+ * per-request page table).  In bf16 elements:
+ *
+ *     pool[layer][page][kv: 0 = K, 1 = V][kv_head][16 * head_dim]
+ *
+ * with layer_stride and page_stride given explicitly, so one (layer, page) is a contiguous
+ * blob of 2 * num_kv_heads * 16 * head_dim elements ("page_elems").  Inside a block
+ * (token t = 0..15 of the page, feature d):
+ *     K:  ((d / 8) * 16 + t) * 8 + d % 8                 [D/8][16 tokens][8 features]
+ *     V:  (((d / 16) * 4 + t / 4) * 16 + d % 16) * 4 + t % 4
+ *                                                        [D/16][4 token groups][16][4 tokens]
+ * These are the register layouts the gfx950 matrix instructions take for Q.K^T and P.V, so
+ * a wavefront reads a block with fully coalesced 16- and 8-byte loads and no shuffles.
+ */
+#ifndef CONSERVE_KV_H
+#define CONSERVE_KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    CS_OK = 0,
+    CS_ERR_INVALID_ARG = -1,        /* null pointer, negative count, inconsistent lengths */
+    CS_ERR_UNSUPPORTED = -2,        /* page size, head_dim or head ratio not supported   */
+    CS_ERR_WORKSPACE_TOO_SMALL = -3,
+    CS_ERR_STAGING_TOO_SMALL = -4,
+    CS_ERR_HIP = -5                 /* a launch failed; see cs_last_hip_error()          */
+} cs_status;
+
+#define CS_PAGE_SIZE 16
+
+/* The caller's KV pool.  Strides are in bf16 ELEMENTS. */
+typedef struct {
+    void*   base;                   /* device                                            */
+    int32_t num_layers;
+    int32_t num_pages;
+    int32_t page_size;              /* must be 16                                        */
+    int32_t num_kv_heads;
+    int32_t head_dim;               /* 64 or 128                                         */
+    int64_t layer_stride;           /* >= num_pages * page_stride                        */
+    int64_t page_stride;            /* >= page_elems, multiple of 8                      */
+} cs_kv_pool;
+
+/* One step's batch: S sequences, sequence s has ctx_lens[s] tokens already in the cache
+ * (the paper's C) and q_s = cu_q_lens[s+1] - cu_q_lens[s] new tokens this step (the paper's
+ * P; 1 for a decode token, >1 for a prefill chunk, 0 for an idle sequence).  New token i of
+ * sequence s has absolute position ctx_lens[s] + i. */
+typedef struct {
+    int32_t        num_seqs;            /* S */
+    int32_t        num_tokens;          /* T = cu_q_lens[S] */
+    const int32_t* block_tables;        /* device [S][max_blocks_per_seq] page ids; entries
+                                           past ceil((ctx+q)/16) are never read          */
+    int32_t        max_blocks_per_seq;
+    const int32_t* ctx_lens;            /* device [S]                                    */
+    const int32_t* cu_q_lens;           /* device [S+1]                                  */
+    const int32_t* h_ctx_lens;          /* host copy of ctx_lens, for launch planning    */
+    const int32_t* h_cu_q_lens;         /* host copy of cu_q_lens                        */
+} cs_batch;
+
+/* Bytes of one (layer, page): K and V of every kv head.  0 if the shape is unsupported. */
+size_t cs_page_bytes(int32_t num_kv_heads, int32_t head_dim);
+
+/* KV append (the cache is append-only, Sec. 1 and 4.4; pages of 16 tokens, Sec. 5).
+ * For every new token t = cu_q_lens[s] + i: copy k_new[t][h][:] and v_new[t][h][:] into
+ * page block_tables[s][(ctx_lens[s]+i)/16], slot (ctx_lens[s]+i)%16 of layer `layer`, in
+ * the pool format above.  No other slot is written.  k_new, v_new: device [T][Hkv][D] bf16.
+ * T == 0 is a no-op. */
+int cs_kv_append(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                 const void* k_new, const void* v_new, void* stream);
+
+/* Workspace the attention call needs for this batch (split partials of the decode path).
+ * Depends only on the host arrays of `batch` and the shape.  Returns 0 on bad arguments. */
+size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t num_q_heads,
+                                          int32_t num_kv_heads, int32_t head_dim);
+
+/* Paged attention of one layer over a mixed batch (Sec. 4.2: a batch holds online and
+ * offline tokens together; the attention term P(P+C); chunked prefill).  For new token t of
+ * sequence s at position p and query head h (kv head h / (Hq/Hkv)):
+ *     out[t][h][:] = sum_{j<=p} softmax_j(scale * <q[t][h], K_s[j]>) * V_s[j]
+ * where K_s, V_s are read from the pool through block_tables[s].  The step's own new K/V
+ * must already be in the pool (call cs_kv_append first on the same stream).  Sequences with
+ * one new token take the split-KV decode path, longer chunks the MFMA tile path.
+ * q, out: device [T][Hq][D] bf16.  workspace: device, at least
+ * cs_paged_attention_workspace_bytes(); contents are scratch. */
+int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                             const void* q, void* out, int32_t num_q_heads,
+                             float softmax_scale, void* workspace, size_t workspace_bytes,
+                             void* stream);
+
+/* Checkpoint gather (Sec. 5: the KV of scattered pages is gathered into one contiguous
+ * buffer and transferred once; Sec. 4.4: only newly filled pages are checkpointed).
+ *     staging[l - layer_begin][i][0 .. page_elems) = pool[l][page_ids[i]][...]
+ * for layer_begin <= l < layer_end, 0 <= i < n.  page_ids: device [n]; duplicates allowed.
+ * staging: device, (layer_end-layer_begin) * n * cs_page_bytes() bytes, 16-byte aligned.
+ * n == 0 is a no-op. */
+int cs_kv_ckpt_gather(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                      const int32_t* page_ids, int32_t n,
+                      void* staging, size_t staging_bytes, void* stream);
+
+/* Restore (Sec. 4.4: evicted KV is brought back in the background on resume): the inverse
+ * copy, pool[l][page_ids[i]] = staging[l - layer_begin][i].  Ids must be distinct. */
+int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                       const int32_t* page_ids, int32_t n,
+                       const void* staging, size_t staging_bytes, void* stream);
+
+/* Plain device-to-device copy kernel of `bytes` (multiple of 16, both pointers 16-byte
+ * aligned): the measured copy ceiling of the device and the calibration point for hardware
+ * byte counters. */
+int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
+
+/* Tuning knob for measurements: force the decode path's tokens per split (multiple of 16,
+ * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */
+void cs_set_decode_split_tokens(int32_t tokens);
+
+const char* cs_status_string(int status);
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char* cs_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CONSERVE_KV_H */

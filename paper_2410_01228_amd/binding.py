@@ -1,0 +1,212 @@
+"""ctypes binding of libconserve_kv with the C names (see include/conserve_kv.h).
+
+Argument marshalling only: torch tensors are used for device memory and streams, every
+step of the path runs in the library's kernels.  There is no fallback: if the built
+library is missing, loading raises.
+"""
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libconserve_kv.so")
+
+CS_OK = 0
+CS_ERR_INVALID_ARG = -1
+CS_ERR_UNSUPPORTED = -2
+CS_ERR_WORKSPACE_TOO_SMALL = -3
+CS_ERR_STAGING_TOO_SMALL = -4
+CS_ERR_HIP = -5
+PAGE = 16
+
+
+class cs_kv_pool(ctypes.Structure):
+    _fields_ = [
+        ("base", ctypes.c_void_p),
+        ("num_layers", ctypes.c_int32),
+        ("num_pages", ctypes.c_int32),
+        ("page_size", ctypes.c_int32),
+        ("num_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32),
+        ("layer_stride", ctypes.c_int64),
+        ("page_stride", ctypes.c_int64),
+    ]
+
+
+class cs_batch(ctypes.Structure):
+    _fields_ = [
+        ("num_seqs", ctypes.c_int32),
+        ("num_tokens", ctypes.c_int32),
+        ("block_tables", ctypes.c_void_p),
+        ("max_blocks_per_seq", ctypes.c_int32),
+        ("ctx_lens", ctypes.c_void_p),
+        ("cu_q_lens", ctypes.c_void_p),
+        ("h_ctx_lens", ctypes.c_void_p),
+        ("h_cu_q_lens", ctypes.c_void_p),
+    ]
+
+
+class CsError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().cs_status_string(status).decode()
+        hip = lib().cs_last_hip_error().decode()
+        super().__init__("%s: %s (%d)%s" % (where, msg, status, (" [" + hip + "]") if hip else ""))
+
+
+_lib = None
+
+
+def lib():
+    """The loaded C library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libconserve_kv.so is not built (%s); run `python -m paper_2410_01228_amd.build`" % LIB_PATH)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        PP, BP = ctypes.POINTER(cs_kv_pool), ctypes.POINTER(cs_batch)
+        L.cs_page_bytes.restype, L.cs_page_bytes.argtypes = sz, [i32, i32]
+        L.cs_kv_append.restype, L.cs_kv_append.argtypes = ctypes.c_int, [PP, i32, BP, vp, vp, vp]
+        L.cs_paged_attention_workspace_bytes.restype = sz
+        L.cs_paged_attention_workspace_bytes.argtypes = [BP, i32, i32, i32]
+        L.cs_paged_attention_mixed.restype = ctypes.c_int
+        L.cs_paged_attention_mixed.argtypes = [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp, sz, vp]
+        for f in (L.cs_kv_ckpt_gather, L.cs_kv_ckpt_restore):
+            f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
+        L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
+        L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
+        L.cs_status_string.restype, L.cs_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
+        L.cs_last_hip_error.restype, L.cs_last_hip_error.argtypes = ctypes.c_char_p, []
+        _lib = L
+    return _lib
+
+
+EXPORTS = [
+    "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
+    "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_debug_copy",
+    "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
+]
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+class Pool:
+    """A cs_kv_pool over a torch tensor [L, P, 2, Hkv, 16*D] bf16 (or any tensor of that
+    many elements); keeps the tensor alive."""
+
+    def __init__(self, tensor: torch.Tensor, L: int, P: int, Hkv: int, D: int,
+                 layer_stride: Optional[int] = None, page_stride: Optional[int] = None):
+        self.tensor = tensor
+        self.page_elems = 2 * Hkv * PAGE * D
+        ps = self.page_elems if page_stride is None else page_stride
+        ls = P * ps if layer_stride is None else layer_stride
+        self.c = cs_kv_pool(_ptr(tensor), L, P, PAGE, Hkv, D, ls, ps)
+        self.L, self.P, self.Hkv, self.D = L, P, Hkv, D
+
+    @classmethod
+    def empty(cls, L, P, Hkv, D, device="cuda"):
+        t = torch.empty((L, P, 2, Hkv, PAGE * D), dtype=torch.bfloat16, device=device)
+        return cls(t, L, P, Hkv, D)
+
+
+class Batch:
+    """A cs_batch; device copies are made from the given CPU int32 tensors."""
+
+    def __init__(self, block_tables: torch.Tensor, ctx_lens: torch.Tensor, cu_q_lens: torch.Tensor,
+                 device="cuda", num_seqs: Optional[int] = None):
+        self.h_bt = block_tables.to(torch.int32).contiguous().cpu()
+        self.h_ctx = ctx_lens.to(torch.int32).contiguous().cpu()
+        self.h_cu = cu_q_lens.to(torch.int32).contiguous().cpu()
+        self.d_bt = self.h_bt.to(device)
+        self.d_ctx = self.h_ctx.to(device)
+        self.d_cu = self.h_cu.to(device)
+        S = self.h_ctx.numel() if num_seqs is None else num_seqs
+        self.max_blocks = int(self.h_bt.shape[1]) if self.h_bt.dim() == 2 and self.h_bt.numel() else 1
+        self.c = cs_batch(S, int(self.h_cu[S]), _ptr(self.d_bt), self.max_blocks, _ptr(self.d_ctx),
+                          _ptr(self.d_cu), _ptr(self.h_ctx), _ptr(self.h_cu))
+
+    def truncated(self, num_seqs: int) -> "Batch":
+        """The same arrays with only the first num_seqs sequences (what a layer-wise
+        preemption does between two layers; paper Sec. 4.3)."""
+        b = object.__new__(Batch)
+        b.__dict__.update(self.__dict__)
+        b.c = cs_batch(num_seqs, int(self.h_cu[num_seqs]), _ptr(self.d_bt), self.max_blocks,
+                       _ptr(self.d_ctx), _ptr(self.d_cu), _ptr(self.h_ctx), _ptr(self.h_cu))
+        return b
+
+    @property
+    def num_tokens(self):
+        return self.c.num_tokens
+
+    @property
+    def num_seqs(self):
+        return self.c.num_seqs
+
+
+def _check(rc, where):
+    if rc != CS_OK:
+        raise CsError(rc, where)
+
+
+def cs_page_bytes(Hkv: int, D: int) -> int:
+    return int(lib().cs_page_bytes(Hkv, D))
+
+
+def cs_kv_append(pool: Pool, layer: int, batch: Batch, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
+    _check(lib().cs_kv_append(ctypes.byref(pool.c), layer, ctypes.byref(batch.c), _ptr(k_new), _ptr(v_new),
+                              _stream(stream)), "cs_kv_append")
+
+
+def cs_paged_attention_workspace_bytes(batch: Batch, Hq: int, Hkv: int, D: int) -> int:
+    return int(lib().cs_paged_attention_workspace_bytes(ctypes.byref(batch.c), Hq, Hkv, D))
+
+
+def cs_paged_attention_mixed(pool: Pool, layer: int, batch: Batch, q: torch.Tensor, out: torch.Tensor,
+                             Hq: int, softmax_scale: float, workspace: Optional[torch.Tensor], stream=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().cs_paged_attention_mixed(ctypes.byref(pool.c), layer, ctypes.byref(batch.c), _ptr(q), _ptr(out),
+                                          Hq, softmax_scale, _ptr(workspace), wb, _stream(stream)),
+           "cs_paged_attention_mixed")
+
+
+def cs_kv_ckpt_gather(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,
+                      staging: torch.Tensor, stream=None):
+    _check(lib().cs_kv_ckpt_gather(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids),
+                                   page_ids.numel(), _ptr(staging), staging.numel() * staging.element_size(),
+                                   _stream(stream)), "cs_kv_ckpt_gather")
+
+
+def cs_kv_ckpt_restore(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,
+                       staging: torch.Tensor, stream=None):
+    _check(lib().cs_kv_ckpt_restore(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids),
+                                    page_ids.numel(), _ptr(staging), staging.numel() * staging.element_size(),
+                                    _stream(stream)), "cs_kv_ckpt_restore")
+
+
+def cs_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() >= nbytes
+    _check(lib().cs_debug_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "cs_debug_copy")
+
+
+def cs_set_decode_split_tokens(tokens: int):
+    lib().cs_set_decode_split_tokens(int(tokens))
+
+
+def workspace_for(batch: Batch, Hq: int, Hkv: int, D: int, device="cuda") -> Optional[torch.Tensor]:
+    n = cs_paged_attention_workspace_bytes(batch, Hq, Hkv, D)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)

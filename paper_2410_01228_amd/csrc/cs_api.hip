@@ -1,0 +1,201 @@
+// C ABI entry points: host-side validation and launch planning.  See include/conserve_kv.h
+// for the contract of each call.
+#include "cs_common.h"
+#include <atomic>
+#include <string.h>
+#include <stdio.h>
+
+namespace cs {
+
+static thread_local char g_hip_error[256] = "";
+static std::atomic<int32_t> g_forced_split{0};
+
+int hip_failed(hipError_t e, const char* what) {
+    snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
+    return CS_ERR_HIP;
+}
+
+static bool shape_supported(int32_t Hkv, int32_t D) {
+    return Hkv >= 1 && (D == 64 || D == 128);
+}
+
+int validate_pool(const cs_kv_pool* p) {
+    if (!p || !p->base) return CS_ERR_INVALID_ARG;
+    if (p->num_layers <= 0 || p->num_pages <= 0 || p->num_kv_heads <= 0 || p->head_dim <= 0)
+        return CS_ERR_INVALID_ARG;
+    if (p->page_size != kPage || !shape_supported(p->num_kv_heads, p->head_dim)) return CS_ERR_UNSUPPORTED;
+    const int64_t page_elems = 2ll * p->num_kv_heads * kPage * p->head_dim;
+    if (p->page_stride < page_elems || (p->page_stride & 7) != 0) return CS_ERR_INVALID_ARG;
+    if (p->layer_stride < (int64_t)p->num_pages * p->page_stride || (p->layer_stride & 7) != 0)
+        return CS_ERR_INVALID_ARG;
+    if (((uintptr_t)p->base & 15) != 0) return CS_ERR_INVALID_ARG;
+    return CS_OK;
+}
+
+int validate_batch(const cs_kv_pool* pool, const cs_batch* b) {
+    (void)pool;
+    if (!b) return CS_ERR_INVALID_ARG;
+    if (b->num_seqs < 0 || b->num_tokens < 0 || b->num_seqs > 65535) return CS_ERR_INVALID_ARG;
+    if (b->num_seqs == 0) return b->num_tokens == 0 ? CS_OK : CS_ERR_INVALID_ARG;
+    if (!b->block_tables || !b->ctx_lens || !b->cu_q_lens || !b->h_ctx_lens || !b->h_cu_q_lens)
+        return CS_ERR_INVALID_ARG;
+    if (b->max_blocks_per_seq <= 0) return CS_ERR_INVALID_ARG;
+    if (b->h_cu_q_lens[0] != 0 || b->h_cu_q_lens[b->num_seqs] != b->num_tokens) return CS_ERR_INVALID_ARG;
+    for (int32_t s = 0; s < b->num_seqs; ++s) {
+        const int64_t ql = (int64_t)b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+        const int64_t c = b->h_ctx_lens[s];
+        if (ql < 0 || c < 0) return CS_ERR_INVALID_ARG;
+        if (c + ql > (int64_t)b->max_blocks_per_seq * kPage) return CS_ERR_INVALID_ARG;
+    }
+    return CS_OK;
+}
+
+DecodePlan plan_decode(const cs_batch* b, int32_t Hkv) {
+    DecodePlan p = {};
+    for (int32_t s = 0; s < b->num_seqs; ++s) {
+        const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+        if (ql == 1) {
+            const int32_t n = b->h_ctx_lens[s] + 1;
+            ++p.num_decode;
+            p.decode_keys += n;
+            if (n > p.max_decode_keys) p.max_decode_keys = n;
+        } else if (ql > 1) {
+            ++p.num_prefill;
+        }
+    }
+    p.split_tokens = 256;
+    p.max_splits = 1;
+    if (p.num_decode == 0) return p;
+    int32_t split = g_forced_split.load();
+    if (split <= 0) {
+        // largest power-of-two split (>= 256 keys) that still leaves ~16 workgroups per CU
+        split = 256;
+        const int64_t work = p.decode_keys * Hkv;
+        while (split < 16384 && work / (split * 2) >= 4096) split *= 2;
+    }
+    p.split_tokens = split;
+    p.max_splits = (p.max_decode_keys + split - 1) / split;
+    return p;
+}
+
+size_t decode_workspace_bytes(const DecodePlan& p, int32_t S, int32_t Hq, int32_t D) {
+    if (p.num_decode == 0 || p.max_splits <= 1) return 0;
+    return (size_t)S * p.max_splits * Hq * (D + 2) * sizeof(float);
+}
+
+}  // namespace cs
+
+using namespace cs;
+
+extern "C" {
+
+size_t cs_page_bytes(int32_t Hkv, int32_t D) {
+    if (!shape_supported(Hkv, D)) return 0;
+    return (size_t)2 * Hkv * kPage * D * 2;
+}
+
+int cs_kv_append(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                 const void* k_new, const void* v_new, void* stream) {
+    int rc = validate_pool(pool);
+    if (rc) return rc;
+    if (layer < 0 || layer >= pool->num_layers) return CS_ERR_INVALID_ARG;
+    rc = validate_batch(pool, batch);
+    if (rc) return rc;
+    if (batch->num_tokens == 0) return CS_OK;
+    if (!k_new || !v_new || ((uintptr_t)k_new & 15) || ((uintptr_t)v_new & 15)) return CS_ERR_INVALID_ARG;
+    return launch_append(*pool, layer, *batch, k_new, v_new, (hipStream_t)stream);
+}
+
+static int attention_shape_ok(int32_t Hq, int32_t Hkv, int32_t D) {
+    if (Hq <= 0 || Hkv <= 0) return CS_ERR_INVALID_ARG;
+    if (Hq % Hkv != 0) return CS_ERR_INVALID_ARG;
+    if (!shape_supported(Hkv, D) || Hq / Hkv > kMaxGroup) return CS_ERR_UNSUPPORTED;
+    return CS_OK;
+}
+
+size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return 0;
+    if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return 0;
+    const DecodePlan p = plan_decode(batch, Hkv);
+    return decode_workspace_bytes(p, batch->num_seqs, Hq, D);
+}
+
+int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                             const void* q, void* out, int32_t Hq, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = validate_pool(pool);
+    if (rc) return rc;
+    if (layer < 0 || layer >= pool->num_layers) return CS_ERR_INVALID_ARG;
+    rc = attention_shape_ok(Hq, pool->num_kv_heads, pool->head_dim);
+    if (rc) return rc;
+    rc = validate_batch(pool, batch);
+    if (rc) return rc;
+    if (batch->num_tokens == 0) return CS_OK;
+    if (!q || !out || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return CS_ERR_INVALID_ARG;
+    if (!(softmax_scale == softmax_scale)) return CS_ERR_INVALID_ARG;
+    const DecodePlan plan = plan_decode(batch, pool->num_kv_heads);
+    const size_t need = decode_workspace_bytes(plan, batch->num_seqs, Hq, pool->head_dim);
+    if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
+    if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
+    hipStream_t st = (hipStream_t)stream;
+    if (plan.num_prefill > 0) {
+        rc = launch_prefill(*pool, layer, *batch, q, out, Hq, softmax_scale, st);
+        if (rc) return rc;
+    }
+    return launch_decode(*pool, layer, *batch, plan, q, out, Hq, softmax_scale, workspace, st);
+}
+
+static int ckpt_common(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                       const void* staging, size_t staging_bytes) {
+    int rc = validate_pool(pool);
+    if (rc) return rc;
+    if (l0 < 0 || l1 < l0 || l1 > pool->num_layers || n < 0) return CS_ERR_INVALID_ARG;
+    if (n == 0 || l1 == l0) return CS_OK;
+    if (!ids || !staging || ((uintptr_t)staging & 15)) return CS_ERR_INVALID_ARG;
+    const size_t need = (size_t)(l1 - l0) * n * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    if (staging_bytes < need) return CS_ERR_STAGING_TOO_SMALL;
+    if ((int64_t)n * 4 > 2147483647ll || l1 - l0 > 65535) return CS_ERR_INVALID_ARG;
+    return 1;   // proceed
+}
+
+int cs_kv_ckpt_gather(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                      void* staging, size_t staging_bytes, void* stream) {
+    const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    return launch_page_copy(*pool, l0, l1, ids, n, staging, true, (hipStream_t)stream);
+}
+
+int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                       const void* staging, size_t staging_bytes, void* stream) {
+    const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    return launch_page_copy(*pool, l0, l1, ids, n, (void*)staging, false, (hipStream_t)stream);
+}
+
+int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (bytes == 0) return CS_OK;
+    if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return CS_ERR_INVALID_ARG;
+    if (bytes > (size_t)1 << 44) return CS_ERR_INVALID_ARG;
+    return launch_plain_copy(dst, src, bytes, (hipStream_t)stream);
+}
+
+void cs_set_decode_split_tokens(int32_t tokens) {
+    if (tokens < 0) tokens = 0;
+    g_forced_split.store((tokens + 15) / 16 * 16);
+}
+
+const char* cs_status_string(int status) {
+    switch (status) {
+        case CS_OK: return "ok";
+        case CS_ERR_INVALID_ARG: return "invalid argument";
+        case CS_ERR_UNSUPPORTED: return "unsupported shape";
+        case CS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case CS_ERR_STAGING_TOO_SMALL: return "staging buffer too small";
+        case CS_ERR_HIP: return "HIP error";
+        default: return "unknown status";
+    }
+}
+
+const char* cs_last_hip_error(void) { return g_hip_error; }
+
+}  // extern "C"

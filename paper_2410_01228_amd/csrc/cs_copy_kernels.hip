@@ -1,0 +1,165 @@
+// Copy kernels: KV append into pages, checkpoint gather / restore of whole pages, and a
+// plain copy used as the bandwidth ceiling.  All are HBM-bound streams of 16-byte lanes.
+#include "cs_common.h"
+
+namespace cs {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// ------------------------------------------------------------------------------------
+// Whole-page copies (paper Sec. 5: gather scattered pages into one contiguous buffer;
+// Sec. 4.4: bring them back on resume).  One (layer, page) is contiguous in the pool, so
+// both directions are straight 16-byte-per-lane streams.  A workgroup of 256 lanes moves
+// kChunk bytes: all loads are issued before the first store so each lane keeps
+// kChunk / 4096 independent 16-byte requests in flight.
+// ------------------------------------------------------------------------------------
+constexpr int kCopyThreads = 256;
+constexpr int kCopyUnroll = 4;                                   // 16 KiB per workgroup
+constexpr int kChunkBytes = kCopyThreads * 16 * kCopyUnroll;
+
+template <bool kToStaging>
+__global__ __launch_bounds__(kCopyThreads) void page_copy_kernel(
+    char* __restrict__ pool_base, int64_t layer_stride_b, int64_t page_stride_b,
+    int32_t num_pages, int32_t layer_begin, const int32_t* __restrict__ ids, int32_t n,
+    char* __restrict__ staging, int32_t page_bytes, int32_t chunks_per_page)
+{
+    // grid.x = n * chunks_per_page (page-major), grid.y = layers
+    const int32_t i = blockIdx.x / chunks_per_page;
+    const int32_t c = blockIdx.x - i * chunks_per_page;
+    const int32_t l = blockIdx.y;
+    const int32_t id = ids[i];
+    if (id < 0 || id >= num_pages) return;                       // never touch a bad page id
+    char* p = pool_base + (int64_t)(layer_begin + l) * layer_stride_b + (int64_t)id * page_stride_b;
+    char* s = staging + ((int64_t)l * n + i) * (int64_t)page_bytes;
+    const char* src = kToStaging ? p : s;
+    char* dst = kToStaging ? s : p;
+    const int32_t off0 = c * kChunkBytes + threadIdx.x * 16;
+    u32x4 r[kCopyUnroll];
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u) {
+        const int32_t off = off0 + u * kCopyThreads * 16;
+        if (off < page_bytes) r[u] = __builtin_nontemporal_load((const u32x4*)(src + off));
+    }
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u) {
+        const int32_t off = off0 + u * kCopyThreads * 16;
+        if (off < page_bytes) __builtin_nontemporal_store(r[u], (u32x4*)(dst + off));
+    }
+}
+
+int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_end,
+                     const int32_t* ids, int32_t n, void* staging, bool to_staging, hipStream_t st)
+{
+    const int32_t layers = layer_end - layer_begin;
+    if (n == 0 || layers == 0) return CS_OK;
+    const int32_t page_bytes = (int32_t)cs_page_bytes(pool.num_kv_heads, pool.head_dim);
+    const int32_t cpp = (page_bytes + kChunkBytes - 1) / kChunkBytes;
+    dim3 grid((uint32_t)n * cpp, (uint32_t)layers);
+    if (to_staging)
+        hipLaunchKernelGGL(page_copy_kernel<true>, grid, dim3(kCopyThreads), 0, st,
+                           (char*)pool.base, pool.layer_stride * 2, pool.page_stride * 2, pool.num_pages,
+                           layer_begin, ids, n, (char*)staging, page_bytes, cpp);
+    else
+        hipLaunchKernelGGL(page_copy_kernel<false>, grid, dim3(kCopyThreads), 0, st,
+                           (char*)pool.base, pool.layer_stride * 2, pool.page_stride * 2, pool.num_pages,
+                           layer_begin, ids, n, (char*)staging, page_bytes, cpp);
+    return check_launch("page_copy_kernel");
+}
+
+// ------------------------------------------------------------------------------------
+// Plain copy: the same inner loop without the page indirection.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(
+    char* __restrict__ dst, const char* __restrict__ src, int64_t bytes)
+{
+    const int64_t off0 = (int64_t)blockIdx.x * kChunkBytes + threadIdx.x * 16;
+    u32x4 r[kCopyUnroll];
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u) {
+        const int64_t off = off0 + u * kCopyThreads * 16;
+        if (off < bytes) r[u] = __builtin_nontemporal_load((const u32x4*)(src + off));
+    }
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u) {
+        const int64_t off = off0 + u * kCopyThreads * 16;
+        if (off < bytes) __builtin_nontemporal_store(r[u], (u32x4*)(dst + off));
+    }
+}
+
+int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return CS_OK;
+    const uint64_t blocks = (bytes + kChunkBytes - 1) / kChunkBytes;
+    hipLaunchKernelGGL(plain_copy_kernel, dim3((uint32_t)blocks), dim3(kCopyThreads), 0, st,
+                       (char*)dst, (const char*)src, (int64_t)bytes);
+    return check_launch("plain_copy_kernel");
+}
+
+// ------------------------------------------------------------------------------------
+// KV append (the cache is append-only: paper Sec. 1, 4.4).  One lane per 16-byte unit
+// (8 features) of a new K row and of a new V row.  The K unit is stored as it is (the K
+// block keeps 8 consecutive features of a token together); the V unit is scattered as 8
+// two-byte stores because the V block keeps 4 consecutive TOKENS of one feature together.
+// A workgroup covers kTokPerBlock tokens; each token finds its sequence by bisection of
+// the prefix sums.
+// ------------------------------------------------------------------------------------
+constexpr int kAppendThreads = 256;
+
+__global__ __launch_bounds__(kAppendThreads) void append_kernel(
+    uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t D, int32_t S, int32_t T,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
+{
+    const int32_t units_per_tok = Hkv * (D >> 3);                 // 16-byte units per K (or V) row
+    const int64_t gid = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
+    const int32_t t = (int32_t)(gid / units_per_tok);
+    if (t >= T) return;
+    const int32_t u = (int32_t)(gid - (int64_t)t * units_per_tok);
+    const int32_t h = u / (D >> 3);
+    const int32_t dblk = u - h * (D >> 3);
+    // sequence of token t: largest s with cu_q_lens[s] <= t
+    int32_t lo = 0, hi = S;                                       // invariant: cu[lo] <= t < cu[hi]
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (cu_q_lens[mid] <= t) lo = mid; else hi = mid;
+    }
+    const int32_t s = lo;
+    const int32_t pos = ctx_lens[s] + (t - cu_q_lens[s]);
+    const int32_t blk = pos >> 4;
+    if (pos < 0 || blk >= max_blocks) return;
+    const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
+    if (page < 0 || page >= num_pages) return;
+    const int32_t slot = pos & 15;
+    const int32_t block_elems = kPage * D;
+    uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
+    uint16_t* vblk = kblk + (int64_t)Hkv * block_elems;
+    const int64_t src = ((int64_t)t * Hkv + h) * D + dblk * 8;
+    const u32x4 kv = *(const u32x4*)(k_new + src);
+    *(u32x4*)(kblk + (dblk * 16 + slot) * 8) = kv;
+    const u32x4 vv = *(const u32x4*)(v_new + src);
+    // feature d = dblk*8 + e  ->  (((d/16)*4 + slot/4)*16 + d%16)*4 + slot%4
+    const int32_t vbase = (((dblk >> 1) * 4 + (slot >> 2)) * 16 + (dblk & 1) * 8) * 4 + (slot & 3);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const uint32_t w = vv[e >> 1];
+        vblk[vbase + e * 4] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
+    }
+}
+
+int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
+                  const void* k_new, const void* v_new, hipStream_t st)
+{
+    if (b.num_tokens == 0) return CS_OK;
+    const int64_t units = (int64_t)b.num_tokens * pool.num_kv_heads * (pool.head_dim / 8);
+    const uint32_t blocks = (uint32_t)((units + kAppendThreads - 1) / kAppendThreads);
+    hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(kAppendThreads), 0, st,
+                       (uint16_t*)pool.base + (int64_t)layer * pool.layer_stride, pool.page_stride,
+                       pool.num_pages, pool.num_kv_heads, pool.head_dim, b.num_seqs, b.num_tokens,
+                       b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
+                       (const uint16_t*)k_new, (const uint16_t*)v_new);
+    return check_launch("append_kernel");
+}
+
+}  // namespace cs

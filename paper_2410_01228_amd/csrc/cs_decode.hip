@@ -1,0 +1,278 @@
+// Decode path of the mixed-batch paged attention: one new token per sequence attends its
+// whole cached context (paper Sec. 4.2, memory-access term: the KV cache is streamed from
+// HBM once).  Split-KV scheme: a workgroup takes one (sequence, kv head, key split), its
+// four wavefronts stream the split's pages straight from HBM into MFMA operand registers
+// (the page format IS the operand layout, so there is no LDS staging and no shuffle),
+// keep an online softmax per query head in fp32, and leave one partial (max, sum,
+// unnormalised output) per split; a second kernel merges the splits.
+//
+// Tile algebra per 16-token page and kv head (G = query heads sharing it, padded to 16):
+//   S^T[token][head] = K[token][:] . Q[head][:]      v_mfma_f32_16x16x32_bf16, D/32 steps
+//   O^T[d][head]    += V^T[d][token] . P^T[token][head]   v_mfma_f32_16x16x16_bf16, D/16 tiles
+// The C layout of S^T (lane = head + 16*(token/4), register = token%4) is exactly the B
+// layout the second product wants, so P never leaves its registers.
+#include "cs_common.h"
+
+namespace cs {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kDecodeWaves = 4;
+constexpr int kDecodeThreads = kDecodeWaves * 64;
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+    // round-to-nearest-even conversion of two floats into one dword of bf16
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 v = { (__bf16)lo, (__bf16)hi };
+    return __builtin_bit_cast(uint32_t, v);
+}
+
+__device__ __forceinline__ float xor_max(float v, int mask) {
+    return fmaxf(v, __shfl_xor(v, mask, 64));
+}
+
+template <int D>
+struct PageRegs {
+    u32x4 k[D / 32];     // K block: unit (kk*64 + lane)
+    u32x2 v[D / 16];     // V block: unit (dt*64 + lane)
+};
+
+template <int D>
+__device__ __forceinline__ void load_page(PageRegs<D>& r, const uint16_t* __restrict__ layer_base,
+                                          int64_t page_stride, int32_t page, int32_t g, int32_t Hkv, int lane)
+{
+    const uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)g * (kPage * D);
+    const uint16_t* vblk = kblk + (int64_t)Hkv * (kPage * D);
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk)
+        r.k[kk] = __builtin_nontemporal_load((const u32x4*)kblk + kk * 64 + lane);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+        r.v[dt] = __builtin_nontemporal_load((const u32x2*)vblk + dt * 64 + lane);
+}
+
+// One wavefront's running state.
+template <int D>
+struct WaveState {
+    f32x4 o[D / 16];     // O^T tiles: row d = dt*16 + 4*(lane/16) + i, column head = lane%16
+    float m;             // running max (log2 domain) of column lane%16
+    float l;             // this lane's share of the running sum
+};
+
+template <int D>
+__device__ __forceinline__ void process_page(WaveState<D>& st, const PageRegs<D>& r, const bf16x8* qb,
+                                             float scale_log2e, int32_t tok0, int32_t n_keys, int lane)
+{
+    f32x4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk)
+        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[kk]), qb[kk], s, 0, 0, 0);
+    const int32_t row0 = tok0 + (lane >> 4) * 4;      // first of this lane's 4 tokens
+    const bool tail = tok0 + kPage > n_keys;           // wave-uniform
+    float x[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[i] = s[i] * scale_log2e;
+        if (tail && row0 + i >= n_keys) x[i] = -INFINITY;
+    }
+    float mx = fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3]));
+    mx = xor_max(mx, 16);
+    mx = xor_max(mx, 32);
+    const float m_new = fmaxf(st.m, mx);               // finite: token tok0 is always valid
+    if (__any(m_new > st.m)) {
+        const float alpha = exp2f(st.m - m_new);       // 0 on the first page (m = -inf)
+        st.l *= alpha;
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) st.o[dt] *= alpha;
+        st.m = m_new;
+    }
+    float p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - st.m);
+    u32x2 pb = { pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]) };
+    // the sum uses the same bf16-rounded weights that multiply V
+    st.l += (__builtin_bit_cast(float, pb[0] << 16) + __builtin_bit_cast(float, pb[0] & 0xffff0000u))
+          + (__builtin_bit_cast(float, pb[1] << 16) + __builtin_bit_cast(float, pb[1] & 0xffff0000u));
+    const s16x4 pbv = __builtin_bit_cast(s16x4, pb);
+    if (tail) {
+        // slots past the sequence end hold stale bits (possibly NaN): zero them so 0 * x stays 0
+        const int32_t valid = n_keys - row0;           // tokens of this lane's group that exist
+        const uint32_t m0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+        const uint32_t m1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+            u32x2 v = r.v[dt];
+            v[0] &= m0; v[1] &= m1;
+            st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, v), pbv, st.o[dt], 0, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt)
+            st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r.v[dt]), pbv, st.o[dt], 0, 0, 0);
+    }
+}
+
+// grid = (max_splits, Hkv, S); block = 4 wavefronts.
+template <int D>
+__global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
+    const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t G,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ q, uint16_t* __restrict__ out,
+    float scale_log2e, int32_t split_tokens, int32_t max_splits,
+    float* __restrict__ part_o, float* __restrict__ part_ml)
+{
+    const int32_t s = blockIdx.z, g = blockIdx.y, split = blockIdx.x;
+    const int32_t t = cu_q_lens[s];
+    if (cu_q_lens[s + 1] - t != 1) return;                       // not a decode sequence
+    const int32_t n_keys = ctx_lens[s] + 1;
+    const int32_t key_begin = split * split_tokens;
+    if (key_begin >= n_keys) return;
+    const int32_t key_end = min(n_keys, key_begin + split_tokens);
+    const int32_t page_begin = key_begin >> 4;
+    const int32_t page_end = min((key_end + kPage - 1) >> 4, max_blocks);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int32_t* table = block_tables + (int64_t)s * max_blocks;
+    const int32_t Hq = Hkv * G;
+
+    // Q as the B operand of S^T = K.Q^T: lane (head = lane%16, k-group = lane/16) holds
+    // features kk*32 + (lane/16)*8 .. +8 of head g*G + lane%16; heads >= G are zero rows.
+    bf16x8 qb[D / 32];
+    {
+        const int head = lane & 15;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) {
+            u32x4 v = zero;
+            if (head < G)
+                v = *(const u32x4*)(q + ((int64_t)t * Hq + g * G + head) * D + kk * 32 + (lane >> 4) * 8);
+            qb[kk] = __builtin_bit_cast(bf16x8, v);
+        }
+    }
+
+    WaveState<D> st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) st.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // wave w streams pages page_begin + w, + w + 4, ...; the next page's loads are in
+    // flight while the current page is multiplied
+    PageRegs<D> cur, nxt;
+    int32_t pg = page_begin + wave;
+    int32_t id_cur = pg < page_end ? table[pg] : -1;
+    int32_t id_nxt = pg + kDecodeWaves < page_end ? table[pg + kDecodeWaves] : -1;
+    if (pg < page_end && id_cur >= 0 && id_cur < num_pages)
+        load_page<D>(cur, layer_base, page_stride, id_cur, g, Hkv, lane);
+    while (pg < page_end) {
+        const int32_t pg_n = pg + kDecodeWaves;
+        const bool have_n = pg_n < page_end;
+        const int32_t id_n2 = pg_n + kDecodeWaves < page_end ? table[pg_n + kDecodeWaves] : -1;
+        const bool ok_n = have_n && id_nxt >= 0 && id_nxt < num_pages;
+        if (ok_n) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
+        if (id_cur >= 0 && id_cur < num_pages)
+            process_page<D>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
+        cur = nxt;
+        id_cur = id_nxt;
+        id_nxt = id_n2;
+        pg = pg_n;
+    }
+    st.l += __shfl_xor(st.l, 16, 64);
+    st.l += __shfl_xor(st.l, 32, 64);
+
+    // merge the four wavefronts through LDS
+    __shared__ float sh_o[kDecodeWaves][kMaxGroup][D];
+    __shared__ float sh_m[kDecodeWaves][kMaxGroup];
+    __shared__ float sh_l[kDecodeWaves][kMaxGroup];
+    {
+        const int head = lane & 15;
+        if (head < G) {
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    sh_o[wave][head][dt * 16 + (lane >> 4) * 4 + i] = st.o[dt][i];
+            if (lane < 16) { sh_m[wave][head] = st.m; sh_l[wave][head] = st.l; }
+        }
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * D; idx += kDecodeThreads) {
+        const int head = idx / D, d = idx - head * D;
+        float M = sh_m[0][head];
+#pragma unroll
+        for (int w = 1; w < kDecodeWaves; ++w) M = fmaxf(M, sh_m[w][head]);
+        float L = 0.f, O = 0.f;
+#pragma unroll
+        for (int w = 0; w < kDecodeWaves; ++w) {
+            const float f = exp2f(sh_m[w][head] - M);            // 0 for a wavefront without pages
+            L += sh_l[w][head] * f;
+            O += sh_o[w][head][d] * f;
+        }
+        const int32_t hq = g * G + head;
+        if (max_splits == 1) {
+            const float r = O / L;
+            out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(pack_bf16(r, 0.f) & 0xffffu);
+        } else {
+            const int64_t slot = ((int64_t)s * max_splits + split) * Hq + hq;
+            part_o[slot * D + d] = O;
+            if (d == 0) { part_ml[slot * 2] = M; part_ml[slot * 2 + 1] = L; }
+        }
+    }
+}
+
+// Merge of the split partials: grid = (Hq, S), block = D lanes.
+template <int D>
+__global__ __launch_bounds__(D) void decode_merge_kernel(
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    int32_t Hq, int32_t split_tokens, int32_t max_splits,
+    const float* __restrict__ part_o, const float* __restrict__ part_ml, uint16_t* __restrict__ out)
+{
+    const int32_t s = blockIdx.y, hq = blockIdx.x, d = threadIdx.x;
+    const int32_t t = cu_q_lens[s];
+    if (cu_q_lens[s + 1] - t != 1) return;
+    const int32_t n_keys = ctx_lens[s] + 1;
+    const int32_t n_splits = min(max_splits, (n_keys + split_tokens - 1) / split_tokens);
+    const int64_t slot0 = (int64_t)s * max_splits * Hq + hq;
+    float M = -INFINITY;
+    for (int i = 0; i < n_splits; ++i) M = fmaxf(M, part_ml[(slot0 + (int64_t)i * Hq) * 2]);
+    float L = 0.f, O = 0.f;
+    for (int i = 0; i < n_splits; ++i) {
+        const int64_t slot = slot0 + (int64_t)i * Hq;
+        const float f = exp2f(part_ml[slot * 2] - M);
+        L += part_ml[slot * 2 + 1] * f;
+        O += part_o[slot * D + d] * f;
+    }
+    out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(pack_bf16(O / L, 0.f) & 0xffffu);
+}
+
+int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
+                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
+{
+    if (plan.num_decode == 0) return CS_OK;
+    const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
+    const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
+    const float scale_log2e = scale * 1.4426950408889634f;
+    float* part_o = (float*)workspace;
+    float* part_ml = part_o + (int64_t)b.num_seqs * plan.max_splits * Hq * D;
+    dim3 grid((uint32_t)plan.max_splits, (uint32_t)Hkv, (uint32_t)b.num_seqs);
+    dim3 mgrid((uint32_t)Hq, (uint32_t)b.num_seqs);
+#define CS_LAUNCH_DECODE(DD)                                                                          \
+    hipLaunchKernelGGL(decode_split_kernel<DD>, grid, dim3(kDecodeThreads), 0, st, layer_base,        \
+                       pool.page_stride, pool.num_pages, Hkv, G, b.block_tables, b.max_blocks_per_seq, \
+                       b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,      \
+                       plan.split_tokens, plan.max_splits, part_o, part_ml);                          \
+    if (plan.max_splits > 1)                                                                          \
+        hipLaunchKernelGGL(decode_merge_kernel<DD>, mgrid, dim3(DD), 0, st, b.ctx_lens, b.cu_q_lens,  \
+                           Hq, plan.split_tokens, plan.max_splits, part_o, part_ml, (uint16_t*)out);
+    if (D == 128) { CS_LAUNCH_DECODE(128) } else { CS_LAUNCH_DECODE(64) }
+#undef CS_LAUNCH_DECODE
+    return check_launch("decode kernels");
+}
+
+}  // namespace cs
