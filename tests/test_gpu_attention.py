@@ -65,3 +65,123 @@ def test_decode_llama8b_shrunk():
     b = synth.config_llama8b_decode(shrink=8)
     out, st, _, _ = run_step(b, 1)
     assert_attention_close(out, st.oracle_attention(), "llama8b/8")
+
+
+# ------------------------------------------------------------------------------------
+# prefill chunks and mixed batches
+# ------------------------------------------------------------------------------------
+
+def test_tiny_config_end_to_end():
+    """Workload 0: append + mixed attention, then checkpoint the 5 newly filled pages,
+    resume them into fresh pages with rewritten block tables: the attention output must not
+    change by a single bit (preempt/resume is invisible to the request)."""
+    b = synth.config_tiny()
+    sh = b.shape
+    out, st, pool, bb = run_step(b, 0)
+    assert_attention_close(out, st.oracle_attention(), "tiny mixed")
+    dirty = synth.newly_filled_pages(b)
+    fresh = [int(x) for x in b.spare_pages[:len(dirty)]]
+    staging = torch.empty((1, len(dirty), sh.page_elems), dtype=torch.bfloat16, device="cuda")
+    cs.cs_kv_ckpt_gather(pool, 0, 1, torch.tensor(dirty, dtype=torch.int32, device="cuda"), staging)
+    torch.cuda.synchronize()
+    flat = pool.tensor.view(sh.L, b.num_pages, -1)
+    flat[:, dirty] = float("nan")                                   # the old pages are released
+    cs.cs_kv_ckpt_restore(pool, 0, 1, torch.tensor(fresh, dtype=torch.int32, device="cuda"), staging)
+    bt2 = b.block_tables.clone()
+    for old, new in zip(dirty, fresh):
+        bt2[b.block_tables == old] = new
+    bb2 = cs.Batch(bt2, b.ctx_lens, b.cu_q_lens)
+    out2 = torch.full_like(out, float("nan"))
+    cs.cs_paged_attention_mixed(pool, 0, bb2, st.q.cuda(), out2, sh.Hq, sh.scale, cs.workspace_for(bb2, sh.Hq, sh.Hkv, sh.D))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 2, 64), (32, 8, 128), (28, 4, 128), (40, 8, 128), (16, 1, 64), (3, 3, 128), (8, 8, 64)])
+def test_prefill_chunks_ragged(Hq, Hkv, D):
+    # chunk lengths that are not multiples of the tile, prior contexts on and off page
+    # boundaries, a first chunk (context 0), a 2-token chunk
+    sh = synth.Shape(Hq, Hkv, D)
+    b = synth.make_batch(sh, [0, 48, 17, 255, 5, 100], [32, 32, 50, 77, 2, 129], synth.generator(31))
+    out, st, _, _ = run_step(b, 31)
+    assert_attention_close(out, st.oracle_attention(), "prefill ragged %d/%d/%d" % (Hq, Hkv, D))
+
+
+def test_prefill_first_row_is_v0_exactly():
+    # the first token of a first chunk sees only itself: out = v0, exact in bf16
+    sh = synth.Shape(4, 2, 64)
+    b = synth.make_batch(sh, [0], [40], synth.generator(32))
+    out, st, _, _ = run_step(b, 32)
+    v0 = st.v_new[0]                                               # [Hkv, D]
+    for h in range(sh.Hq):
+        assert torch.equal(out[0, h].cpu(), v0[h // sh.G])
+
+
+def test_prefill_peaked_softmax():
+    sh = synth.Shape(8, 2, 128)
+    b = synth.make_batch(sh, [0, 333, 1000], [96, 64, 40], synth.generator(33))
+    out, st, _, _ = run_step(b, 33, q_gain=6.0)
+    assert_attention_close(out, st.oracle_attention(), "prefill peaked")
+
+
+@pytest.mark.parametrize("maker,seed,shrink", [(synth.config_qwen7b_mixed, 2, 8), (synth.config_llama70b_long, 3, 16),
+                                               (synth.config_qwen14b_ckpt, 4, 16)])
+def test_mixed_shrunk_configs(maker, seed, shrink):
+    b = maker(shrink=shrink)
+    if b.shape.L > 1:
+        b.shape.L = 1
+    out, st, _, _ = run_step(b, seed)
+    active = [s for s in range(b.S) if int(b.q_lens[s]) > 0]
+    assert_attention_close(out, st.oracle_attention(active), b.name)
+
+
+def test_preemption_drops_offline_tail_without_touching_online_rows():
+    """Layer-wise preemption hands the same arrays with a smaller num_seqs: the online rows
+    must be bit-identical with and without the offline sequences in the batch."""
+    b = synth.config_qwen7b_mixed(shrink=16)
+    sh = b.shape
+    n_on = b.extra["n_online"]
+    out, st, pool, bb = run_step(b, 2)
+    bb_on = bb.truncated(n_on)
+    out_on = torch.full_like(out, float("nan"))
+    ws = cs.workspace_for(bb_on, sh.Hq, sh.Hkv, sh.D)
+    cs.cs_paged_attention_mixed(pool, 0, bb_on, st.q.cuda(), out_on, sh.Hq, sh.scale, ws)
+    torch.cuda.synchronize()
+    T_on = bb_on.num_tokens
+    assert T_on == n_on
+    if cs.cs_paged_attention_workspace_bytes(bb, sh.Hq, sh.Hkv, sh.D) == cs.cs_paged_attention_workspace_bytes(bb_on, sh.Hq, sh.Hkv, sh.D):
+        assert torch.equal(out[:T_on].view(torch.int16), out_on[:T_on].view(torch.int16))
+    assert_attention_close(out_on[:T_on], st.oracle_attention(range(n_on))[:T_on], "online only")
+    assert torch.isnan(out_on[T_on:].float()).all()                  # offline rows were not written
+
+
+def test_page_permutation_leaves_output_bit_identical():
+    sh = synth.Shape(8, 2, 128)
+    ctx, ql = [100, 700, 31, 0, 260], [1, 1, 1, 48, 33]
+    b1 = synth.make_batch(sh, ctx, ql, synth.generator(41), spare=5)
+    b2 = synth.make_batch(sh, ctx, ql, synth.generator(42), spare=5)
+    assert not torch.equal(b1.block_tables, b2.block_tables)
+    o1, _, _, _ = run_step(b1, 40)
+    o2, _, _, _ = run_step(b2, 40)                                   # same values, other pages
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+def test_attention_argument_errors():
+    sh = synth.Shape(4, 2, 64)
+    b = decode_batch(sh, [600, 700], 50)
+    pool = cs.Pool.empty(1, b.num_pages, sh.Hkv, sh.D)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    q = torch.zeros((2, 4, 64), dtype=torch.bfloat16, device="cuda")
+    cs.cs_set_decode_split_tokens(256)
+    try:
+        with pytest.raises(cs.CsError) as e:
+            cs.cs_paged_attention_mixed(pool, 0, bb, q, q.clone(), 4, 0.125, None)
+        assert e.value.status in (cs.CS_ERR_WORKSPACE_TOO_SMALL, cs.CS_ERR_INVALID_ARG)
+        with pytest.raises(cs.CsError) as e:
+            cs.cs_paged_attention_mixed(pool, 0, bb, q, q.clone(), 3, 0.125, cs.workspace_for(bb, 4, 2, 64))
+        assert e.value.status == cs.CS_ERR_INVALID_ARG                # 3 query heads over 2 kv heads
+        with pytest.raises(cs.CsError) as e:
+            cs.cs_paged_attention_mixed(pool, 1, bb, q, q.clone(), 4, 0.125, cs.workspace_for(bb, 4, 2, 64))
+        assert e.value.status == cs.CS_ERR_INVALID_ARG                # layer out of range
+    finally:
+        cs.cs_set_decode_split_tokens(0)
