@@ -1,0 +1,269 @@
+#!/usr/bin/env python3
+"""Benchmark of the co-serving attention / KV hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--detail]
+
+One "step" is one pass of the per-layer hot path over one synthetic batch: cs_kv_append of
+the step's new K/V followed by cs_paged_attention_mixed (for the checkpoint workload also
+cs_kv_ckpt_gather + cs_kv_ckpt_restore over all layers).  Inputs are resident in HBM before
+the timed region.  Prints ONE JSON line on stdout; everything else goes to stderr.
+
+The default workload is the Llama-3.1-8B decode batch (256 sequences, context uniform in
+[512, 4096], 32/8 heads, head dim 128, 16-token pages) the headline metric is quoted on.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK = 8.0e12            # B/s, MI355X HBM3E
+MFMA_BF16_PEAK = 2.5e15      # FLOP/s, dense bf16
+
+WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b_ckpt"]
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def fill_randn_bf16(t, gen):
+    """N(0,1) rounded to bf16, written in place in chunks (t is a flat bf16 device tensor)."""
+    import torch
+    step = 1 << 27
+    for o in range(0, t.numel(), step):
+        n = min(step, t.numel() - o)
+        t[o:o + n] = torch.randn(n, generator=gen, device=t.device, dtype=torch.float32).to(torch.bfloat16)
+
+
+class Leg:
+    """One timed call of the step with its algorithmic work."""
+
+    def __init__(self, name, fn, bound, work, unit_count=None):
+        self.name, self.fn, self.bound, self.work = name, fn, bound, work
+        self.us = None
+
+    def roofline(self, traffic=None):
+        peak = HBM_PEAK if self.bound == "hbm" else MFMA_BF16_PEAK
+        ach = self.work / (self.us * 1e-6)
+        if self.bound == "hbm":
+            return {"bound": "hbm", "achieved": round(ach / 1e9, 1), "peak": peak / 1e9, "unit": "GB/s",
+                    "frac": round(ach / peak, 4), "traffic": traffic}
+        return {"bound": "mfma", "achieved": round(ach / 1e12, 2), "peak": peak / 1e12, "unit": "TFLOP/s",
+                "frac": round(ach / peak, 4), "traffic": traffic}
+
+
+def attention_work(b, seqs=None):
+    """Algorithmic bytes of the decode sequences and flops of the prefill chunks."""
+    sh = b.shape
+    dec_bytes = pre_flops = pre_bytes = 0
+    for s in (range(b.S) if seqs is None else seqs):
+        c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
+        if ql == 1:
+            n = c + 1
+            dec_bytes += n * 2 * sh.Hkv * sh.D * 2 + 2 * sh.Hq * sh.D * 2 + 4 * ((n + 15) // 16)
+        elif ql > 1:
+            pre_flops += 4 * sh.Hq * sh.D * (ql * c + ql * (ql + 1) // 2)
+            pre_bytes += (c + ql) * 2 * sh.Hkv * sh.D * 2 + 2 * ql * sh.Hq * sh.D * 2
+    return dec_bytes, pre_flops, pre_bytes
+
+
+def build(name):
+    """Allocate and fill the workload on the GPU; returns (batch, legs, dominant leg name, info)."""
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    from paper_2410_01228_amd import synth
+
+    idx = WORKLOADS.index(name)
+    b = synth.CONFIGS[idx]()
+    sh = b.shape
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + idx)
+    pool = cs.Pool.empty(sh.L, b.num_pages, sh.Hkv, sh.D)
+    fill_randn_bf16(pool.tensor.view(-1), gen)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    T = b.T
+    q = synth.randn_bf16((T, sh.Hq, sh.D), gen, "cuda")
+    k_new = synth.randn_bf16((T, sh.Hkv, sh.D), gen, "cuda")
+    v_new = synth.randn_bf16((T, sh.Hkv, sh.D), gen, "cuda")
+    out = torch.empty_like(q)
+    ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+    keep = [pool, bb, q, k_new, v_new, out, ws]
+    dec_bytes, pre_flops, pre_bytes = attention_work(b)
+    append_bytes = 2 * T * 2 * sh.Hkv * sh.D * 2
+    layer = [0]
+
+    legs = []
+    if name == "qwen14b_ckpt":
+        dirty = torch.tensor(b.extra["dirty_pages"], dtype=torch.int32, device="cuda")
+        fresh = b.spare_pages[:dirty.numel()].to("cuda")
+        staging = torch.empty((sh.L, dirty.numel(), sh.page_elems), dtype=torch.bfloat16, device="cuda")
+        keep += [dirty, fresh, staging]
+        cp_bytes = 2 * sh.L * dirty.numel() * sh.page_elems * 2
+        legs.append(Leg("ckpt_gather", lambda: cs.cs_kv_ckpt_gather(pool, 0, sh.L, dirty, staging), "hbm", cp_bytes))
+        legs.append(Leg("ckpt_restore", lambda: cs.cs_kv_ckpt_restore(pool, 0, sh.L, fresh, staging), "hbm", cp_bytes))
+    legs.append(Leg("kv_append", lambda: cs.cs_kv_append(pool, layer[0], bb, k_new, v_new), "hbm", append_bytes))
+    att_bound = "hbm" if pre_flops / MFMA_BF16_PEAK < dec_bytes / HBM_PEAK else "mfma"
+    legs.append(Leg("paged_attention_mixed",
+                    lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb, q, out, sh.Hq, sh.scale, ws),
+                    att_bound, dec_bytes if att_bound == "hbm" else pre_flops))
+
+    detail = []
+    n_on = b.extra.get("n_online", 0)
+    n_act = b.extra.get("n_active", b.S)
+    if 0 < n_on < n_act:
+        # the two paths on their own sub-batches (for per-path roofline fractions)
+        bb_dec = bb.truncated(n_on)
+        ws_dec = cs.workspace_for(bb_dec, sh.Hq, sh.Hkv, sh.D)
+        cu = b.cu_q_lens[n_on:n_act + 1] - b.cu_q_lens[n_on]
+        bb_pre = cs.Batch(b.block_tables[n_on:n_act], b.ctx_lens[n_on:n_act], cu)
+        T_on = int(b.cu_q_lens[n_on])
+        q_pre, out_pre = q[T_on:], out[T_on:]
+        keep += [bb_dec, ws_dec, bb_pre, q_pre, out_pre]
+        detail.append(Leg("decode_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_dec, q, out, sh.Hq, sh.scale, ws_dec),
+                          "hbm", dec_bytes))
+        detail.append(Leg("prefill_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_pre, q_pre, out_pre, sh.Hq, sh.scale, None),
+                          "mfma", pre_flops))
+    info = {"T": T, "S": b.S, "dec_bytes": dec_bytes, "pre_flops": pre_flops, "pre_bytes": pre_bytes,
+            "append_bytes": append_bytes, "pool_gb": pool.tensor.numel() * 2 / 1e9, "name": b.name,
+            "keep": keep, "layer": layer, "L": sh.L}
+    return b, legs, detail, info
+
+
+def time_legs(legs, steps, warmup):
+    """W untimed steps, then K timed steps bracketed by synchronisation; HIP events on the
+    launch stream around every call give the per-call durations."""
+    import torch
+    for _ in range(warmup):
+        for leg in legs:
+            leg.fn()
+    torch.cuda.synchronize()
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(legs) + 1)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for k in range(steps):
+        for i, leg in enumerate(legs):
+            ev[k][i].record()
+            leg.fn()
+        ev[k][len(legs)].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for i, leg in enumerate(legs):
+        leg.us = sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(steps)) / steps * 1e3
+    return wall / steps
+
+
+def cpu_baseline(b, max_seconds=20.0):
+    """The oracle as it stands, timed on this host on a bounded sample of the workload's
+    sequences (inputs regenerated on the CPU with the same recipe)."""
+    import numpy as np
+    import torch
+    from oracle import attention
+    from paper_2410_01228_amd import synth
+    sh = b.shape
+    order = [s for s in range(b.S) if int(b.q_lens[s]) > 0]
+    # cost model of the plain loops: 4*Hq*D flop per (query, key) pair at roughly 1 GFLOP/s/thread
+    threads = attention.num_threads()
+    budget = max_seconds * 1.0e9 * threads
+    pick, cost = [], 0.0
+    stride = max(1, len(order) // 16)
+    for s in order[::stride] + [x for i, x in enumerate(order) if i % stride]:
+        c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
+        w = 4.0 * sh.Hq * sh.D * (ql * c + ql * (ql + 1) / 2)
+        if pick and cost + w > budget:
+            continue
+        pick.append(s)
+        cost += w
+        if len(pick) >= 64:
+            break
+    g = synth.generator(99)
+    tokens, secs = 0, 0.0
+    for s in pick:
+        c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
+        K = synth.randn_bf16((c + ql, sh.Hkv, sh.D), g).float().numpy()
+        V = synth.randn_bf16((c + ql, sh.Hkv, sh.D), g).float().numpy()
+        Q = synth.randn_bf16((ql, sh.Hq, sh.D), g).float().numpy()
+        t0 = time.perf_counter()
+        attention.attention_chunk(Q, K, V, c, sh.scale)
+        secs += time.perf_counter() - t0
+        tokens += ql
+    return {"value": round(tokens / secs, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": "%d of %d sequences (%d tokens) of the same workload, fp64 logical attention, %.1f s"
+                      % (len(pick), len(order), tokens, secs)}
+
+
+def read_traffic(name):
+    """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
+    p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
+    if not os.path.exists(p):
+        return None
+    for line in open(p):
+        if line.startswith("traffic_bytes_per_launch:"):
+            return float(line.split(":")[1])
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="llama8b_decode", choices=WORKLOADS)
+    ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build measures ONE GPU (the kernels of one GPU's share of the path); "
+            "--gpus %d is not supported, run with --gpus 1." % args.gpus)
+        sys.exit(2)
+
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    cs.lib()                                   # fail loudly if the HIP library is not built
+    torch.cuda.set_device(0)
+    cs.cs_set_decode_split_tokens(args.split_tokens)
+    b, legs, detail, info = build(args.workload)
+    log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
+        % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))
+    sec_per_step = time_legs(legs, args.steps, args.warmup)
+    for leg in legs:
+        r = leg.roofline()
+        log("  %-24s %9.1f us  %10.1f %s  (%.1f%% of %s peak)" % (leg.name, leg.us, r["achieved"], r["unit"], 100 * r["frac"], r["bound"]))
+    if args.detail and detail:
+        time_legs(detail, args.steps, args.warmup)
+        for leg in detail:
+            r = leg.roofline()
+            log("  %-24s %9.1f us  %10.1f %s  (%.1f%% of %s peak)" % (leg.name, leg.us, r["achieved"], r["unit"], 100 * r["frac"], r["bound"]))
+
+    by_name = {l.name: l for l in legs}
+    att_us = by_name["kv_append"].us + by_name["paged_attention_mixed"].us
+    if args.workload == "qwen14b_ckpt":
+        dom = by_name["ckpt_gather"]
+    elif args.detail and detail and by_name["paged_attention_mixed"].bound == "mfma":
+        dom = detail[1]
+    else:
+        dom = by_name["paged_attention_mixed"]
+    result = {
+        "metric": "mixed-batch paged-attn tokens/s per layer",
+        "value": round(info["T"] / (att_us * 1e-6), 1),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
+                   "page_size": 16, "layers_per_step": 1,
+                   "step": "+".join(l.name for l in legs)},
+        "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=dom.name),
+        "legs": {l.name: {"us": round(l.us, 2), "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(b)
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()
