@@ -6,14 +6,22 @@
 // A workgroup (4 wavefronts) owns one kv head and a tile of TQ consecutive chunk tokens
 // with all G query heads that share the kv head: 16 "column tiles" of 16 query rows
 // (16 tokens of one head), 4 per wavefront.  It walks the sequence's keys 32 at a time
-// (two pages): all lanes copy the two pages' K and V blocks into LDS (double buffered, one
-// barrier per step), every wavefront reads them back as MFMA operands -- the page format
-// is the operand layout, so the LDS reads are linear in the lane id -- and computes
+// (two pages).  All lanes copy the pages' K and V blocks into LDS (two K and two V
+// buffers, one barrier per step); every wavefront reads them back as MFMA operands -- the
+// page format is the operand layout, so the LDS reads are linear in the lane id -- and
 //   S^T[key][query]   = K . Q^T                      v_mfma_f32_16x16x32_bf16
 //   O^T[d][query]    += V^T[d][32 keys] . P^T        v_mfma_f32_16x16x32_bf16
 // with P^T taken straight from the S^T accumulators of the two pages (their C layout is
-// the B layout of the second product).
+// the B layout of the second product).  The softmax denominators come from one more MFMA
+// per tile with an all-ones A operand, so they sum exactly the bf16 weights that multiply V.
+//
+// The loop is software-pipelined: iteration i exponentiates the scores of step i and
+// multiplies them with V(i) while the matrix cores already compute the scores of step
+// i+1, so the exp/convert work of one step overlaps the MFMAs of the next.  The running
+// maximum is only raised (and the accumulators rescaled) when a new score exceeds it by
+// more than 2^kLazyLog2, which keeps the rescale out of the steady-state loop.
 #include "cs_common.h"
+#include <type_traits>
 
 namespace cs {
 
@@ -26,6 +34,7 @@ constexpr int kPrefillWaves = 4;
 constexpr int kPrefillThreads = kPrefillWaves * 64;
 constexpr int kNCT = 4;                       // column tiles per wavefront
 constexpr int kKeysPerStep = 32;              // two pages
+constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
 
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -44,10 +53,12 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e)
 {
-    constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block
-    constexpr int kStepUnits = 4 * kUnits;            // K,V of two pages
-    constexpr int kLoads = kStepUnits / kPrefillThreads;
-    __shared__ u32x4 lds[2][kStepUnits];
+    constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block of a page
+    constexpr int kStepUnits = 2 * kUnits;            // K (or V) units of one step (two pages)
+    constexpr int kLoads = kStepUnits / kPrefillThreads;   // 16-byte loads per lane, for K and for V
+    constexpr int kLoadsPerPage = kLoads / 2 > 0 ? kLoads / 2 : 1;
+    __shared__ u32x4 lds_k[2][kStepUnits];
+    __shared__ u32x4 lds_v[2][kStepUnits];
 
     const int32_t TQ = prefill_tile_tokens(G);
     const int32_t g = blockIdx.x;
@@ -70,6 +81,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     const int32_t n_seq_keys = C + q_len;              // keys the sequence holds after the append
     const int32_t n_keys = C + tok0 + n_tok;           // keys visible to the tile's last token
     const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
+    const int32_t first_edge = (C + tok0 + 1) / kKeysPerStep;   // steps before it need no causal mask
     const int32_t n_pages = min((n_seq_keys + kPage - 1) >> 4, max_blocks);
     const int32_t* table = block_tables + (int64_t)s * max_blocks;
     const int32_t Hq = Hkv * G;
@@ -79,7 +91,6 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     // ---- this wavefront's column tiles: ct = wave*4 + c -> (token block, head) ----
     bf16x8 qb[kNCT][D / 32];
     int32_t pos_q[kNCT];                               // absolute position of this lane's query
-    int32_t min_pos[kNCT];                             // of the tile's first token (wave-uniform)
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
@@ -88,7 +99,6 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         const int32_t tl = tok0 + tb * 16 + (lane & 15);     // chunk-local token of this column
         const bool valid = tb * 16 < TQ && tl < q_len;
         pos_q[c] = C + tl;
-        min_pos[c] = C + tok0 + tb * 16;
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
             u32x4 v = zero4;
@@ -99,112 +109,164 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     }
 
     f32x4 o[kNCT][D / 16];
-    float m_run[kNCT], l_run[kNCT];
+    f32x4 lacc[kNCT];                                  // softmax denominators (every row equal)
+    float m_run[kNCT];
+    float x[kNCT][8];                                  // scaled scores of the current step
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
         m_run[c] = -INFINITY;
-        l_run[c] = 0.f;
+        lacc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) o[c][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
+    const u32x4 ones4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
+    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
 
-    // ---- global -> register stage of one step (two pages, K and V blocks of head g) ----
-    u32x4 stage[kLoads];
-    auto fetch = [&](int32_t step) {
+    // ---- global -> register staging.  Lane tid, load j covers unit (j % LPP)*256 + tid of
+    // page j / LPP of the step, for K and for V alike. ----
+    auto page_id = [&](int32_t pg) -> int32_t {        // wave-uniform, -1 if there is no such page
+        int32_t id = -1;
+        if (pg < n_pages) {
+            id = __builtin_amdgcn_readfirstlane(table[pg]);
+            if (id < 0 || id >= num_pages) id = -1;
+        }
+        return id;
+    };
+    auto fetch = [&](u32x4* stage, int32_t step, int32_t id0, int32_t id1, int kv) {
 #pragma unroll
         for (int j = 0; j < kLoads; ++j) {
-            const int u = tid + j * kPrefillThreads;
-            const int pg_in = u / (2 * kUnits);                 // 0 or 1: page within the step
-            const int rem = u - pg_in * 2 * kUnits;
-            const int kv = rem / kUnits, idx = rem - kv * kUnits;
-            const int32_t pg = step * 2 + pg_in;
+            int pg_in, idx;
+            if (kLoads >= 2) { pg_in = j / kLoadsPerPage; idx = tid + (j % kLoadsPerPage) * kPrefillThreads; }
+            else             { pg_in = tid / kUnits;      idx = tid % kUnits; }
+            const int32_t id = kLoads >= 2 ? (pg_in ? id1 : id0) : (pg_in ? id1 : id0);
             u32x4 v = zero4;
-            if (pg < n_pages) {
-                const int32_t id = table[pg];
-                if (id >= 0 && id < num_pages) {
-                    const uint16_t* blk = layer_base + (int64_t)id * page_stride
-                                        + ((int64_t)kv * Hkv + g) * (kPage * D);
-                    v = *((const u32x4*)blk + idx);
-                    if (kv == 1 && (pg + 1) * kPage > n_seq_keys) {
-                        // V slots past the end of the sequence hold stale bits: zero them so
-                        // that a zero weight times the slot stays zero.  A 16-byte unit holds
-                        // two features of one 4-token group.
-                        const int32_t valid = n_seq_keys - (pg * kPage + ((idx >> 3) & 3) * 4);
-                        const uint32_t m0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
-                        const uint32_t m1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
-                        v[0] &= m0; v[1] &= m1; v[2] &= m0; v[3] &= m1;
-                    }
+            if (id >= 0) {
+                const uint16_t* blk = layer_base + (int64_t)id * page_stride + ((int64_t)kv * Hkv + g) * (kPage * D);
+                v = *((const u32x4*)blk + idx);
+                const int32_t pg = step * 2 + pg_in;
+                if (kv == 1 && (pg + 1) * kPage > n_seq_keys) {
+                    // V slots past the end of the sequence hold stale bits: zero them so that a
+                    // zero weight times the slot stays zero.  A 16-byte unit holds two features
+                    // of one 4-token group.
+                    const int32_t valid = n_seq_keys - (pg * kPage + ((idx >> 3) & 3) * 4);
+                    const uint32_t m0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
+                    const uint32_t m1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
+                    v[0] &= m0; v[1] &= m1; v[2] &= m0; v[3] &= m1;
                 }
             }
             stage[j] = v;
         }
     };
-    auto commit = [&](int buf) {
+    auto commit = [&](u32x4* dst, const u32x4* stage) {
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) lds[buf][tid + j * kPrefillThreads] = stage[j];
+        for (int j = 0; j < kLoads; ++j) {
+            int slot;
+            if (kLoads >= 2) slot = (j / kLoadsPerPage) * kUnits + tid + (j % kLoadsPerPage) * kPrefillThreads;
+            else             slot = tid;
+            dst[slot] = stage[j];
+        }
     };
 
-    fetch(0);
-    commit(0);
-    __syncthreads();
-
-    for (int32_t step = 0; step < n_steps; ++step) {
-        const int buf = step & 1;
-        if (step + 1 < n_steps) fetch(step + 1);
-        const int32_t kb = step * kKeysPerStep;               // first key of the step
-        const u32x4* kA0 = &lds[buf][0];
-        const u32x2* vA0 = (const u32x2*)&lds[buf][kUnits];
-        const u32x4* kA1 = &lds[buf][2 * kUnits];
-        const u32x2* vA1 = (const u32x2*)&lds[buf][3 * kUnits];
-
-        bf16x8 ka[2][D / 32];
+    // scores of one step: x[c][0..3] = keys kb + 4*(lane/16) + i of the first page, x[c][4..7]
+    // the same rows of the second page; column maxima over the 32 keys in mx[c]
+    auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8], float (&mx)[kNCT]) {
+        constexpr bool kMask = decltype(masked)::value;
+        const u32x4* kA0 = &lds_k[step & 1][0];
+        const u32x4* kA1 = &lds_k[step & 1][kUnits];
+        f32x4 s0[kNCT], s1[kNCT];
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
-            ka[0][kk] = __builtin_bit_cast(bf16x8, kA0[kk * 64 + lane]);
-            ka[1][kk] = __builtin_bit_cast(bf16x8, kA1[kk * 64 + lane]);
+            const bf16x8 ka0 = __builtin_bit_cast(bf16x8, kA0[kk * 64 + lane]);
+            const bf16x8 ka1 = __builtin_bit_cast(bf16x8, kA1[kk * 64 + lane]);
+#pragma unroll
+            for (int c = 0; c < kNCT; ++c) {
+                s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka0, qb[c][kk], s0[c], 0, 0, 0);
+                s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka1, qb[c][kk], s1[c], 0, 0, 0);
+            }
         }
-        bf16x8 pb[kNCT];
+        const int32_t key0 = step * kKeysPerStep + (lane >> 4) * 4;
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
-            f32x4 s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int kk = 0; kk < D / 32; ++kk) {
-                s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[0][kk], qb[c][kk], s0, 0, 0, 0);
-                s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka[1][kk], qb[c][kk], s1, 0, 0, 0);
-            }
-            float x[8];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) { x[i] = s0[i] * scale_log2e; x[4 + i] = s1[i] * scale_log2e; }
-            if (kb + kKeysPerStep - 1 > min_pos[c]) {          // causal edge inside this step
-                const int32_t key0 = kb + (lane >> 4) * 4;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    if (key0 + i > pos_q[c]) x[i] = -INFINITY;
-                    if (key0 + 16 + i > pos_q[c]) x[4 + i] = -INFINITY;
+            for (int i = 0; i < 4; ++i) {
+                xs[c][i] = s0[c][i] * scale_log2e;
+                xs[c][4 + i] = s1[c][i] * scale_log2e;
+                if (kMask) {
+                    if (key0 + i > pos_q[c]) xs[c][i] = -INFINITY;
+                    if (key0 + 16 + i > pos_q[c]) xs[c][4 + i] = -INFINITY;
                 }
             }
-            float mx = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), fmaxf(fmaxf(x[4], x[5]), fmaxf(x[6], x[7])));
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m_run[c], mx);            // finite from step 0 on (key 0 is visible)
-            if (__any(m_new > m_run[c])) {
-                const float alpha = exp2f(m_run[c] - m_new);
-                l_run[c] *= alpha;
+            float m = fmaxf(fmaxf(fmaxf(xs[c][0], xs[c][1]), fmaxf(xs[c][2], xs[c][3])),
+                            fmaxf(fmaxf(xs[c][4], xs[c][5]), fmaxf(xs[c][6], xs[c][7])));
+            m = fmaxf(m, __shfl_xor(m, 16, 64));
+            m = fmaxf(m, __shfl_xor(m, 32, 64));
+            mx[c] = m;
+        }
+    };
+    // raise the running maxima where a new score exceeds them by more than 2^kLazyLog2
+    auto raise_max = [&](const float (&mx)[kNCT]) {
+        bool need = false;
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c) need |= mx[c] > m_run[c] + kLazyLog2;
+        if (__any(need)) {
+#pragma unroll
+            for (int c = 0; c < kNCT; ++c) {
+                const float m_new = fmaxf(m_run[c], mx[c]);
+                const float alpha = __builtin_amdgcn_exp2f(m_run[c] - m_new);   // 0 while m_run is -inf
+                lacc[c] *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) o[c][dt] *= alpha;
                 m_run[c] = m_new;
             }
+        }
+    };
+
+    // ---- prologue: K(0), V(0), K(1) into LDS; scores of step 0 ----
+    u32x4 stage_k[kLoads], stage_v[kLoads];
+    int32_t idk0 = page_id(0), idk1 = page_id(1);      // pages of the step whose K is fetched next
+    fetch(stage_k, 0, idk0, idk1, 0);
+    fetch(stage_v, 0, idk0, idk1, 1);
+    commit(lds_k[0], stage_k);
+    commit(lds_v[0], stage_v);
+    int32_t idv0 = page_id(2), idv1 = page_id(3);      // pages of step 1 (its V is fetched in iteration 0)
+    fetch(stage_k, 1, idv0, idv1, 0);
+    commit(lds_k[1], stage_k);
+    idk0 = page_id(4); idk1 = page_id(5);              // pages of step 2
+    __syncthreads();
+    {
+        float mx[kNCT];
+        scores(std::true_type{}, 0, x, mx);
+        raise_max(mx);
+    }
+    __syncthreads();
+
+    // ---- iteration i: weights of step i, scores of step i+1, O += V(i) P(i) ----
+    auto iteration = [&](auto masked, int32_t i) {
+        const bool has_next = i + 1 < n_steps;
+        // K(i+2) and V(i+1) leave for the registers now and land in LDS at the end of the iteration
+        fetch(stage_k, i + 2, idk0, idk1, 0);
+        fetch(stage_v, i + 1, idv0, idv1, 1);
+        idv0 = idk0; idv1 = idk1;
+        idk0 = page_id(2 * (i + 3)); idk1 = page_id(2 * (i + 3) + 1);
+
+        bf16x8 pb[kNCT];
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c) {
             float p[8];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) p[i] = exp2f(x[i] - m_run[c]);
-            u32x4 pk = { pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]) };
-            float ls = 0.f;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)        // sum the weights as rounded, the ones that multiply V
-                ls += __builtin_bit_cast(float, pk[i] << 16) + __builtin_bit_cast(float, pk[i] & 0xffff0000u);
-            l_run[c] += ls;
+            for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(x[c][j] - m_run[c]);
+            const u32x4 pk = { pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]) };
             pb[c] = __builtin_bit_cast(bf16x8, pk);
         }
+        float mx[kNCT];
+        if (has_next) scores(masked, i + 1, x, mx);
+        const u32x2* vA0 = (const u32x2*)&lds_v[i & 1][0];
+        const u32x2* vA1 = (const u32x2*)&lds_v[i & 1][kUnits];
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c)
+            lacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[c], lacc[c], 0, 0, 0);
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
             const u32x2 a0 = vA0[dt * 64 + lane], a1 = vA1[dt * 64 + lane];
@@ -214,21 +276,23 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
             for (int c = 0; c < kNCT; ++c)
                 o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[c], o[c][dt], 0, 0, 0);
         }
-        if (step + 1 < n_steps) commit(buf ^ 1);
+        if (has_next) raise_max(mx);
+        commit(lds_k[i & 1], stage_k);
+        commit(lds_v[(i + 1) & 1], stage_v);
         __syncthreads();
-    }
+    };
+    int32_t i = 0;
+    for (; i + 1 < first_edge; ++i) iteration(std::false_type{}, i);      // step i+1 is fully visible
+    for (; i < n_steps; ++i) iteration(std::true_type{}, i);
 
     // ---- normalise and store: lane holds 4 consecutive features of one query row per tile ----
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
-        float l = l_run[c];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
         const int32_t ct = wave * kNCT + c;
         const int32_t tb = ct / G, hh = ct - tb * G;
         const int32_t tl = tok0 + tb * 16 + (lane & 15);
         if (tb * 16 < TQ && tl < q_len) {
-            const float inv = 1.f / l;
+            const float inv = 1.f / lacc[c][0];
             uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + (lane >> 4) * 4;
 #pragma unroll
             for (int dt = 0; dt < D / 16; ++dt) {
