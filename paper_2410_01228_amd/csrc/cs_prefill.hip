@@ -6,8 +6,9 @@
 // A workgroup (4 wavefronts) owns one kv head and a tile of TQ consecutive chunk tokens
 // with all G query heads that share the kv head: 16 "column tiles" of 16 query rows
 // (16 tokens of one head), 4 per wavefront.  It walks the sequence's keys 32 at a time
-// (two pages).  All lanes copy the pages' K and V blocks into LDS (two K and two V
-// buffers, one barrier per step); every wavefront reads them back as MFMA operands -- the
+// (two pages).  The pages' K and V blocks are copied global -> LDS by LDS-DMA loads into a
+// ring of slots several steps ahead (one barrier per step, no staging registers); every
+// wavefront reads them back as MFMA operands -- the
 // page format is the operand layout, so the LDS reads are linear in the lane id -- and
 //   S^T[key][query]   = K . Q^T                      v_mfma_f32_16x16x32_bf16
 //   O^T[d][query]    += V^T[d][32 keys] . P^T        v_mfma_f32_16x16x32_bf16
@@ -35,6 +36,26 @@ constexpr int kPrefillThreads = kPrefillWaves * 64;
 constexpr int kNCT = 4;                       // column tiles per wavefront
 constexpr int kKeysPerStep = 32;              // two pages
 constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
+constexpr int kRing = 4;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
+
+// s_waitcnt on the vector-memory counter alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
+// expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
+}
+
+// One LDS-DMA load: every lane's 16 bytes at `src` go to LDS at `dst_wave_base` + lane*16
+// (dst_wave_base is wave-uniform and travels in M0).  Written as inline assembly so that the
+// compiler's wait-count pass does not see it: it cannot tell which ring slot a later LDS
+// read touches and would drain the whole copy queue (vmcnt(0)) before every read.  The waits
+// are placed by hand with wait_vmcnt<>() instead.
+__device__ __forceinline__ void lds_dma16(const void* src, void* dst_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_base;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :: "s"(lds_addr), "v"(src) : "memory", "m0");
+}
 
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
@@ -56,9 +77,9 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block of a page
     constexpr int kStepUnits = 2 * kUnits;            // K (or V) units of one step (two pages)
     constexpr int kLoads = kStepUnits / kPrefillThreads;   // 16-byte loads per lane, for K and for V
-    constexpr int kLoadsPerPage = kLoads / 2 > 0 ? kLoads / 2 : 1;
-    __shared__ u32x4 lds_k[2][kStepUnits];
-    __shared__ u32x4 lds_v[2][kStepUnits];
+    constexpr int kStepLoads = 2 * kLoads;            // LDS-DMA instructions per wavefront and step
+    __shared__ u32x4 lds_k[kRing][kStepUnits];
+    __shared__ u32x4 lds_v[kRing][kStepUnits];
 
     const int32_t TQ = prefill_tile_tokens(G);
     const int32_t g = blockIdx.x;
@@ -122,48 +143,34 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     const u32x4 ones4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
     const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
 
-    // ---- global -> register staging.  Lane tid, load j covers unit (j % LPP)*256 + tid of
-    // page j / LPP of the step, for K and for V alike. ----
-    auto page_id = [&](int32_t pg) -> int32_t {        // wave-uniform, -1 if there is no such page
-        int32_t id = -1;
+    // ---- global -> LDS copies (LDS-DMA: each lane hands its 16 bytes straight to LDS at
+    // base + lane*16, no staging registers).  Per step and wavefront kLoads instructions for K
+    // and kLoads for V; instruction r covers units (r*4 + wave)*64 .. +64 of the step, which
+    // lie inside one page.  A page the sequence does not have is replaced by page 0 of the
+    // pool: every step issues the same number of instructions (the vmcnt arithmetic below
+    // relies on it) and whatever lands is masked where it is used. ----
+    auto page_id = [&](int32_t pg) -> int32_t {        // wave-uniform, always a valid page
+        int32_t id = 0;
         if (pg < n_pages) {
             id = __builtin_amdgcn_readfirstlane(table[pg]);
-            if (id < 0 || id >= num_pages) id = -1;
+            if (id < 0 || id >= num_pages) id = 0;
         }
         return id;
     };
-    auto fetch = [&](u32x4* stage, int32_t step, int32_t id0, int32_t id1, int kv) {
+    auto dma_step = [&](int32_t step, int32_t id0, int32_t id1) {
+        const int slot = step % kRing;
 #pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            int pg_in, idx;
-            if (kLoads >= 2) { pg_in = j / kLoadsPerPage; idx = tid + (j % kLoadsPerPage) * kPrefillThreads; }
-            else             { pg_in = tid / kUnits;      idx = tid % kUnits; }
-            const int32_t id = kLoads >= 2 ? (pg_in ? id1 : id0) : (pg_in ? id1 : id0);
-            u32x4 v = zero4;
-            if (id >= 0) {
+        for (int kv = 0; kv < 2; ++kv) {
+#pragma unroll
+            for (int r = 0; r < kLoads; ++r) {
+                const int unit0 = (r * kPrefillWaves + wave) * 64;          // wave-uniform
+                const int pg_in = unit0 / kUnits;
+                const int32_t id = pg_in ? id1 : id0;
                 const uint16_t* blk = layer_base + (int64_t)id * page_stride + ((int64_t)kv * Hkv + g) * (kPage * D);
-                v = *((const u32x4*)blk + idx);
-                const int32_t pg = step * 2 + pg_in;
-                if (kv == 1 && (pg + 1) * kPage > n_seq_keys) {
-                    // V slots past the end of the sequence hold stale bits: zero them so that a
-                    // zero weight times the slot stays zero.  A 16-byte unit holds two features
-                    // of one 4-token group.
-                    const int32_t valid = n_seq_keys - (pg * kPage + ((idx >> 3) & 3) * 4);
-                    const uint32_t m0 = valid >= 2 ? 0xffffffffu : (valid == 1 ? 0x0000ffffu : 0u);
-                    const uint32_t m1 = valid >= 4 ? 0xffffffffu : (valid == 3 ? 0x0000ffffu : 0u);
-                    v[0] &= m0; v[1] &= m1; v[2] &= m0; v[3] &= m1;
-                }
+                const u32x4* src = (const u32x4*)blk + (unit0 - pg_in * kUnits) + lane;
+                u32x4* dst = kv ? &lds_v[slot][unit0] : &lds_k[slot][unit0];
+                lds_dma16(src, dst);
             }
-            stage[j] = v;
-        }
-    };
-    auto commit = [&](u32x4* dst, const u32x4* stage) {
-#pragma unroll
-        for (int j = 0; j < kLoads; ++j) {
-            int slot;
-            if (kLoads >= 2) slot = (j / kLoadsPerPage) * kUnits + tid + (j % kLoadsPerPage) * kPrefillThreads;
-            else             slot = tid;
-            dst[slot] = stage[j];
         }
     };
 
@@ -171,8 +178,8 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     // the same rows of the second page; column maxima over the 32 keys in mx[c]
     auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8], float (&mx)[kNCT]) {
         constexpr bool kMask = decltype(masked)::value;
-        const u32x4* kA0 = &lds_k[step & 1][0];
-        const u32x4* kA1 = &lds_k[step & 1][kUnits];
+        const u32x4* kA0 = &lds_k[step % kRing][0];
+        const u32x4* kA1 = &lds_k[step % kRing][kUnits];
         f32x4 s0[kNCT], s1[kNCT];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
@@ -223,33 +230,28 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         }
     };
 
-    // ---- prologue: K(0), V(0), K(1) into LDS; scores of step 0 ----
-    u32x4 stage_k[kLoads], stage_v[kLoads];
-    int32_t idk0 = page_id(0), idk1 = page_id(1);      // pages of the step whose K is fetched next
-    fetch(stage_k, 0, idk0, idk1, 0);
-    fetch(stage_v, 0, idk0, idk1, 1);
-    commit(lds_k[0], stage_k);
-    commit(lds_v[0], stage_v);
-    int32_t idv0 = page_id(2), idv1 = page_id(3);      // pages of step 1 (its V is fetched in iteration 0)
-    fetch(stage_k, 1, idv0, idv1, 0);
-    commit(lds_k[1], stage_k);
-    idk0 = page_id(4); idk1 = page_id(5);              // pages of step 2
+    // ---- prologue: steps 0 .. kRing-2 in flight, steps 0 and 1 landed, scores of step 0 ----
+    int32_t id_a = 0, id_b = 0;                        // pages of the step issued next
+#pragma unroll
+    for (int j = 0; j < kRing - 1; ++j) dma_step(j, page_id(2 * j), page_id(2 * j + 1));
+    id_a = page_id(2 * (kRing - 1));
+    id_b = page_id(2 * (kRing - 1) + 1);
+    wait_vmcnt<(kRing - 3) * kStepLoads>();
     __syncthreads();
     {
         float mx[kNCT];
         scores(std::true_type{}, 0, x, mx);
         raise_max(mx);
     }
-    __syncthreads();
 
     // ---- iteration i: weights of step i, scores of step i+1, O += V(i) P(i) ----
     auto iteration = [&](auto masked, int32_t i) {
         const bool has_next = i + 1 < n_steps;
-        // K(i+2) and V(i+1) leave for the registers now and land in LDS at the end of the iteration
-        fetch(stage_k, i + 2, idk0, idk1, 0);
-        fetch(stage_v, i + 1, idv0, idv1, 1);
-        idv0 = idk0; idv1 = idk1;
-        idk0 = page_id(2 * (i + 3)); idk1 = page_id(2 * (i + 3) + 1);
+        // step i+kRing-1 goes into the slot step i-1 left (its last reader finished before the
+        // barrier that ended iteration i-1)
+        dma_step(i + kRing - 1, id_a, id_b);
+        id_a = page_id(2 * (i + kRing));
+        id_b = page_id(2 * (i + kRing) + 1);
 
         bf16x8 pb[kNCT];
 #pragma unroll
@@ -262,28 +264,43 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         }
         float mx[kNCT];
         if (has_next) scores(masked, i + 1, x, mx);
-        const u32x2* vA0 = (const u32x2*)&lds_v[i & 1][0];
-        const u32x2* vA1 = (const u32x2*)&lds_v[i & 1][kUnits];
+        const u32x2* vA0 = (const u32x2*)&lds_v[i % kRing][0];
+        const u32x2* vA1 = (const u32x2*)&lds_v[i % kRing][kUnits];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
             lacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[c], lacc[c], 0, 0, 0);
+        // V slots at or past the end of the sequence hold stale bits (or nothing at all): zero
+        // them so that a zero weight times the slot stays zero.  Lane holds tokens
+        // 4*(lane/16) .. +4 of each page.
+        uint32_t vm[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
+        if (decltype(masked)::value && (i + 1) * kKeysPerStep > n_seq_keys) {
+            const int32_t v0 = n_seq_keys - (i * kKeysPerStep + (lane >> 4) * 4);
+            const int32_t v1 = v0 - kPage;
+            vm[0] = v0 >= 2 ? 0xffffffffu : (v0 == 1 ? 0x0000ffffu : 0u);
+            vm[1] = v0 >= 4 ? 0xffffffffu : (v0 == 3 ? 0x0000ffffu : 0u);
+            vm[2] = v1 >= 2 ? 0xffffffffu : (v1 == 1 ? 0x0000ffffu : 0u);
+            vm[3] = v1 >= 4 ? 0xffffffffu : (v1 == 3 ? 0x0000ffffu : 0u);
+        }
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
             const u32x2 a0 = vA0[dt * 64 + lane], a1 = vA1[dt * 64 + lane];
-            const u32x4 av = { a0[0], a0[1], a1[0], a1[1] };
+            u32x4 av = { a0[0], a0[1], a1[0], a1[1] };
+            if (decltype(masked)::value) { av[0] &= vm[0]; av[1] &= vm[1]; av[2] &= vm[2]; av[3] &= vm[3]; }
             const bf16x8 va = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
             for (int c = 0; c < kNCT; ++c)
                 o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[c], o[c][dt], 0, 0, 0);
         }
         if (has_next) raise_max(mx);
-        commit(lds_k[i & 1], stage_k);
-        commit(lds_v[(i + 1) & 1], stage_v);
+        // K(i+2) and V(i+1) must have landed before the next iteration reads them: all but the
+        // copies of the last kRing-3 steps issued
+        wait_vmcnt<(kRing - 3) * kStepLoads>();
         __syncthreads();
     };
     int32_t i = 0;
     for (; i + 1 < first_edge; ++i) iteration(std::false_type{}, i);      // step i+1 is fully visible
     for (; i < n_steps; ++i) iteration(std::true_type{}, i);
+    wait_vmcnt<0>();                                   // no copy may outlive the workgroup's LDS
 
     // ---- normalise and store: lane holds 4 consecutive features of one query row per tile ----
 #pragma unroll
