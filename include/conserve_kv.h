@@ -107,6 +107,7 @@ size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t num_q_h
  * where K_s, V_s are read from the pool through block_tables[s].  The step's own new K/V
  * must already be in the pool (call cs_kv_append first on the same stream).  Sequences with
  * one new token take the split-KV decode path, longer chunks the MFMA tile path.
+ * softmax_scale must be positive and finite.
  * q, out: device [T][Hq][D] bf16.  workspace: device, at least
  * cs_paged_attention_workspace_bytes(); contents are scratch. */
 int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,

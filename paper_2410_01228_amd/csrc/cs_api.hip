@@ -132,7 +132,7 @@ int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_bat
     if (rc) return rc;
     if (batch->num_tokens == 0) return CS_OK;
     if (!q || !out || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return CS_ERR_INVALID_ARG;
-    if (!(softmax_scale == softmax_scale)) return CS_ERR_INVALID_ARG;
+    if (!(softmax_scale > 0.f) || softmax_scale > 3.0e38f) return CS_ERR_INVALID_ARG;   // positive, finite
     const DecodePlan plan = plan_decode(batch, pool->num_kv_heads);
     const size_t need = decode_workspace_bytes(plan, batch->num_seqs, Hq, pool->head_dim);
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;

@@ -132,7 +132,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     f32x4 o[kNCT][D / 16];
     f32x4 lacc[kNCT];                                  // softmax denominators (every row equal)
     float m_run[kNCT];
-    float x[kNCT][8];                                  // scaled scores of the current step
+    float x[kNCT][8];                                  // raw scores of the current step
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
         m_run[c] = -INFINITY;
@@ -149,14 +149,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     // lie inside one page.  A page the sequence does not have is replaced by page 0 of the
     // pool: every step issues the same number of instructions (the vmcnt arithmetic below
     // relies on it) and whatever lands is masked where it is used. ----
-    auto page_id = [&](int32_t pg) -> int32_t {        // wave-uniform, always a valid page
-        int32_t id = 0;
-        if (pg < n_pages) {
-            id = __builtin_amdgcn_readfirstlane(table[pg]);
-            if (id < 0 || id >= num_pages) id = 0;
-        }
-        return id;
+    auto page_id_raw = [&](int32_t pg) -> int32_t {    // wave-uniform table entry, unchecked
+        return pg < n_pages ? __builtin_amdgcn_readfirstlane(table[pg]) : 0;
     };
+    auto checked = [&](int32_t id) -> int32_t { return (id < 0 || id >= num_pages) ? 0 : id; };
     auto dma_step = [&](int32_t step, int32_t id0, int32_t id1) {
         const int slot = step % kRing;
 #pragma unroll
@@ -165,7 +161,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
             for (int r = 0; r < kLoads; ++r) {
                 const int unit0 = (r * kPrefillWaves + wave) * 64;          // wave-uniform
                 const int pg_in = unit0 / kUnits;
-                const int32_t id = pg_in ? id1 : id0;
+                const int32_t id = checked(pg_in ? id1 : id0);
                 const uint16_t* blk = layer_base + (int64_t)id * page_stride + ((int64_t)kv * Hkv + g) * (kPage * D);
                 const u32x4* src = (const u32x4*)blk + (unit0 - pg_in * kUnits) + lane;
                 u32x4* dst = kv ? &lds_v[slot][unit0] : &lds_k[slot][unit0];
@@ -174,9 +170,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         }
     };
 
-    // scores of one step: x[c][0..3] = keys kb + 4*(lane/16) + i of the first page, x[c][4..7]
-    // the same rows of the second page; column maxima over the 32 keys in mx[c]
-    auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8], float (&mx)[kNCT]) {
+    // Raw scores of one step (before the softmax scale): xs[c][0..3] = keys
+    // 32*step + 4*(lane/16) + i of the first page, xs[c][4..7] the same rows of the second page.
+    // Masked entries become -inf.
+    auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8]) {
         constexpr bool kMask = decltype(masked)::value;
         const u32x4* kA0 = &lds_k[step % kRing][0];
         const u32x4* kA1 = &lds_k[step % kRing][kUnits];
@@ -198,34 +195,45 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         for (int c = 0; c < kNCT; ++c) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                xs[c][i] = s0[c][i] * scale_log2e;
-                xs[c][4 + i] = s1[c][i] * scale_log2e;
+                xs[c][i] = s0[c][i];
+                xs[c][4 + i] = s1[c][i];
                 if (kMask) {
                     if (key0 + i > pos_q[c]) xs[c][i] = -INFINITY;
                     if (key0 + 16 + i > pos_q[c]) xs[c][4 + i] = -INFINITY;
                 }
             }
-            float m = fmaxf(fmaxf(fmaxf(xs[c][0], xs[c][1]), fmaxf(xs[c][2], xs[c][3])),
-                            fmaxf(fmaxf(xs[c][4], xs[c][5]), fmaxf(xs[c][6], xs[c][7])));
-            m = fmaxf(m, __shfl_xor(m, 16, 64));
-            m = fmaxf(m, __shfl_xor(m, 32, 64));
-            mx[c] = m;
         }
     };
-    // raise the running maxima where a new score exceeds them by more than 2^kLazyLog2
-    auto raise_max = [&](const float (&mx)[kNCT]) {
+    // Lazy running maximum.  m_run[c] is the (log2-domain) offset all four lane groups of a
+    // column use; it only has to bound the scores loosely.  The hot path merely tests this
+    // lane's raw scores against thr[c] = (m_run[c] + kLazyLog2) / scale; the cross-lane maximum
+    // and the rescale of the accumulators run only when some lane trips the test.
+    float thr[kNCT];
+#pragma unroll
+    for (int c = 0; c < kNCT; ++c) thr[c] = -INFINITY;
+    const float inv_scale = 1.f / scale_log2e;
+    auto raise_max = [&](const float (&xs)[kNCT][8]) {
         bool need = false;
 #pragma unroll
-        for (int c = 0; c < kNCT; ++c) need |= mx[c] > m_run[c] + kLazyLog2;
+        for (int c = 0; c < kNCT; ++c) {
+            const float m = fmaxf(fmaxf(fmaxf(xs[c][0], xs[c][1]), fmaxf(xs[c][2], xs[c][3])),
+                                  fmaxf(fmaxf(xs[c][4], xs[c][5]), fmaxf(xs[c][6], xs[c][7])));
+            need |= m > thr[c];
+        }
         if (__any(need)) {
 #pragma unroll
             for (int c = 0; c < kNCT; ++c) {
-                const float m_new = fmaxf(m_run[c], mx[c]);
+                float m = fmaxf(fmaxf(fmaxf(xs[c][0], xs[c][1]), fmaxf(xs[c][2], xs[c][3])),
+                                fmaxf(fmaxf(xs[c][4], xs[c][5]), fmaxf(xs[c][6], xs[c][7])));
+                m = fmaxf(m, __shfl_xor(m, 16, 64));
+                m = fmaxf(m, __shfl_xor(m, 32, 64));
+                const float m_new = fmaxf(m_run[c], m * scale_log2e);
                 const float alpha = __builtin_amdgcn_exp2f(m_run[c] - m_new);   // 0 while m_run is -inf
                 lacc[c] *= alpha;
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) o[c][dt] *= alpha;
                 m_run[c] = m_new;
+                thr[c] = (m_new + kLazyLog2) * inv_scale;
             }
         }
     };
@@ -233,37 +241,37 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     // ---- prologue: steps 0 .. kRing-2 in flight, steps 0 and 1 landed, scores of step 0 ----
     int32_t id_a = 0, id_b = 0;                        // pages of the step issued next
 #pragma unroll
-    for (int j = 0; j < kRing - 1; ++j) dma_step(j, page_id(2 * j), page_id(2 * j + 1));
-    id_a = page_id(2 * (kRing - 1));
-    id_b = page_id(2 * (kRing - 1) + 1);
+    for (int j = 0; j < kRing - 1; ++j) dma_step(j, page_id_raw(2 * j), page_id_raw(2 * j + 1));
+    id_a = page_id_raw(2 * (kRing - 1));
+    id_b = page_id_raw(2 * (kRing - 1) + 1);
     wait_vmcnt<(kRing - 3) * kStepLoads>();
     __syncthreads();
-    {
-        float mx[kNCT];
-        scores(std::true_type{}, 0, x, mx);
-        raise_max(mx);
-    }
+    scores(std::true_type{}, 0, x);
+    raise_max(x);
 
-    // ---- iteration i: weights of step i, scores of step i+1, O += V(i) P(i) ----
-    auto iteration = [&](auto masked, int32_t i) {
-        const bool has_next = i + 1 < n_steps;
+    // ---- iteration i: scores of step i+1 (into xn) and weights of step i (from xc) side by
+    // side, then O += V(i) P(i) while the new scores are tested against the running maxima.
+    // kMask: causal / end-of-sequence masking (needed from the first edge step on);
+    // kLast: there is no step i+1. ----
+    auto iteration = [&](auto masked, auto last, int32_t i, float (&xc)[kNCT][8], float (&xn)[kNCT][8]) {
+        constexpr bool kMask = decltype(masked)::value;
+        constexpr bool kLast = decltype(last)::value;
         // step i+kRing-1 goes into the slot step i-1 left (its last reader finished before the
         // barrier that ended iteration i-1)
         dma_step(i + kRing - 1, id_a, id_b);
-        id_a = page_id(2 * (i + kRing));
-        id_b = page_id(2 * (i + kRing) + 1);
+        id_a = page_id_raw(2 * (i + kRing));          // consumed by the next iteration
+        id_b = page_id_raw(2 * (i + kRing) + 1);
 
+        if (!kLast) scores(masked, i + 1, xn);
         bf16x8 pb[kNCT];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
             float p[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(x[c][j] - m_run[c]);
+            for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(xc[c][j], scale_log2e, -m_run[c]));
             const u32x4 pk = { pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]) };
             pb[c] = __builtin_bit_cast(bf16x8, pk);
         }
-        float mx[kNCT];
-        if (has_next) scores(masked, i + 1, x, mx);
         const u32x2* vA0 = (const u32x2*)&lds_v[i % kRing][0];
         const u32x2* vA1 = (const u32x2*)&lds_v[i % kRing][kUnits];
 #pragma unroll
@@ -273,7 +281,7 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         // them so that a zero weight times the slot stays zero.  Lane holds tokens
         // 4*(lane/16) .. +4 of each page.
         uint32_t vm[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
-        if (decltype(masked)::value && (i + 1) * kKeysPerStep > n_seq_keys) {
+        if (kMask && (i + 1) * kKeysPerStep > n_seq_keys) {
             const int32_t v0 = n_seq_keys - (i * kKeysPerStep + (lane >> 4) * 4);
             const int32_t v1 = v0 - kPage;
             vm[0] = v0 >= 2 ? 0xffffffffu : (v0 == 1 ? 0x0000ffffu : 0u);
@@ -285,21 +293,48 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
         for (int dt = 0; dt < D / 16; ++dt) {
             const u32x2 a0 = vA0[dt * 64 + lane], a1 = vA1[dt * 64 + lane];
             u32x4 av = { a0[0], a0[1], a1[0], a1[1] };
-            if (decltype(masked)::value) { av[0] &= vm[0]; av[1] &= vm[1]; av[2] &= vm[2]; av[3] &= vm[3]; }
+            if (kMask) { av[0] &= vm[0]; av[1] &= vm[1]; av[2] &= vm[2]; av[3] &= vm[3]; }
             const bf16x8 va = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
             for (int c = 0; c < kNCT; ++c)
                 o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[c], o[c][dt], 0, 0, 0);
         }
-        if (has_next) raise_max(mx);
+        if (!kMask && !kLast) {
+            // steady state: ask the scheduler to pair every MFMA with vector-ALU work (the
+            // exp / convert of step i under the score MFMAs of step i+1, the read-out and the
+            // threshold test of the new scores under the P.V MFMAs)
+#pragma unroll
+            for (int r = 0; r < 8 * (D / 32); ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
+            }
+#pragma unroll
+            for (int r = 0; r < 4 + 4 * (D / 16); ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+        }
+        if (!kLast) raise_max(xn);
         // K(i+2) and V(i+1) must have landed before the next iteration reads them: all but the
         // copies of the last kRing-3 steps issued
         wait_vmcnt<(kRing - 3) * kStepLoads>();
         __syncthreads();
     };
+    float xb[kNCT][8];
     int32_t i = 0;
-    for (; i + 1 < first_edge; ++i) iteration(std::false_type{}, i);      // step i+1 is fully visible
-    for (; i < n_steps; ++i) iteration(std::true_type{}, i);
+    // steady state in pairs, the scores ping-ponging between x and xb; step i+2 fully visible
+    for (; i + 2 < first_edge; i += 2) {
+        iteration(std::false_type{}, std::false_type{}, i, x, xb);
+        iteration(std::false_type{}, std::false_type{}, i + 1, xb, x);
+    }
+    for (; i + 1 < n_steps; ++i) {
+        iteration(std::true_type{}, std::false_type{}, i, x, xb);
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) x[c][j] = xb[c][j];
+    }
+    iteration(std::true_type{}, std::true_type{}, i, x, xb);
     wait_vmcnt<0>();                                   // no copy may outlive the workgroup's LDS
 
     // ---- normalise and store: lane holds 4 consecutive features of one query row per tile ----
