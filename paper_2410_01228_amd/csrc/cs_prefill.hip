@@ -3,9 +3,10 @@
 // term grows as P(P+C); chunked prefill).  Compute-bound, so the tiles run on the bf16
 // matrix cores with an fp32 online softmax.
 //
-// A workgroup (4 wavefronts) owns one kv head and a tile of TQ consecutive chunk tokens
-// with all G query heads that share the kv head: 16 "column tiles" of 16 query rows
-// (16 tokens of one head), 4 per wavefront.  It walks the sequence's keys 32 at a time
+// A workgroup (4 wavefronts) owns one kv head and kTileCols "column tiles" of 16 query rows
+// each (16 consecutive chunk tokens of one of the G query heads sharing the kv head; tiles
+// are numbered token-block major, so any G packs without waste), kNCT per wavefront; two
+// workgroups share a CU.  It walks the sequence's keys 32 at a time
 // (two pages).  The pages' K and V blocks are copied global -> LDS by LDS-DMA loads into a
 // ring of slots several steps ahead (one barrier per step, no staging registers); every
 // wavefront reads them back as MFMA operands -- the
@@ -33,7 +34,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kPrefillWaves = 4;
 constexpr int kPrefillThreads = kPrefillWaves * 64;
-constexpr int kNCT = 4;                       // column tiles per wavefront
+constexpr int kNCT = 2;                       // column tiles per wavefront
 constexpr int kKeysPerStep = 32;              // two pages
 constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
 constexpr int kRing = 4;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
@@ -63,11 +64,19 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, v);
 }
 
-// Tokens per workgroup tile for a group size G: as many 16-token blocks as fit 16 column tiles.
-__host__ __device__ inline int32_t prefill_tile_tokens(int32_t G) { return 16 * (16 / G); }
+constexpr int kTileCols = kPrefillWaves * kNCT;   // column tiles per workgroup
+
+// Workgroup slots.  A sequence with q new tokens has ceil(q/16) * G column tiles, numbered
+// token-block major (ct = token_block * G + head), and needs ceil(that / kTileCols)
+// workgroups.  Slots are dealt without a prefix sum over tile counts: sequence s starts at
+//   start(s) = floor((cu_q_lens[s] + 16 s) * G / (16 * kTileCols)) + s,
+// which is strictly increasing and leaves every sequence at least as many slots as it needs.
+__host__ __device__ inline int64_t prefill_slot_start(int32_t cu_q, int32_t s, int32_t G) {
+    return ((int64_t)cu_q + 16ll * s) * G / (16 * kTileCols) + s;
+}
 
 template <int D>
-__global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
+__global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G, int32_t S,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
@@ -81,28 +90,28 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     __shared__ u32x4 lds_k[kRing][kStepUnits];
     __shared__ u32x4 lds_v[kRing][kStepUnits];
 
-    const int32_t TQ = prefill_tile_tokens(G);
     const int32_t g = blockIdx.x;
     const int32_t b = blockIdx.y;
-    // sequence owning tile slot b: slots are dealt as start[s] = cu_q_lens[s] / TQ + s, which
-    // leaves every sequence at least ceil(q_s / TQ) slots; find the largest s with start[s] <= b
+    // sequence owning slot b: the largest s with start(s) <= b
     int32_t lo = 0, hi = S;
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
-        if (cu_q_lens[mid] / TQ + mid <= b) lo = mid; else hi = mid;
+        if (prefill_slot_start(cu_q_lens[mid], mid, G) <= b) lo = mid; else hi = mid;
     }
     const int32_t s = lo;
     const int32_t t_seq = cu_q_lens[s];
     const int32_t q_len = cu_q_lens[s + 1] - t_seq;
     if (q_len <= 1) return;                            // decode and idle sequences: other path
-    const int32_t tok0 = (b - (t_seq / TQ + s)) * TQ;  // first chunk token of this tile
-    if (tok0 >= q_len) return;
+    const int32_t n_ct = ((q_len + 15) >> 4) * G;      // column tiles of the sequence
+    const int32_t ct0 = (int32_t)(b - prefill_slot_start(t_seq, s, G)) * kTileCols;
+    if (ct0 >= n_ct) return;
+    const int32_t tb_min = ct0 / G;                    // first and last token block of the tile
+    const int32_t tb_max = (min(ct0 + kTileCols, n_ct) - 1) / G;
     const int32_t C = ctx_lens[s];
-    const int32_t n_tok = min(TQ, q_len - tok0);
     const int32_t n_seq_keys = C + q_len;              // keys the sequence holds after the append
-    const int32_t n_keys = C + tok0 + n_tok;           // keys visible to the tile's last token
+    const int32_t n_keys = C + min(q_len, (tb_max + 1) * 16);   // keys visible to the tile's last token
     const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
-    const int32_t first_edge = (C + tok0 + 1) / kKeysPerStep;   // steps before it need no causal mask
+    const int32_t first_edge = (C + tb_min * 16 + 1) / kKeysPerStep;   // steps before it need no causal mask
     const int32_t n_pages = min((n_seq_keys + kPage - 1) >> 4, max_blocks);
     const int32_t* table = block_tables + (int64_t)s * max_blocks;
     const int32_t Hq = Hkv * G;
@@ -115,10 +124,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
-        const int32_t ct = wave * kNCT + c;
+        const int32_t ct = ct0 + wave * kNCT + c;
         const int32_t tb = ct / G, hh = ct - tb * G;
-        const int32_t tl = tok0 + tb * 16 + (lane & 15);     // chunk-local token of this column
-        const bool valid = tb * 16 < TQ && tl < q_len;
+        const int32_t tl = tb * 16 + (lane & 15);            // chunk-local token of this column
+        const bool valid = ct < n_ct && tl < q_len;
         pos_q[c] = C + tl;
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
@@ -304,12 +313,12 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
             // exp / convert of step i under the score MFMAs of step i+1, the read-out and the
             // threshold test of the new scores under the P.V MFMAs)
 #pragma unroll
-            for (int r = 0; r < 8 * (D / 32); ++r) {
+            for (int r = 0; r < 2 * kNCT * (D / 32); ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
                 __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
             }
 #pragma unroll
-            for (int r = 0; r < 4 + 4 * (D / 16); ++r) {
+            for (int r = 0; r < kNCT + kNCT * (D / 16); ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
             }
@@ -340,10 +349,10 @@ __global__ __launch_bounds__(kPrefillThreads, 1) void prefill_kernel(
     // ---- normalise and store: lane holds 4 consecutive features of one query row per tile ----
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
-        const int32_t ct = wave * kNCT + c;
+        const int32_t ct = ct0 + wave * kNCT + c;
         const int32_t tb = ct / G, hh = ct - tb * G;
-        const int32_t tl = tok0 + tb * 16 + (lane & 15);
-        if (tb * 16 < TQ && tl < q_len) {
+        const int32_t tl = tb * 16 + (lane & 15);
+        if (ct < n_ct && tl < q_len) {
             const float inv = 1.f / lacc[c][0];
             uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + (lane >> 4) * 4;
 #pragma unroll
@@ -360,11 +369,11 @@ int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
                    const void* q, void* out, int32_t Hq, float scale, hipStream_t st)
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
-    const int32_t TQ = prefill_tile_tokens(G);
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     const float scale_log2e = scale * 1.4426950408889634f;
-    const uint32_t slots = (uint32_t)(b.num_tokens / TQ + b.num_seqs);
-    if (slots > 65535u) return CS_ERR_UNSUPPORTED;
+    const int64_t slots64 = prefill_slot_start(b.num_tokens, b.num_seqs, G);
+    if (slots64 > 65535) return CS_ERR_UNSUPPORTED;
+    const uint32_t slots = (uint32_t)slots64;
     dim3 grid((uint32_t)Hkv, slots);
     if (D == 128)
         hipLaunchKernelGGL(prefill_kernel<128>, grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
