@@ -37,7 +37,7 @@ constexpr int kPrefillThreads = kPrefillWaves * 64;
 constexpr int kNCT = 2;                       // column tiles per wavefront
 constexpr int kKeysPerStep = 32;              // two pages
 constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
-constexpr int kRing = 4;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
+constexpr int kRing = 5;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
 
 // s_waitcnt on the vector-memory counter alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
@@ -158,8 +158,19 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     // lie inside one page.  A page the sequence does not have is replaced by page 0 of the
     // pool: every step issues the same number of instructions (the vmcnt arithmetic below
     // relies on it) and whatever lands is masked where it is used. ----
+    // Page ids travel in a lane register: idvec holds table[idbase + lane] for 64 consecutive
+    // pages and a step's two ids are read out with v_readlane, so the steady state has no
+    // scalar-memory load (whose unordered return would turn every LDS wait into a full
+    // lgkmcnt(0)).  The register is refilled once per 32 steps.
+    int32_t idbase = 0;
+    int32_t idvec = lane < n_pages ? table[lane] : 0;
     auto page_id_raw = [&](int32_t pg) -> int32_t {    // wave-uniform table entry, unchecked
-        return pg < n_pages ? __builtin_amdgcn_readfirstlane(table[pg]) : 0;
+        if (pg - idbase >= 64) {                       // pg only ever grows, two pages per step
+            idbase += 64;
+            idvec = idbase + lane < n_pages ? table[idbase + lane] : 0;
+            asm volatile("" : "+v"(idvec));            // take the load's wait here, not at every readlane
+        }
+        return __builtin_amdgcn_readlane(idvec, pg - idbase);
     };
     auto checked = [&](int32_t id) -> int32_t { return (id < 0 || id >= num_pages) ? 0 : id; };
     auto dma_step = [&](int32_t step, int32_t id0, int32_t id1) {
@@ -309,18 +320,23 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
                 o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[c], o[c][dt], 0, 0, 0);
         }
         if (!kMask && !kLast) {
-            // steady state: ask the scheduler to pair every MFMA with vector-ALU work (the
-            // exp / convert of step i under the score MFMAs of step i+1, the read-out and the
-            // threshold test of the new scores under the P.V MFMAs)
+            // steady state: tell the scheduler the order we want.  K operands leave LDS first;
+            // the exp / convert work of step i starts while they are in flight and continues
+            // under the score MFMAs of step i+1; the V operands are fetched under those MFMAs
+            // too; the threshold test of the new scores runs under the P.V MFMAs.
+            constexpr int kQK = 2 * kNCT * (D / 32), kPV = kNCT + kNCT * (D / 16);
+            __builtin_amdgcn_sched_group_barrier(0x100, 2 * (D / 32), 0);        // K: ds_read_b128
+            __builtin_amdgcn_sched_group_barrier(0x002, 6 * kNCT, 0);            // VALU
 #pragma unroll
-            for (int r = 0; r < 2 * kNCT * (D / 32); ++r) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-                __builtin_amdgcn_sched_group_barrier(0x002, 3, 0);   // 3 VALU
+            for (int r = 0; r < kQK; ++r) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // 1 MFMA
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);               // 2 VALU
+                if (r < D / 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // V: one LDS read
             }
 #pragma unroll
-            for (int r = 0; r < kNCT + kNCT * (D / 16); ++r) {
+            for (int r = 0; r < kPV; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
             }
         }
         if (!kLast) raise_max(xn);
