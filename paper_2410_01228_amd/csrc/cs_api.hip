@@ -50,37 +50,66 @@ int validate_batch(const cs_kv_pool* pool, const cs_batch* b) {
     return CS_OK;
 }
 
-DecodePlan plan_decode(const cs_batch* b, int32_t Hkv) {
+DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
     DecodePlan p = {};
+    int32_t max_keys = 0, min_keys = 2147483647;
     for (int32_t s = 0; s < b->num_seqs; ++s) {
         const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
         if (ql == 1) {
             const int32_t n = b->h_ctx_lens[s] + 1;
             ++p.num_decode;
             p.decode_keys += n;
-            if (n > p.max_decode_keys) p.max_decode_keys = n;
+            if (n > max_keys) max_keys = n;
+            if (n < min_keys) min_keys = n;
         } else if (ql > 1) {
             ++p.num_prefill;
         }
     }
     p.split_tokens = 256;
-    p.max_splits = 1;
     if (p.num_decode == 0) return p;
     int32_t split = g_forced_split.load();
     if (split <= 0) {
-        // largest power-of-two split (>= 256 keys) that still leaves ~16 workgroups per CU
-        split = 256;
-        const int64_t work = p.decode_keys * Hkv;
-        while (split < 16384 && work / (split * 2) >= 4096) split *= 2;
+        // Few, long work items stream best: each pays its start-up latencies once, and when no
+        // sequence is cut the plan and merge kernels are not launched at all.  Start from items
+        // of about 2 MiB of K/V per kv head and halve only until the grid has enough workgroups:
+        // four per CU, or two per CU when the sequences are of nearly equal length (then the
+        // items are too, and nothing straggles).
+        const int32_t cap = head_dim >= 128 ? 4096 : 8192;
+        const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
+        const int64_t need = uniform ? 512 : 1024;
+        for (split = cap; split > 256; split /= 2) {
+            int64_t items = 0;
+            for (int32_t s = 0; s < b->num_seqs; ++s)
+                if (b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s] == 1)
+                    items += decode_num_splits(b->h_ctx_lens[s] + 1, split);
+            if (items * Hkv >= need) break;
+        }
     }
     p.split_tokens = split;
-    p.max_splits = (p.max_decode_keys + split - 1) / split;
+    for (int32_t s = 0; s < b->num_seqs; ++s) {
+        if (b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s] != 1) continue;
+        const int32_t k = decode_num_splits(b->h_ctx_lens[s] + 1, split);
+        p.total_items += k;
+        if (k > 1) ++p.num_multi;
+    }
     return p;
 }
 
-size_t decode_workspace_bytes(const DecodePlan& p, int32_t S, int32_t Hq, int32_t D) {
-    if (p.num_decode == 0 || p.max_splits <= 1) return 0;
-    return (size_t)S * p.max_splits * Hq * (D + 2) * sizeof(float);
+static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
+
+DecodeWorkspace decode_workspace(const DecodePlan& p, int32_t S, int32_t Hq, int32_t D) {
+    DecodeWorkspace w = {};
+    if (p.num_decode == 0) return w;
+    size_t off = 0;
+    w.items = off;    off += align16((size_t)p.total_items * 8 * sizeof(int32_t));
+    w.cu_items = off; off += align16((size_t)(S + 1) * sizeof(int32_t));
+    w.multi = off;    off += align16((size_t)(p.num_multi + 1) * sizeof(int32_t));
+    // partials are indexed by item; only items of multi-item sequences are ever written
+    const size_t part_items = p.num_multi ? (size_t)p.total_items : 0;
+    w.part_ml = off;  off += align16(part_items * Hq * 2 * sizeof(float));
+    w.part_o = off;   off += align16(part_items * Hq * D * sizeof(float));
+    w.total = off;
+    return w;
 }
 
 }  // namespace cs
@@ -116,8 +145,8 @@ static int attention_shape_ok(int32_t Hq, int32_t Hkv, int32_t D) {
 size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D) {
     if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return 0;
     if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return 0;
-    const DecodePlan p = plan_decode(batch, Hkv);
-    return decode_workspace_bytes(p, batch->num_seqs, Hq, D);
+    const DecodePlan p = plan_decode(batch, Hkv, D);
+    return decode_workspace(p, batch->num_seqs, Hq, D).total;
 }
 
 int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
@@ -133,8 +162,8 @@ int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_bat
     if (batch->num_tokens == 0) return CS_OK;
     if (!q || !out || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return CS_ERR_INVALID_ARG;
     if (!(softmax_scale > 0.f) || softmax_scale > 3.0e38f) return CS_ERR_INVALID_ARG;   // positive, finite
-    const DecodePlan plan = plan_decode(batch, pool->num_kv_heads);
-    const size_t need = decode_workspace_bytes(plan, batch->num_seqs, Hq, pool->head_dim);
+    const DecodePlan plan = plan_decode(batch, pool->num_kv_heads, pool->head_dim);
+    const size_t need = decode_workspace(plan, batch->num_seqs, Hq, pool->head_dim).total;
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;

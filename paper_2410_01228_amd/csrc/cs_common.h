@@ -22,18 +22,35 @@ inline int check_launch(const char* what) {
 int validate_pool(const cs_kv_pool* pool);
 int validate_batch(const cs_kv_pool* pool, const cs_batch* batch);
 
+// Split arithmetic of the decode path, shared by the host plan and the kernels.  A decode
+// sequence with n keys is cut into round(n / split) pieces (at least one) of equal,
+// page-aligned length, so no piece is a sliver.
+__host__ __device__ inline int32_t decode_num_splits(int32_t n_keys, int32_t split) {
+    const int32_t k = (n_keys + split / 2) / split;
+    return k < 1 ? 1 : k;
+}
+__host__ __device__ inline int32_t decode_chunk_keys(int32_t n_keys, int32_t n_splits) {
+    const int32_t c = (n_keys + n_splits - 1) / n_splits;
+    return (c + kPage - 1) & ~(kPage - 1);
+}
+
 // Plan of the decode path, a pure function of the host lengths (used by both the
 // workspace query and the launch).
 struct DecodePlan {
     int32_t num_decode;        // sequences with exactly one new token
     int32_t num_prefill;       // sequences with more than one new token
-    int32_t max_decode_keys;   // max over decode sequences of ctx + 1
-    int32_t split_tokens;      // keys per split (multiple of 16)
-    int32_t max_splits;        // ceil(max_decode_keys / split_tokens)
+    int32_t split_tokens;      // target keys per work item (multiple of 16)
+    int32_t total_items;       // sum over decode sequences of their split count
+    int32_t num_multi;         // decode sequences cut into more than one item
     int64_t decode_keys;       // total keys read by decode sequences
 };
-DecodePlan plan_decode(const cs_batch* batch, int32_t num_kv_heads);
-size_t decode_workspace_bytes(const DecodePlan& p, int32_t num_seqs, int32_t num_q_heads, int32_t head_dim);
+DecodePlan plan_decode(const cs_batch* batch, int32_t num_kv_heads, int32_t head_dim);
+// Workspace layout (all 16-byte aligned): work items | per-sequence item offsets |
+// multi-item sequence list | partial (max, sum) | partial outputs.
+struct DecodeWorkspace {
+    size_t items, cu_items, multi, part_ml, part_o, total;
+};
+DecodeWorkspace decode_workspace(const DecodePlan& p, int32_t num_seqs, int32_t num_q_heads, int32_t head_dim);
 
 // Kernel launchers (defined next to their kernels).
 int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,

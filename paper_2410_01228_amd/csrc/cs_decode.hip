@@ -1,6 +1,6 @@
 // Decode path of the mixed-batch paged attention: one new token per sequence attends its
 // whole cached context (paper Sec. 4.2, memory-access term: the KV cache is streamed from
-// HBM once).  Split-KV scheme: a workgroup takes one (sequence, kv head, key split), its
+// HBM once).  Split-KV scheme: a workgroup takes one (sequence, kv head, key range), its
 // four wavefronts stream the split's pages straight from HBM into MFMA operand registers
 // (the page format IS the operand layout, so there is no LDS staging and no shuffle),
 // keep an online softmax per query head in fp32, and leave one partial (max, sum,
@@ -116,26 +116,99 @@ __device__ __forceinline__ void process_page(WaveState<D>& st, const PageRegs<D>
     }
 }
 
-// grid = (max_splits, Hkv, S); block = 4 wavefronts.
-template <int D>
+// Work items.  A plan kernel turns the batch's lengths into a compact list of
+// (sequence, key range) items, so the split kernel launches exactly one workgroup per item
+// and kv head: no workgroup starts only to find it has nothing to do, and a long sequence
+// and a short one both break into pieces of about the same size.
+struct DecodeItem {
+    int32_t seq, token, n_keys, key_begin, key_end, n_splits, pad0, pad1;   // 32 bytes
+};
+
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(
+    int32_t S, const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    int32_t split_tokens, int32_t total_items, int32_t num_multi,
+    DecodeItem* __restrict__ items, int32_t* __restrict__ cu_items, int32_t* __restrict__ multi)
+{
+    // total_items / num_multi are what the host planned from its copies of the lengths; they
+    // bound every write here should the device arrays disagree with those copies
+    __shared__ int32_t sh_items[kPlanThreads], sh_multi[kPlanThreads];
+    const int tid = threadIdx.x;
+    const int32_t per = (S + kPlanThreads - 1) / kPlanThreads;
+    const int32_t s0 = min(S, tid * per), s1 = min(S, s0 + per);
+    int32_t n_items = 0, n_multi = 0;
+    for (int32_t s = s0; s < s1; ++s) {
+        if (cu_q_lens[s + 1] - cu_q_lens[s] != 1) continue;
+        const int32_t k = decode_num_splits(ctx_lens[s] + 1, split_tokens);
+        n_items += k;
+        n_multi += k > 1;
+    }
+    sh_items[tid] = n_items;
+    sh_multi[tid] = n_multi;
+    __syncthreads();
+    for (int off = 1; off < kPlanThreads; off <<= 1) {           // inclusive scan
+        const int32_t a = tid >= off ? sh_items[tid - off] : 0;
+        const int32_t b = tid >= off ? sh_multi[tid - off] : 0;
+        __syncthreads();
+        sh_items[tid] += a;
+        sh_multi[tid] += b;
+        __syncthreads();
+    }
+    int32_t item = sh_items[tid] - n_items, m = sh_multi[tid] - n_multi;   // exclusive
+    for (int32_t s = s0; s < s1; ++s) {
+        cu_items[s] = item;
+        const int32_t t = cu_q_lens[s];
+        if (cu_q_lens[s + 1] - t != 1) continue;
+        const int32_t n = ctx_lens[s] + 1;
+        const int32_t k = decode_num_splits(n, split_tokens);
+        const int32_t chunk = decode_chunk_keys(n, k);
+        for (int32_t i = 0; i < k; ++i) {
+            DecodeItem it;
+            it.seq = s; it.token = t; it.n_keys = n;
+            it.key_begin = min(n, i * chunk);
+            it.key_end = min(n, (i + 1) * chunk);
+            it.n_splits = k; it.pad0 = 0; it.pad1 = 0;
+            if (item + i < total_items) items[item + i] = it;
+        }
+        item += k;
+        if (k > 1 && m < num_multi) multi[m++] = s;
+    }
+    if (tid == kPlanThreads - 1) cu_items[S] = sh_items[tid];
+}
+
+// grid = total_items * Hkv workgroups, kv head fastest (the heads of one page are neighbours
+// in memory, so neighbouring workgroups share DRAM pages and translations); block = 4
+// wavefronts.  kIdentity: no sequence is cut, so the
+// item list is not built at all: workgroup x is sequence x (and leaves at once if that
+// sequence is not a decode).
+template <int D, bool kIdentity>
 __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const DecodeItem* __restrict__ items,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out,
-    float scale_log2e, int32_t split_tokens, int32_t max_splits,
-    float* __restrict__ part_o, float* __restrict__ part_ml)
+    float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
-    const int32_t s = blockIdx.z, g = blockIdx.y, split = blockIdx.x;
-    const int32_t t = cu_q_lens[s];
-    if (cu_q_lens[s + 1] - t != 1) return;                       // not a decode sequence
-    const int32_t n_keys = ctx_lens[s] + 1;
-    const int32_t key_begin = split * split_tokens;
-    if (key_begin >= n_keys) return;
-    const int32_t key_end = min(n_keys, key_begin + split_tokens);
-    const int32_t page_begin = key_begin >> 4;
-    const int32_t page_end = min((key_end + kPage - 1) >> 4, max_blocks);
+    const int32_t item = blockIdx.x / Hkv, g = blockIdx.x - item * Hkv;
+    DecodeItem it;
+    if (kIdentity) {
+        it.seq = item;
+        it.token = cu_q_lens[item];
+        if (cu_q_lens[item + 1] - it.token != 1) return;
+        it.n_keys = ctx_lens[item] + 1;
+        it.key_begin = 0;
+        it.key_end = it.n_keys;
+        it.n_splits = 1;
+    } else {
+        it = items[item];
+    }
+    const int32_t s = it.seq, t = it.token, n_keys = it.n_keys;
+    const int32_t page_begin = it.key_begin >> 4;
+    // an item can come out empty when a short sequence is cut very finely
+    const int32_t page_end = it.key_end > it.key_begin ? min((it.key_end + kPage - 1) >> 4, max_blocks) : page_begin;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int32_t* table = block_tables + (int64_t)s * max_blocks;
@@ -210,41 +283,41 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
         float L = 0.f, O = 0.f;
 #pragma unroll
         for (int w = 0; w < kDecodeWaves; ++w) {
-            const float f = exp2f(sh_m[w][head] - M);            // 0 for a wavefront without pages
+            const float mw = sh_m[w][head];
+            const float f = mw == -INFINITY ? 0.f : exp2f(mw - M);     // a wavefront without pages
             L += sh_l[w][head] * f;
             O += sh_o[w][head][d] * f;
         }
         const int32_t hq = g * G + head;
-        if (max_splits == 1) {
+        if (it.n_splits == 1) {
             const float r = O / L;
             out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(pack_bf16(r, 0.f) & 0xffffu);
         } else {
-            const int64_t slot = ((int64_t)s * max_splits + split) * Hq + hq;
+            const int64_t slot = (int64_t)item * Hq + hq;
             part_o[slot * D + d] = O;
             if (d == 0) { part_ml[slot * 2] = M; part_ml[slot * 2 + 1] = L; }
         }
     }
 }
 
-// Merge of the split partials: grid = (Hq, S), block = D lanes.
+// Merge of the split partials of the sequences that were cut: grid = (Hq, num_multi),
+// block = D lanes.
 template <int D>
 __global__ __launch_bounds__(D) void decode_merge_kernel(
-    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
-    int32_t Hq, int32_t split_tokens, int32_t max_splits,
+    const int32_t* __restrict__ multi, const int32_t* __restrict__ cu_items,
+    const int32_t* __restrict__ cu_q_lens, int32_t Hq,
     const float* __restrict__ part_o, const float* __restrict__ part_ml, uint16_t* __restrict__ out)
 {
-    const int32_t s = blockIdx.y, hq = blockIdx.x, d = threadIdx.x;
+    const int32_t s = multi[blockIdx.y], hq = blockIdx.x, d = threadIdx.x;
     const int32_t t = cu_q_lens[s];
-    if (cu_q_lens[s + 1] - t != 1) return;
-    const int32_t n_keys = ctx_lens[s] + 1;
-    const int32_t n_splits = min(max_splits, (n_keys + split_tokens - 1) / split_tokens);
-    const int64_t slot0 = (int64_t)s * max_splits * Hq + hq;
+    const int32_t i0 = cu_items[s], i1 = cu_items[s + 1];
     float M = -INFINITY;
-    for (int i = 0; i < n_splits; ++i) M = fmaxf(M, part_ml[(slot0 + (int64_t)i * Hq) * 2]);
+    for (int32_t i = i0; i < i1; ++i) M = fmaxf(M, part_ml[((int64_t)i * Hq + hq) * 2]);
     float L = 0.f, O = 0.f;
-    for (int i = 0; i < n_splits; ++i) {
-        const int64_t slot = slot0 + (int64_t)i * Hq;
-        const float f = exp2f(part_ml[slot * 2] - M);
+    for (int32_t i = i0; i < i1; ++i) {
+        const int64_t slot = (int64_t)i * Hq + hq;
+        const float mi = part_ml[slot * 2];
+        const float f = mi == -INFINITY ? 0.f : exp2f(mi - M);
         L += part_ml[slot * 2 + 1] * f;
         O += part_o[slot * D + d] * f;
     }
@@ -258,19 +331,35 @@ int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, cons
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     const float scale_log2e = scale * 1.4426950408889634f;
-    float* part_o = (float*)workspace;
-    float* part_ml = part_o + (int64_t)b.num_seqs * plan.max_splits * Hq * D;
-    dim3 grid((uint32_t)plan.max_splits, (uint32_t)Hkv, (uint32_t)b.num_seqs);
-    dim3 mgrid((uint32_t)Hq, (uint32_t)b.num_seqs);
-#define CS_LAUNCH_DECODE(DD)                                                                          \
-    hipLaunchKernelGGL(decode_split_kernel<DD>, grid, dim3(kDecodeThreads), 0, st, layer_base,        \
+    const DecodeWorkspace w = decode_workspace(plan, b.num_seqs, Hq, D);
+    char* ws = (char*)workspace;
+    DecodeItem* items = (DecodeItem*)(ws + w.items);
+    int32_t* cu_items = (int32_t*)(ws + w.cu_items);
+    int32_t* multi = (int32_t*)(ws + w.multi);
+    float* part_ml = (float*)(ws + w.part_ml);
+    float* part_o = (float*)(ws + w.part_o);
+    const bool identity = plan.num_multi == 0;
+    if (!identity)
+        hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, b.num_seqs, b.ctx_lens,
+                           b.cu_q_lens, plan.split_tokens, plan.total_items, plan.num_multi, items, cu_items, multi);
+    dim3 grid((uint32_t)(identity ? b.num_seqs : plan.total_items) * (uint32_t)Hkv);
+    dim3 mgrid((uint32_t)Hq, (uint32_t)plan.num_multi);
+#define CS_LAUNCH_DECODE(DD, ID)                                                                      \
+    hipLaunchKernelGGL((decode_split_kernel<DD, ID>), grid, dim3(kDecodeThreads), 0, st, layer_base,  \
                        pool.page_stride, pool.num_pages, Hkv, G, b.block_tables, b.max_blocks_per_seq, \
-                       b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,      \
-                       plan.split_tokens, plan.max_splits, part_o, part_ml);                          \
-    if (plan.max_splits > 1)                                                                          \
-        hipLaunchKernelGGL(decode_merge_kernel<DD>, mgrid, dim3(DD), 0, st, b.ctx_lens, b.cu_q_lens,  \
-                           Hq, plan.split_tokens, plan.max_splits, part_o, part_ml, (uint16_t*)out);
-    if (D == 128) { CS_LAUNCH_DECODE(128) } else { CS_LAUNCH_DECODE(64) }
+                       items, b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out,            \
+                       scale_log2e, part_o, part_ml);
+    if (identity) {
+        if (D == 128) { CS_LAUNCH_DECODE(128, true) } else { CS_LAUNCH_DECODE(64, true) }
+    } else {
+        if (D == 128) { CS_LAUNCH_DECODE(128, false) } else { CS_LAUNCH_DECODE(64, false) }
+        if (D == 128)
+            hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(128), 0, st, multi, cu_items,
+                               b.cu_q_lens, Hq, part_o, part_ml, (uint16_t*)out);
+        else
+            hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(64), 0, st, multi, cu_items,
+                               b.cu_q_lens, Hq, part_o, part_ml, (uint16_t*)out);
+    }
 #undef CS_LAUNCH_DECODE
     return check_launch("decode kernels");
 }
