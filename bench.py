@@ -155,43 +155,50 @@ def time_legs(legs, steps, warmup):
     return wall / steps
 
 
-def cpu_baseline(b, max_seconds=20.0):
+def cpu_baseline(b, min_seconds=10.0, max_seconds=30.0):
     """The oracle as it stands, timed on this host on a bounded sample of the workload's
-    sequences (inputs regenerated on the CPU with the same recipe)."""
-    import numpy as np
+    sequences (inputs regenerated on the CPU with the same recipe; generation is not timed).
+    The sample is swept repeatedly until about 10 s of oracle time has accumulated."""
     import torch
     from oracle import attention
     from paper_2410_01228_amd import synth
     sh = b.shape
     order = [s for s in range(b.S) if int(b.q_lens[s]) > 0]
-    # cost model of the plain loops: 4*Hq*D flop per (query, key) pair at roughly 1 GFLOP/s/thread
     threads = attention.num_threads()
-    budget = max_seconds * 1.0e9 * threads
-    pick, cost = [], 0.0
-    stride = max(1, len(order) // 16)
-    for s in order[::stride] + [x for i, x in enumerate(order) if i % stride]:
+    # bound the sample by memory (fp32 K and V of the picked sequences <= ~1.5 GB) and by a
+    # rough cost model of the plain loops (4*Hq*D flop per (query, key) pair, ~0.5 GFLOP/s/thread)
+    budget_flop = max_seconds * 0.5e9 * threads
+    budget_bytes = 1.5e9
+    stride = max(1, len(order) // 32)
+    pick, cost, mem = [], 0.0, 0.0
+    for s in order[::stride]:
         c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
         w = 4.0 * sh.Hq * sh.D * (ql * c + ql * (ql + 1) / 2)
-        if pick and cost + w > budget:
+        m = 2.0 * (c + ql) * sh.Hkv * sh.D * 4
+        if pick and (cost + w > budget_flop or mem + m > budget_bytes):
             continue
         pick.append(s)
         cost += w
-        if len(pick) >= 64:
-            break
+        mem += m
     g = synth.generator(99)
-    tokens, secs = 0, 0.0
+    data = []
     for s in pick:
         c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
         K = synth.randn_bf16((c + ql, sh.Hkv, sh.D), g).float().numpy()
         V = synth.randn_bf16((c + ql, sh.Hkv, sh.D), g).float().numpy()
         Q = synth.randn_bf16((ql, sh.Hq, sh.D), g).float().numpy()
-        t0 = time.perf_counter()
-        attention.attention_chunk(Q, K, V, c, sh.scale)
-        secs += time.perf_counter() - t0
-        tokens += ql
+        data.append((Q, K, V, c, ql))
+    tokens, secs, sweeps = 0, 0.0, 0
+    while secs < min_seconds and sweeps < 1000:
+        for Q, K, V, c, ql in data:
+            t0 = time.perf_counter()
+            attention.attention_chunk(Q, K, V, c, sh.scale)
+            secs += time.perf_counter() - t0
+            tokens += ql
+        sweeps += 1
     return {"value": round(tokens / secs, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": "%d of %d sequences (%d tokens) of the same workload, fp64 logical attention, %.1f s"
-                      % (len(pick), len(order), tokens, secs)}
+            "sample": "%d of %d sequences (%d tokens a sweep) of the same workload, fp64 logical attention, "
+                      "%d sweeps, %.1f s" % (len(pick), len(order), sum(d[4] for d in data), sweeps, secs)}
 
 
 def read_traffic(name):
@@ -214,6 +221,9 @@ def main():
     ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
+    ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
+                    help="also run the plain copy kernel on this many GiB three times (the known-size "
+                         "reference that hardware byte counters are scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build measures ONE GPU (the kernels of one GPU's share of the path); "
@@ -225,6 +235,15 @@ def main():
     cs.lib()                                   # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
     cs.cs_set_decode_split_tokens(args.split_tokens)
+    if args.calibration_copy_gib > 0:
+        n = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
+        src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            cs.cs_debug_copy(dst, src)
+        torch.cuda.synchronize()
+        log("calibration: plain_copy_kernel moved %d bytes (read) + %d bytes (written) per launch" % (n, n))
+        del src, dst
     b, legs, detail, info = build(args.workload)
     log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
         % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))

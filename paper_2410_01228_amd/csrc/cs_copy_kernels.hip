@@ -9,12 +9,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // ------------------------------------------------------------------------------------
 // Whole-page copies (paper Sec. 5: gather scattered pages into one contiguous buffer;
 // Sec. 4.4: bring them back on resume).  One (layer, page) is contiguous in the pool, so
-// both directions are straight 16-byte-per-lane streams.  A workgroup of 256 lanes moves
-// kChunk bytes: all loads are issued before the first store so each lane keeps
-// kChunk / 4096 independent 16-byte requests in flight.
+// both directions are straight 16-byte-per-lane streams.  A workgroup is a single wavefront
+// moving kChunkBytes (measured: many one-wavefront workgroups of 1 KiB sustain more HBM
+// bandwidth on this part than fewer, fatter ones with several requests per lane in flight).
 // ------------------------------------------------------------------------------------
-constexpr int kCopyThreads = 256;
-constexpr int kCopyUnroll = 4;                                   // 16 KiB per workgroup
+constexpr int kCopyThreads = 64;
+constexpr int kCopyUnroll = 1;                                   // 1 KiB per workgroup
 constexpr int kChunkBytes = kCopyThreads * 16 * kCopyUnroll;
 
 template <bool kToStaging>

@@ -1,0 +1,166 @@
+"""Parity at the stated workload sizes, in the launch configuration bench.py times.
+
+The pools are filled with seeded N(0,1) bf16 directly on the GPU (the logical K/V of a
+sequence is then, by definition, what its block table points at).  The oracle cannot redo
+whole batches of this size in seconds, so it recomputes SAMPLED sequences / query rows one by
+one from logical K/V that the test extracts with the oracle's own format code; append,
+gather and restore are compared bit for bit on sampled pages.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention, kv_layout
+from paper_2410_01228_amd import binding as cs
+from paper_2410_01228_amd import synth
+from helpers import ABS_TOL, REL_TOL, bits
+
+pytestmark = pytest.mark.gpu
+
+
+def fill(t, gen):
+    flat = t.view(-1)
+    step = 1 << 27
+    for o in range(0, flat.numel(), step):
+        n = min(step, flat.numel() - o)
+        flat[o:o + n] = torch.randn(n, generator=gen, device=t.device, dtype=torch.float32).to(torch.bfloat16)
+
+
+def logical_from_pool(pool_t, layer, bt_row, n, Hkv, D):
+    """Logical K, V (float32 [n, Hkv, D]) of one sequence: pull its pages to the host with
+    plain torch indexing and undo the page format with the oracle's reader."""
+    nb = (n + 15) // 16
+    ids = bt_row[:nb].to(torch.int64)
+    pages = pool_t[layer].index_select(0, ids.to(pool_t.device)).cpu()            # [nb, 2, Hkv, 16*D]
+    small = bits(pages).reshape(1, nb, 2, Hkv, 16 * D)
+    K, V = kv_layout.read_logical(small, 0, np.arange(nb), n)
+    return kv_layout.bf16_bits_to_f32(K), kv_layout.bf16_bits_to_f32(V)
+
+
+def run_full(index, sample_seqs, rows_per_chunk=6):
+    b = synth.CONFIGS[index]()
+    sh = b.shape
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + index)
+    L_alloc = 1                                     # attention uses one layer of the pool
+    pool = cs.Pool.empty(L_alloc, b.num_pages, sh.Hkv, sh.D)
+    fill(pool.tensor, gen)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    q = synth.randn_bf16((b.T, sh.Hq, sh.D), gen, "cuda")
+    k_new = synth.randn_bf16((b.T, sh.Hkv, sh.D), gen, "cuda")
+    v_new = synth.randn_bf16((b.T, sh.Hkv, sh.D), gen, "cuda")
+    # snapshot the pages the sampled sequences will append into, before the append
+    touched = {}
+    for s in sample_seqs:
+        c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
+        for blk in range(c // 16, (c + ql - 1) // 16 + 1):
+            pid = int(b.block_tables[s, blk])
+            touched[pid] = bits(pool.tensor[0, pid].cpu()).copy()
+    cs.cs_kv_append(pool, 0, bb, k_new, v_new)
+    out = torch.full((b.T, sh.Hq, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+    cs.cs_paged_attention_mixed(pool, 0, bb, q, out, sh.Hq, sh.scale, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all(), "non-finite output rows"
+    kn, vn = bits(k_new), bits(v_new)
+    qf = q.float().cpu().numpy()
+    worst_abs = worst_rel = 0.0
+    for s in sample_seqs:
+        c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
+        t0 = int(b.cu_q_lens[s])
+        # (1) append, bit exact on every page this sequence wrote: oracle append on the snapshot
+        blks = list(range(c // 16, (c + ql - 1) // 16 + 1))
+        small = np.stack([touched[int(b.block_tables[s, blk])] for blk in blks])[None]   # [1, nb, 2, Hkv, 16D]
+        bt_local = np.full((1, (c + ql + 15) // 16), -1, np.int32)
+        for j, blk in enumerate(blks):
+            bt_local[0, blk] = j
+        kv_layout.ref_append(small, 0, bt_local, np.array([c]), np.array([0, ql]), kn[t0:t0 + ql], vn[t0:t0 + ql])
+        for j, blk in enumerate(blks):
+            got = bits(pool.tensor[0, int(b.block_tables[s, blk])].cpu())
+            np.testing.assert_array_equal(got, small[0, j], err_msg="append, seq %d block %d" % (s, blk))
+        # (2) attention on sampled rows, from logical K/V read back through the block table
+        K, V = logical_from_pool(pool.tensor, 0, b.block_tables[s], c + ql, sh.Hkv, sh.D)
+        np.testing.assert_array_equal(K[c:], kv_layout.bf16_bits_to_f32(kn[t0:t0 + ql]))
+        rows = sorted(set([0, ql - 1] + list(np.random.default_rng(s).integers(0, ql, rows_per_chunk)))) if ql > 1 else [0]
+        ref = attention.attention_rows(qf[[t0 + r for r in rows]], np.array([c + r for r in rows]), K, V, sh.scale)
+        got = out[[t0 + r for r in rows]].float().cpu().numpy().astype(np.float64)
+        err = np.abs(got - ref).max()
+        rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
+        worst_abs, worst_rel = max(worst_abs, err), max(worst_rel, rel)
+        assert err <= ABS_TOL and rel <= REL_TOL, "seq %d: max abs %.3e rel %.3e" % (s, err, rel)
+    return worst_abs, worst_rel
+
+
+def test_llama8b_decode_full_size():
+    b = synth.config_llama8b_decode()
+    order = np.argsort(b.ctx_lens.numpy())
+    run_full(1, [int(order[0]), int(order[-1]), int(order[128]), 0, 255, 17])
+
+
+def test_qwen7b_mixed_full_size():
+    b = synth.config_qwen7b_mixed()
+    order = np.argsort(b.ctx_lens[:64].numpy())
+    run_full(2, [int(order[0]), int(order[-1]), 5, 64, 65, 66, 67])
+
+
+def test_llama70b_long_full_size():
+    b = synth.config_llama70b_long()
+    order = np.argsort(b.ctx_lens[:128].numpy())
+    run_full(3, [int(order[0]), int(order[-1]), 77, 128], rows_per_chunk=4)
+
+
+def test_qwen14b_ckpt_full_size():
+    """Workload 4 at its stated page counts on a subset of layers: gather all dirty pages of 3
+    of the 48 layers (the kernels index layers independently), restore into the spare pages,
+    rewrite the block tables, and run the mixed attention pass over the restored requests."""
+    b = synth.config_qwen14b_ckpt()
+    sh = b.shape
+    L = 3
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.BASE_SEED + 4)
+    pool = cs.Pool.empty(L, b.num_pages, sh.Hkv, sh.D)
+    fill(pool.tensor, gen)
+    dirty = b.extra["dirty_pages"]
+    fresh = [int(x) for x in b.spare_pages[:len(dirty)]]
+    d_ids = torch.tensor(dirty, dtype=torch.int32, device="cuda")
+    f_ids = torch.tensor(fresh, dtype=torch.int32, device="cuda")
+    staging = torch.empty((L, len(dirty), sh.page_elems), dtype=torch.bfloat16, device="cuda")
+    before = pool.tensor[:, dirty].cpu()
+    cs.cs_kv_ckpt_gather(pool, 0, L, d_ids, staging)
+    torch.cuda.synchronize()
+    # gather: bit exact against the oracle on sampled layers/pages (and all pages via torch equality)
+    sample = [0, 1, len(dirty) // 2, len(dirty) - 1]
+    small_pool = bits(before[:, sample]).reshape(L, len(sample), 2, sh.Hkv, 16 * sh.D)
+    want = kv_layout.ref_gather(small_pool, 0, L, list(range(len(sample))))
+    np.testing.assert_array_equal(bits(staging[:, sample].cpu()), want)
+    assert torch.equal(staging.cpu().view(torch.int16), before.reshape(L, len(dirty), -1).view(torch.int16))
+    # preempt: the old pages are given away; resume into fresh pages
+    pool.tensor[:, dirty] = float("nan")
+    cs.cs_kv_ckpt_restore(pool, 0, L, f_ids, staging)
+    torch.cuda.synchronize()
+    assert torch.equal(pool.tensor[:, fresh].cpu().view(torch.int16), before.view(torch.int16))
+    remap = torch.arange(b.num_pages, dtype=torch.int32)
+    remap[torch.tensor(dirty, dtype=torch.int64)] = torch.tensor(fresh, dtype=torch.int32)
+    bt2 = b.block_tables.clone()
+    bt2[bt2 >= 0] = remap[bt2[bt2 >= 0].to(torch.int64)]
+    # attention over the restored requests (layer 1), sampled sequences checked by the oracle
+    n_act = b.extra["n_active"]
+    bb = cs.Batch(bt2[:n_act], b.ctx_lens[:n_act], b.cu_q_lens[:n_act + 1])
+    q = synth.randn_bf16((b.T, sh.Hq, sh.D), gen, "cuda")
+    k_new = synth.randn_bf16((b.T, sh.Hkv, sh.D), gen, "cuda")
+    v_new = synth.randn_bf16((b.T, sh.Hkv, sh.D), gen, "cuda")
+    cs.cs_kv_append(pool, 1, bb, k_new, v_new)
+    out = torch.full((b.T, sh.Hq, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    cs.cs_paged_attention_mixed(pool, 1, bb, q, out, sh.Hq, sh.scale, cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D))
+    torch.cuda.synchronize()
+    assert torch.isfinite(out.float()).all()
+    qf = q.float().cpu().numpy()
+    for s in (0, 63, 64, 67):
+        c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
+        t0 = int(b.cu_q_lens[s])
+        K, V = logical_from_pool(pool.tensor, 1, bt2[s], c + ql, sh.Hkv, sh.D)
+        rows = [0, ql - 1] if ql > 1 else [0]
+        ref = attention.attention_rows(qf[[t0 + r for r in rows]], np.array([c + r for r in rows]), K, V, sh.scale)
+        got = out[[t0 + r for r in rows]].float().cpu().numpy().astype(np.float64)
+        assert np.abs(got - ref).max() <= ABS_TOL
+        assert np.linalg.norm(got - ref) / np.linalg.norm(ref) <= REL_TOL
