@@ -1,0 +1,133 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares, and its
+host-side checks answer with error codes before anything would be enqueued."""
+import ctypes
+import os
+import re
+
+import pytest
+import torch
+
+from paper_2410_01228_amd import binding as cs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "conserve_kv.h")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cs_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert {"cs_kv_append", "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore"} <= set(names)
+    lib = cs.lib()
+    for n in names:
+        assert hasattr(lib, n), "missing export: " + n
+    assert sorted(cs.EXPORTS) == names
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    monkeypatch.setattr(cs, "_lib", None)
+    monkeypatch.setattr(cs, "LIB_PATH", "/nonexistent/libconserve_kv.so")
+    with pytest.raises(RuntimeError):
+        cs.lib()
+
+
+def test_page_bytes_and_status_strings():
+    assert cs.cs_page_bytes(8, 128) == 65536 and cs.cs_page_bytes(4, 128) == 32768 and cs.cs_page_bytes(2, 64) == 8192
+    assert cs.cs_page_bytes(8, 96) == 0
+    lib = cs.lib()
+    assert lib.cs_status_string(0) == b"ok"
+    assert lib.cs_status_string(cs.CS_ERR_WORKSPACE_TOO_SMALL) == b"workspace too small"
+
+
+def _pool(base=0x1000, L=2, P=8, Hkv=2, D=64, page=16, ls=None, ps=None):
+    pe = 2 * Hkv * 16 * D
+    ps = pe if ps is None else ps
+    return cs.cs_kv_pool(base, L, P, page, Hkv, D, P * ps if ls is None else ls, ps)
+
+
+def _batch(ctx, ql, max_blocks=64, fake_dev=0x2000):
+    h_ctx = torch.tensor(ctx, dtype=torch.int32)
+    cu = torch.zeros(len(ql) + 1, dtype=torch.int32)
+    cu[1:] = torch.cumsum(torch.tensor(ql, dtype=torch.int32), 0)
+    b = cs.cs_batch(len(ctx), int(cu[-1]), fake_dev, max_blocks, fake_dev, fake_dev, h_ctx.data_ptr(), cu.data_ptr())
+    return b, (h_ctx, cu)
+
+
+def test_checkpoint_argument_checks_happen_on_the_host():
+    lib = cs.lib()
+    ids, st = 0x3000, 0x4000
+    page = cs.cs_page_bytes(2, 64)
+    p = _pool()
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p), 0, 2, ids, 3, st, 2 * 3 * page - 1, None) == cs.CS_ERR_STAGING_TOO_SMALL
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p), 0, 3, ids, 3, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p), 1, 0, ids, 3, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p), 0, 2, None, 3, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_kv_ckpt_restore(ctypes.byref(p), 0, 2, ids, -1, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_kv_ckpt_restore(ctypes.byref(p), 0, 2, ids, 3, st + 4, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    # empty work is legal and launches nothing
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p), 0, 2, None, 0, None, 0, None) == cs.CS_OK
+    assert lib.cs_kv_ckpt_restore(ctypes.byref(p), 1, 1, ids, 3, st, 0, None) == cs.CS_OK
+    # unsupported / malformed pools
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(page=32)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_UNSUPPORTED
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(D=96)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_UNSUPPORTED
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(ps=100)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(base=0)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_kv_ckpt_gather(None, 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
+
+
+def test_batch_checks_and_empty_batches():
+    lib = cs.lib()
+    p = _pool()
+    q = 0x5000
+    b, keep = _batch([5, 40], [1, 3])
+    assert lib.cs_kv_append(ctypes.byref(p), 2, ctypes.byref(b), q, q, None) == cs.CS_ERR_INVALID_ARG      # layer
+    assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b), None, q, None) == cs.CS_ERR_INVALID_ARG
+    b2, keep2 = _batch([5, 40], [1, 3], max_blocks=2)                       # 43 tokens need 3 blocks
+    assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b2), q, q, None) == cs.CS_ERR_INVALID_ARG
+    b3, keep3 = _batch([5, -1], [1, 1])
+    assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b3), q, q, None) == cs.CS_ERR_INVALID_ARG
+    b4, keep4 = _batch([5, 6], [1, 1])
+    b4.num_tokens = 3                                                       # disagrees with cu_q_lens
+    assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b4), q, q, None) == cs.CS_ERR_INVALID_ARG
+    empty = cs.cs_batch(0, 0, None, 0, None, None, None, None)
+    assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(empty), None, None, None) == cs.CS_OK
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(empty), None, None, 4, 0.125, None, 0, None) == cs.CS_OK
+    idle, keep5 = _batch([5, 6], [0, 0])
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(idle), None, None, 4, 0.125, None, 0, None) == cs.CS_OK
+
+
+def test_attention_shape_and_workspace_checks():
+    lib = cs.lib()
+    p = _pool()
+    q = 0x5000
+    b, keep = _batch([5000, 40000], [1, 1], max_blocks=4096)
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(b), q, q, 3, 0.125, None, 0, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(b), q, q, 64, 0.125, None, 0, None) == cs.CS_ERR_UNSUPPORTED
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(b), q, q, 4, 0.0, None, 0, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(b), q, q, 4, float("nan"), None, 0, None) == cs.CS_ERR_INVALID_ARG
+    # these two sequences are cut into several items, so a workspace is needed
+    need = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64)
+    assert need > 0
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(b), q, q, 4, 0.125, 0x6000, need - 16, None) == cs.CS_ERR_WORKSPACE_TOO_SMALL
+    assert lib.cs_paged_attention_mixed(ctypes.byref(p), 0, ctypes.byref(b), q, q, 4, 0.125, None, need, None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 3, 2, 64) == 0
+    # the split knob changes the plan and therefore the workspace
+    try:
+        lib.cs_set_decode_split_tokens(256)
+        more = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64)
+        lib.cs_set_decode_split_tokens(1 << 20)
+        none_cut = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64)
+    finally:
+        lib.cs_set_decode_split_tokens(0)
+    assert more >= need > none_cut == 0
+
+
+def test_debug_copy_argument_checks():
+    lib = cs.lib()
+    assert lib.cs_debug_copy(0x1000, 0x2000, 24, None) == cs.CS_ERR_INVALID_ARG          # not a multiple of 16
+    assert lib.cs_debug_copy(0x1008, 0x2000, 32, None) == cs.CS_ERR_INVALID_ARG          # misaligned
+    assert lib.cs_debug_copy(None, None, 0, None) == cs.CS_OK
