@@ -99,7 +99,7 @@ static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
 
 DecodeWorkspace decode_workspace(const DecodePlan& p, int32_t S, int32_t Hq, int32_t D) {
     DecodeWorkspace w = {};
-    if (p.num_decode == 0) return w;
+    if (p.num_decode == 0 || p.num_multi == 0) return w;   // nothing is cut: no item list, no partials
     size_t off = 0;
     w.items = off;    off += align16((size_t)p.total_items * 8 * sizeof(int32_t));
     w.cu_items = off; off += align16((size_t)(S + 1) * sizeof(int32_t));
