@@ -96,37 +96,117 @@ int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 }
 
 // ------------------------------------------------------------------------------------
-// KV append (the cache is append-only: paper Sec. 1, 4.4).  One lane per 16-byte unit
-// (8 features) of a new K row and of a new V row.  The K unit is stored as it is (the K
-// block keeps 8 consecutive features of a token together); the V unit is scattered as 8
-// two-byte stores because the V block keeps 4 consecutive TOKENS of one feature together.
-// A workgroup covers kTokPerBlock tokens; each token finds its sequence by bisection of
-// the prefix sums.
+// KV append (the cache is append-only: paper Sec. 1, 4.4).  A workgroup of 4 wavefronts
+// owns one (page touched this step, kv head) and writes that page's K and V blocks in the
+// order they lie in memory, so every store instruction of a wavefront covers 1 KiB of
+// consecutive bytes; slots the step does not fill are simply masked out.  Sequences with a
+// single new token go through append_token_kernel below instead.  Wavefront w moves features 32w .. 32w+31:
+//   K: lane (feature block dl = lane/16, token = lane%16) loads 16 bytes of its token's row
+//      and stores them to unit (dblk*16 + token) -- consecutive lanes, consecutive units;
+//   V: lane (tile dt = lane/32, token group tg, feature pair i) loads one dword (two
+//      features) from each of the group's 4 token rows, regroups them into two 8-byte
+//      pieces (one feature x 4 tokens each) and stores 16 bytes -- again consecutive.
+// Workgroup slots are dealt to sequences as start(s) = cu_q_lens[s]/16 + 2s (a step of q
+// tokens touches at most q/16 + 2 pages), found by bisection.
 // ------------------------------------------------------------------------------------
 constexpr int kAppendThreads = 256;
 
-__global__ __launch_bounds__(kAppendThreads) void append_kernel(
+__global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
+    uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t D, int32_t S,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
+{
+    const int32_t h = blockIdx.x % Hkv;
+    const int32_t slot_id = blockIdx.x / Hkv;
+    int32_t lo = 0, hi = S;                                       // largest s with start(s) <= slot_id
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if ((cu_q_lens[mid] >> 4) + 2 * mid <= slot_id) lo = mid; else hi = mid;
+    }
+    const int32_t s = lo;
+    const int32_t t_seq = cu_q_lens[s];
+    const int32_t first = ctx_lens[s];                            // the step fills positions [first, last)
+    const int32_t last = first + (cu_q_lens[s + 1] - t_seq);
+    if (last - first == 1) return;                               // single tokens: append_token_kernel
+    const int32_t blk = (first >> 4) + (slot_id - ((t_seq >> 4) + 2 * s));
+    const int32_t p0 = blk << 4;                                  // first position of the page
+    if (p0 >= last || blk >= max_blocks) return;
+    const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
+    if (page < 0 || page >= num_pages) return;
+    const int32_t block_elems = kPage * D;
+    uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
+    uint16_t* vblk = kblk + (int64_t)Hkv * block_elems;
+    const int64_t row = (int64_t)Hkv * D;                         // elements between consecutive tokens
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    if (wave * 32 >= D) return;                                   // head_dim 64: two wavefronts suffice
+    // packed token index of page position p0 (may lie before the step's first token)
+    const int64_t tok_base = (int64_t)t_seq + (p0 - first);
+
+    {   // K: features wave*32 + dl*8 .. +8 of token lane%16
+        const int32_t tok = lane & 15, dblk = wave * 4 + (lane >> 4);
+        const int32_t pos = p0 + tok;
+        if (pos >= first && pos < last) {
+            const u32x4 v = *(const u32x4*)(k_new + ((tok_base + tok) * Hkv + h) * D + dblk * 8);
+            *(u32x4*)(kblk + (dblk * 16 + tok) * 8) = v;
+        }
+    }
+    {   // V: tile dt = wave*2 + lane/32, token group tg = (lane/8)%4, features dt*16 + 2i, +1
+        const int32_t dt = wave * 2 + (lane >> 5), tg = (lane >> 3) & 3, i = lane & 7;
+        const int32_t pos = p0 + tg * 4;                          // first position of the group
+        const uint16_t* src = v_new + ((tok_base + tg * 4) * Hkv + h) * D + dt * 16 + 2 * i;
+        uint16_t* dst = vblk + ((dt * 4 + tg) * 16 + 2 * i) * 4;  // two adjacent 8-byte pieces
+        if (pos >= first && pos + 4 <= last) {
+            uint32_t w[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) w[j] = *(const uint32_t*)(src + j * row);
+            u32x4 o;
+            o[0] = (w[0] & 0xffffu) | (w[1] << 16);               // feature 2i:   tokens 0,1
+            o[1] = (w[2] & 0xffffu) | (w[3] << 16);               //               tokens 2,3
+            o[2] = (w[0] >> 16) | (w[1] & 0xffff0000u);           // feature 2i+1: tokens 0,1
+            o[3] = (w[2] >> 16) | (w[3] & 0xffff0000u);           //               tokens 2,3
+            *(u32x4*)dst = o;
+        } else {
+            // a group the step fills only partly: element by element
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                if (pos + j >= first && pos + j < last) {
+                    const uint32_t w = *(const uint32_t*)(src + j * row);
+                    dst[j] = (uint16_t)(w & 0xffffu);
+                    dst[4 + j] = (uint16_t)(w >> 16);
+                }
+            }
+        }
+    }
+}
+
+// Single new tokens (decode): one lane per 16-byte unit (8 features) of the token's K row
+// and V row.  The K unit is stored as it is; the V unit is scattered as 8 two-byte stores
+// (the V block keeps 4 consecutive TOKENS of one feature together).  Sequences with more
+// than one new token are left to append_page_kernel.
+__global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t D, int32_t S, int32_t T,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
 {
-    const int32_t units_per_tok = Hkv * (D >> 3);                 // 16-byte units per K (or V) row
+    const int32_t units_per_tok = Hkv * (D >> 3);
     const int64_t gid = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
     const int32_t t = (int32_t)(gid / units_per_tok);
     if (t >= T) return;
     const int32_t u = (int32_t)(gid - (int64_t)t * units_per_tok);
     const int32_t h = u / (D >> 3);
     const int32_t dblk = u - h * (D >> 3);
-    // sequence of token t: largest s with cu_q_lens[s] <= t
     int32_t lo = 0, hi = S;                                       // invariant: cu[lo] <= t < cu[hi]
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
         if (cu_q_lens[mid] <= t) lo = mid; else hi = mid;
     }
     const int32_t s = lo;
-    const int32_t pos = ctx_lens[s] + (t - cu_q_lens[s]);
+    if (cu_q_lens[s + 1] - cu_q_lens[s] != 1) return;
+    const int32_t pos = ctx_lens[s];
     const int32_t blk = pos >> 4;
     if (pos < 0 || blk >= max_blocks) return;
     const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
@@ -136,8 +216,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_kernel(
     uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
     uint16_t* vblk = kblk + (int64_t)Hkv * block_elems;
     const int64_t src = ((int64_t)t * Hkv + h) * D + dblk * 8;
-    const u32x4 kv = *(const u32x4*)(k_new + src);
-    *(u32x4*)(kblk + (dblk * 16 + slot) * 8) = kv;
+    *(u32x4*)(kblk + (dblk * 16 + slot) * 8) = *(const u32x4*)(k_new + src);
     const u32x4 vv = *(const u32x4*)(v_new + src);
     // feature d = dblk*8 + e  ->  (((d/16)*4 + slot/4)*16 + d%16)*4 + slot%4
     const int32_t vbase = (((dblk >> 1) * 4 + (slot >> 2)) * 16 + (dblk & 1) * 8) * 4 + (slot & 3);
@@ -152,14 +231,31 @@ int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
                   const void* k_new, const void* v_new, hipStream_t st)
 {
     if (b.num_tokens == 0) return CS_OK;
-    const int64_t units = (int64_t)b.num_tokens * pool.num_kv_heads * (pool.head_dim / 8);
-    const uint32_t blocks = (uint32_t)((units + kAppendThreads - 1) / kAppendThreads);
-    hipLaunchKernelGGL(append_kernel, dim3(blocks), dim3(kAppendThreads), 0, st,
-                       (uint16_t*)pool.base + (int64_t)layer * pool.layer_stride, pool.page_stride,
-                       pool.num_pages, pool.num_kv_heads, pool.head_dim, b.num_seqs, b.num_tokens,
-                       b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
-                       (const uint16_t*)k_new, (const uint16_t*)v_new);
-    return check_launch("append_kernel");
+    bool any_single = false, any_chunk = false;
+    for (int32_t s = 0; s < b.num_seqs; ++s) {
+        const int32_t ql = b.h_cu_q_lens[s + 1] - b.h_cu_q_lens[s];
+        any_single |= ql == 1;
+        any_chunk |= ql > 1;
+    }
+    uint16_t* layer_base = (uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
+    if (any_chunk) {
+        const int64_t slots = (int64_t)(b.num_tokens >> 4) + 2ll * b.num_seqs;
+        const int64_t blocks = slots * pool.num_kv_heads;
+        if (blocks > 2147483647ll) return CS_ERR_UNSUPPORTED;
+        hipLaunchKernelGGL(append_page_kernel, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
+                           layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
+                           b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
+                           (const uint16_t*)k_new, (const uint16_t*)v_new);
+    }
+    if (any_single) {
+        const int64_t units = (int64_t)b.num_tokens * pool.num_kv_heads * (pool.head_dim / 8);
+        const uint32_t blocks = (uint32_t)((units + kAppendThreads - 1) / kAppendThreads);
+        hipLaunchKernelGGL(append_token_kernel, dim3(blocks), dim3(kAppendThreads), 0, st,
+                           layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
+                           b.num_seqs, b.num_tokens, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
+                           b.cu_q_lens, (const uint16_t*)k_new, (const uint16_t*)v_new);
+    }
+    return check_launch("append kernels");
 }
 
 }  // namespace cs
