@@ -201,6 +201,64 @@ def cpu_baseline(b, min_seconds=10.0, max_seconds=30.0):
                       "%d sweeps, %.1f s" % (len(pick), len(order), sum(d[4] for d in data), sweeps, secs)}
 
 
+def checkpoint_pipeline(info, layers=8, reps=5):
+    """The asynchronous checkpoint pipeline (gather + one device-to-host copy on its own
+    stream) alone and concurrent with the attention call: host-link rate and interference."""
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    pool, bb, q, k_new, v_new, out, ws = info["keep"][:7]
+    dirty, fresh, staging = info["keep"][7:10]
+    sh_Hq, scale = q.shape[1], 1.0 / (q.shape[2] ** 0.5)
+    n = dirty.numel()
+    stage = staging[:layers]
+    host = torch.empty((layers, n, staging.shape[2]), dtype=torch.bfloat16).pin_memory()
+    nbytes = host.numel() * 2
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+
+    def attn():
+        cs.cs_paged_attention_mixed(pool, 0, bb, q, out, sh_Hq, scale, ws)
+
+    def timed(stream, fn, n_rep):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(n_rep):
+            fn()
+        e1.record(stream)
+        return e0, e1
+
+    for _ in range(2):
+        cs.cs_kv_ckpt_save(pool, 0, layers, dirty, stage, host, stream=side)
+        attn()
+    torch.cuda.synchronize()
+    a0, a1 = timed(main, attn, 50)
+    torch.cuda.synchronize()
+    attn_alone = a0.elapsed_time(a1) / 50 * 1e3
+    s0, s1 = timed(side, lambda: cs.cs_kv_ckpt_save(pool, 0, layers, dirty, stage, host, stream=side), reps)
+    torch.cuda.synchronize()
+    save_alone = s0.elapsed_time(s1) / reps * 1e3
+    # concurrent: keep attention running on the compute stream for as long as the saves take
+    n_attn = max(50, int(reps * save_alone / attn_alone * 1.2))
+    s0, s1 = timed(side, lambda: cs.cs_kv_ckpt_save(pool, 0, layers, dirty, stage, host, stream=side), reps)
+    a0, a1 = timed(main, attn, n_attn)
+    torch.cuda.synchronize()
+    save_busy = s0.elapsed_time(s1) / reps * 1e3
+    attn_busy = a0.elapsed_time(a1) / n_attn * 1e3
+    l0, l1 = timed(side, lambda: cs.cs_kv_ckpt_load(pool, 0, layers, fresh, stage, host, stream=side), reps)
+    torch.cuda.synchronize()
+    load_alone = l0.elapsed_time(l1) / reps * 1e3
+    r = {"layers": layers, "pages": n, "bytes": nbytes,
+         "save_us": round(save_alone, 1), "save_GBps": round(nbytes / save_alone / 1e3, 1),
+         "load_us": round(load_alone, 1), "load_GBps": round(nbytes / load_alone / 1e3, 1),
+         "save_us_during_attention": round(save_busy, 1), "save_GBps_during_attention": round(nbytes / save_busy / 1e3, 1),
+         "attention_us_alone": round(attn_alone, 1), "attention_us_during_save": round(attn_busy, 1)}
+    log("  checkpoint pipeline (%d layers, %d pages, %.2f GB): save %.0f us = %.1f GB/s host link, load %.0f us = %.1f GB/s; "
+        "with attention running: save %.1f GB/s, attention %.1f -> %.1f us"
+        % (layers, n, nbytes / 1e9, save_alone, r["save_GBps"], load_alone, r["load_GBps"],
+           r["save_GBps_during_attention"], attn_alone, attn_busy))
+    return r
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
     p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
@@ -279,6 +337,8 @@ def main():
         "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=dom.name),
         "legs": {l.name: {"us": round(l.us, 2), "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }
+    if args.detail and args.workload == "qwen14b_ckpt":
+        result["ckpt_pipeline"] = checkpoint_pipeline(info)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(b)
     print(json.dumps(result), flush=True)

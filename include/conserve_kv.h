@@ -131,6 +131,24 @@ int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t layer_begin, int32_t laye
                        const int32_t* page_ids, int32_t n,
                        const void* staging, size_t staging_bytes, void* stream);
 
+/* Incremental checkpoint to host memory and back (Sec. 4.4: checkpoint the newly filled
+ * pages after each step, prefetch them back on resume; Sec. 5: gather into one contiguous
+ * buffer, transfer it once, on a stream of its own so the copy overlaps the model's work --
+ * full pages are immutable, so no synchronisation with the compute stream is needed).
+ *   save: cs_kv_ckpt_gather into `staging`, then ONE device-to-host copy of the gathered
+ *         bytes to `host_buf`, both enqueued on `stream`;
+ *   load: ONE host-to-device copy from `host_buf` into `staging`, then cs_kv_ckpt_restore.
+ * host_buf: PINNED host memory (hipHostMalloc) of at least the gathered size, laid out like
+ * staging ([layers][n][page bytes]); it must stay valid until the stream has run.  Pageable
+ * memory would make the copy synchronous and is the caller's mistake to avoid.  Errors as
+ * for gather / restore. */
+int cs_kv_ckpt_save(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                    const int32_t* page_ids, int32_t n, void* staging, size_t staging_bytes,
+                    void* host_buf, void* stream);
+int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                    const int32_t* page_ids, int32_t n, void* staging, size_t staging_bytes,
+                    const void* host_buf, void* stream);
+
 /* Plain device-to-device copy kernel of `bytes` (multiple of 16, both pointers 16-byte
  * aligned): the measured copy ceiling of the device and the calibration point for hardware
  * byte counters. */

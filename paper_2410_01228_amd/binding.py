@@ -77,6 +77,8 @@ def lib():
         L.cs_paged_attention_mixed.argtypes = [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         for f in (L.cs_kv_ckpt_gather, L.cs_kv_ckpt_restore):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
+        for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
+            f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp, vp]
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_status_string.restype, L.cs_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
@@ -87,7 +89,8 @@ def lib():
 
 EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
-    "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_debug_copy",
+    "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_save",
+    "cs_kv_ckpt_load", "cs_debug_copy",
     "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
 ]
 
@@ -195,6 +198,22 @@ def cs_kv_ckpt_restore(pool: Pool, layer_begin: int, layer_end: int, page_ids: t
     _check(lib().cs_kv_ckpt_restore(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids),
                                     page_ids.numel(), _ptr(staging), staging.numel() * staging.element_size(),
                                     _stream(stream)), "cs_kv_ckpt_restore")
+
+
+def cs_kv_ckpt_save(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,
+                    staging: torch.Tensor, host_buf: torch.Tensor, stream=None):
+    assert host_buf.is_pinned(), "host_buf must be pinned host memory"
+    _check(lib().cs_kv_ckpt_save(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids), page_ids.numel(),
+                                 _ptr(staging), staging.numel() * staging.element_size(), _ptr(host_buf),
+                                 _stream(stream)), "cs_kv_ckpt_save")
+
+
+def cs_kv_ckpt_load(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,
+                    staging: torch.Tensor, host_buf: torch.Tensor, stream=None):
+    assert host_buf.is_pinned(), "host_buf must be pinned host memory"
+    _check(lib().cs_kv_ckpt_load(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids), page_ids.numel(),
+                                 _ptr(staging), staging.numel() * staging.element_size(), _ptr(host_buf),
+                                 _stream(stream)), "cs_kv_ckpt_load")
 
 
 def cs_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):

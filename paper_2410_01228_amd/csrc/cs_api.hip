@@ -201,6 +201,29 @@ int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int
     return launch_page_copy(*pool, l0, l1, ids, n, (void*)staging, false, (hipStream_t)stream);
 }
 
+int cs_kv_ckpt_save(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                    void* staging, size_t staging_bytes, void* host_buf, void* stream) {
+    const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    if (!host_buf) return CS_ERR_INVALID_ARG;
+    const int lrc = launch_page_copy(*pool, l0, l1, ids, n, staging, true, (hipStream_t)stream);
+    if (lrc) return lrc;
+    const size_t bytes = (size_t)(l1 - l0) * n * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const hipError_t e = hipMemcpyAsync(host_buf, staging, bytes, hipMemcpyDeviceToHost, (hipStream_t)stream);
+    return e == hipSuccess ? CS_OK : hip_failed(e, "checkpoint device-to-host copy");
+}
+
+int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                    void* staging, size_t staging_bytes, const void* host_buf, void* stream) {
+    const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    if (!host_buf) return CS_ERR_INVALID_ARG;
+    const size_t bytes = (size_t)(l1 - l0) * n * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const hipError_t e = hipMemcpyAsync(staging, host_buf, bytes, hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_failed(e, "checkpoint host-to-device copy");
+    return launch_page_copy(*pool, l0, l1, ids, n, staging, false, (hipStream_t)stream);
+}
+
 int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (bytes == 0) return CS_OK;
     if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return CS_ERR_INVALID_ARG;
