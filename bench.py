@@ -259,6 +259,62 @@ def checkpoint_pipeline(info, layers=8, reps=5):
     return r
 
 
+def preemption_loop(b, layers=32, iters=10):
+    """Layer-wise preemption driver (cs_run_layers) over `layers` layers of this batch: cost
+    of the safepoints (every 4 layers) with and without waiting for the stream, and the time
+    of an iteration that is preempted at its second safepoint."""
+    import ctypes
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    from paper_2410_01228_amd import synth
+    sh = b.shape
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(77)
+    pool = cs.Pool.empty(layers, b.num_pages, sh.Hkv, sh.D)
+    fill_randn_bf16(pool.tensor.view(-1), gen)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    q = synth.randn_bf16((layers, b.T, sh.Hq, sh.D), gen, "cuda")
+    k = synth.randn_bf16((layers, b.T, sh.Hkv, sh.D), gen, "cuda")
+    v = synth.randn_bf16((layers, b.T, sh.Hkv, sh.D), gen, "cuda")
+    out = torch.empty_like(q)
+    ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+    n_on = b.extra["n_online"]
+    flag = ctypes.c_int32(0)
+
+    count = [0]
+
+    def run(sp):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            count[0] = 0
+            cs.cs_run_layers(pool, 0, layers, bb, q, k, v, out, sh.Hq, sh.scale, ws, sp)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters * 1e3
+
+    run(None)
+    t_none = run(None)
+    t_nosync = run(cs.cs_safepoint(ctypes.addressof(flag), cs.POLL_FN(0), None, 4, n_on, 0))
+    t_sync = run(cs.cs_safepoint(ctypes.addressof(flag), cs.POLL_FN(0), None, 4, n_on, 1))
+
+    def poll(_):
+        count[0] += 1
+        return 1 if count[0] == 2 else 0                             # second safepoint of every iteration
+
+    cb = cs.POLL_FN(poll)
+    t_pre = run(cs.cs_safepoint(None, cb, None, 4, n_on, 1))
+    n_sp = layers // 4
+    r = {"layers": layers, "safepoints": n_sp, "iteration_ms": round(t_none, 3),
+         "iteration_ms_safepoints_nosync": round(t_nosync, 3), "iteration_ms_safepoints_sync": round(t_sync, 3),
+         "safepoint_us_nosync": round((t_nosync - t_none) / n_sp * 1e3, 2),
+         "safepoint_us_sync": round((t_sync - t_none) / n_sp * 1e3, 2),
+         "iteration_ms_preempted_at_layer_4": round(t_pre, 3)}
+    log("  preemption loop (%d layers, safepoint every 4): iteration %.3f ms; with safepoints %.3f ms (no wait, %.2f us each) / "
+        "%.3f ms (waiting, %.2f us each); preempted at layer 4: %.3f ms"
+        % (layers, t_none, t_nosync, r["safepoint_us_nosync"], t_sync, r["safepoint_us_sync"], t_pre))
+    return r
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
     p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
@@ -337,6 +393,9 @@ def main():
         "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=dom.name),
         "legs": {l.name: {"us": round(l.us, 2), "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }
+    if args.detail and args.workload == "qwen7b_mixed":
+        del info["keep"][:]
+        result["preemption_loop"] = preemption_loop(b)
     if args.detail and args.workload == "qwen14b_ckpt":
         result["ckpt_pipeline"] = checkpoint_pipeline(info)
     if not args.no_cpu_baseline:

@@ -149,6 +149,38 @@ int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_e
                     const int32_t* page_ids, int32_t n, void* staging, size_t staging_bytes,
                     const void* host_buf, void* stream);
 
+/* Layer-wise preemption (Sec. 4.3, Alg. 1): the layers of one iteration are enqueued one
+ * call at a time, and every `check_every` layers (a safepoint; the paper uses 4) the driver
+ * looks at a preemption signal that a scheduler thread raises when an online request
+ * arrives.  Once it is raised, the remaining layers run with only the first
+ * `num_online_seqs` sequences (the batch is ordered online-first, so this is a smaller
+ * num_seqs / num_tokens over the same arrays -- nothing is rebuilt).
+ *   flag: host memory shared with the scheduler (pinned or ordinary), nonzero = preempt;
+ *   poll: optional callback asked at each safepoint instead of / in addition to the flag;
+ *   sync_at_safepoint: nonzero = wait for the stream before looking (preemption takes effect
+ *   within check_every layers of GPU work, at the price of draining the launch queue);
+ *   zero = look without waiting (no bubble; takes effect for layers not yet enqueued). */
+typedef struct {
+    const volatile int32_t* flag;
+    int32_t (*poll)(void* arg);
+    void*   poll_arg;
+    int32_t check_every;
+    int32_t num_online_seqs;
+    int32_t sync_at_safepoint;
+} cs_safepoint;
+
+/* Runs cs_kv_append + cs_paged_attention_mixed for layers [layer_begin, layer_end) with the
+ * safepoints above (safepoint == NULL: none).  Per-layer tensors: layer l uses
+ * q + (l - layer_begin) * q_layer_stride elements, likewise k_new / v_new (kv_layer_stride)
+ * and out (q_layer_stride); strides in bf16 elements.  *preempted_before_layer (host,
+ * nullable) receives the first layer that ran online-only, or -1.  Workspace as for
+ * cs_paged_attention_mixed of the full batch.  Errors as for the two calls. */
+int cs_run_layers(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end, const cs_batch* batch,
+                  const void* q, const void* k_new, const void* v_new, void* out,
+                  int64_t q_layer_stride, int64_t kv_layer_stride,
+                  int32_t num_q_heads, float softmax_scale, void* workspace, size_t workspace_bytes,
+                  const cs_safepoint* safepoint, int32_t* preempted_before_layer, void* stream);
+
 /* Plain device-to-device copy kernel of `bytes` (multiple of 16, both pointers 16-byte
  * aligned): the measured copy ceiling of the device and the calibration point for hardware
  * byte counters. */

@@ -48,6 +48,20 @@ class cs_batch(ctypes.Structure):
     ]
 
 
+POLL_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p)
+
+
+class cs_safepoint(ctypes.Structure):
+    _fields_ = [
+        ("flag", ctypes.c_void_p),
+        ("poll", POLL_FN),
+        ("poll_arg", ctypes.c_void_p),
+        ("check_every", ctypes.c_int32),
+        ("num_online_seqs", ctypes.c_int32),
+        ("sync_at_safepoint", ctypes.c_int32),
+    ]
+
+
 class CsError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
@@ -79,6 +93,10 @@ def lib():
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
         for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp, vp]
+        L.cs_run_layers.restype = ctypes.c_int
+        L.cs_run_layers.argtypes = [PP, i32, i32, BP, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, i32,
+                                    ctypes.c_float, vp, sz, ctypes.POINTER(cs_safepoint),
+                                    ctypes.POINTER(ctypes.c_int32), vp]
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_status_string.restype, L.cs_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
@@ -90,7 +108,7 @@ def lib():
 EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
     "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_save",
-    "cs_kv_ckpt_load", "cs_debug_copy",
+    "cs_kv_ckpt_load", "cs_run_layers", "cs_debug_copy",
     "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
 ]
 
@@ -214,6 +232,21 @@ def cs_kv_ckpt_load(pool: Pool, layer_begin: int, layer_end: int, page_ids: torc
     _check(lib().cs_kv_ckpt_load(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids), page_ids.numel(),
                                  _ptr(staging), staging.numel() * staging.element_size(), _ptr(host_buf),
                                  _stream(stream)), "cs_kv_ckpt_load")
+
+
+def cs_run_layers(pool: Pool, layer_begin: int, layer_end: int, batch: Batch, q: torch.Tensor,
+                  k_new: torch.Tensor, v_new: torch.Tensor, out: torch.Tensor, Hq: int, softmax_scale: float,
+                  workspace: Optional[torch.Tensor], safepoint: Optional[cs_safepoint] = None, stream=None) -> int:
+    """q, out: [layers, T, Hq, D]; k_new, v_new: [layers, T, Hkv, D].  Returns the first layer
+    that ran online-only, or -1."""
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    first = ctypes.c_int32(-1)
+    _check(lib().cs_run_layers(ctypes.byref(pool.c), layer_begin, layer_end, ctypes.byref(batch.c), _ptr(q),
+                               _ptr(k_new), _ptr(v_new), _ptr(out), q.stride(0), k_new.stride(0), Hq,
+                               softmax_scale, _ptr(workspace), wb,
+                               ctypes.byref(safepoint) if safepoint is not None else None,
+                               ctypes.byref(first), _stream(stream)), "cs_run_layers")
+    return first.value
 
 
 def cs_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):

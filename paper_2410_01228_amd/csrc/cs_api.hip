@@ -224,6 +224,51 @@ int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_
     return launch_page_copy(*pool, l0, l1, ids, n, staging, false, (hipStream_t)stream);
 }
 
+int cs_run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch* batch,
+                  const void* q, const void* k_new, const void* v_new, void* out,
+                  int64_t q_stride, int64_t kv_stride, int32_t Hq, float scale,
+                  void* workspace, size_t workspace_bytes, const cs_safepoint* sp,
+                  int32_t* preempted_before_layer, void* stream) {
+    if (preempted_before_layer) *preempted_before_layer = -1;
+    int rc = validate_pool(pool);
+    if (rc) return rc;
+    if (l0 < 0 || l1 < l0 || l1 > pool->num_layers || q_stride < 0 || kv_stride < 0) return CS_ERR_INVALID_ARG;
+    rc = validate_batch(pool, batch);
+    if (rc) return rc;
+    if (sp && (sp->check_every <= 0 || sp->num_online_seqs < 0 || sp->num_online_seqs > batch->num_seqs))
+        return CS_ERR_INVALID_ARG;
+    cs_batch cur = *batch;
+    bool preempted = false;
+    for (int32_t l = l0; l < l1; ++l) {
+        if (sp && !preempted && (l - l0) % sp->check_every == 0) {
+            // safepoint: between two layers nothing of the iteration is half done
+            if (sp->sync_at_safepoint) {
+                const hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+                if (e != hipSuccess) return hip_failed(e, "safepoint synchronise");
+            }
+            bool raise = sp->flag && *sp->flag != 0;
+            if (!raise && sp->poll) raise = sp->poll(sp->poll_arg) != 0;
+            if (raise) {
+                // drop the offline tail: same arrays, fewer sequences
+                preempted = true;
+                cur.num_seqs = sp->num_online_seqs;
+                cur.num_tokens = cur.num_seqs > 0 ? batch->h_cu_q_lens[cur.num_seqs] : 0;
+                if (preempted_before_layer) *preempted_before_layer = l;
+            }
+        }
+        const int64_t i = l - l0;
+        const uint16_t* ql = (const uint16_t*)q + i * q_stride;
+        const uint16_t* kl = (const uint16_t*)k_new + i * kv_stride;
+        const uint16_t* vl = (const uint16_t*)v_new + i * kv_stride;
+        uint16_t* ol = (uint16_t*)out + i * q_stride;
+        rc = cs_kv_append(pool, l, &cur, kl, vl, stream);
+        if (rc) return rc;
+        rc = cs_paged_attention_mixed(pool, l, &cur, ql, ol, Hq, scale, workspace, workspace_bytes, stream);
+        if (rc) return rc;
+    }
+    return CS_OK;
+}
+
 int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
     if (bytes == 0) return CS_OK;
     if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return CS_ERR_INVALID_ARG;
