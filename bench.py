@@ -315,6 +315,67 @@ def preemption_loop(b, layers=32, iters=10):
     return r
 
 
+def fit_latency_model(reps=8):
+    """Offline profiler of the paper's latency model, restricted to this path: time
+    append + attention on a grid of (compute tokens, context) batches at the Llama-3.1-8B
+    shape, least-squares fit of the per-token, attention, memory-access and constant terms,
+    relative error of the fit (the paper reports < 4% for whole iterations)."""
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    from paper_2410_01228_amd import synth
+    from paper_2410_01228_amd.latency_model import fit
+    sh = synth.Shape(32, 8, 128)
+    grid = []
+    for P in (128, 256, 512, 1024, 2048):                        # one prefill chunk
+        for C in (0, 2048, 8192, 16384, 32768):
+            grid.append([(P, C)])
+    for S in (32, 128, 256):                                     # decode batches
+        for C in (1024, 4096, 16384):
+            grid.append([(1, C)] * S)
+    for P, C, S, Cd in ((512, 4096, 64, 2048), (1024, 16384, 128, 4096), (2048, 8192, 32, 8192)):   # mixed
+        grid.append([(1, Cd)] * S + [(P, C)])
+    pages = max(sum((p + c + 15) // 16 for p, c in batch) for batch in grid)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(5)
+    pool = cs.Pool.empty(1, pages, sh.Hkv, sh.D)
+    fill_randn_bf16(pool.tensor.view(-1), gen)
+    samples = []
+    for batch in grid:
+        g = synth.generator(6)
+        b = synth.make_batch(sh, [c for _, c in batch], [p for p, _ in batch], g, num_pages=pages)
+        bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+        q = synth.randn_bf16((b.T, sh.Hq, sh.D), gen, "cuda")
+        kn = synth.randn_bf16((b.T, sh.Hkv, sh.D), gen, "cuda")
+        out = torch.empty_like(q)
+        ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+
+        def step():
+            cs.cs_kv_append(pool, 0, bb, kn, kn)
+            cs.cs_paged_attention_mixed(pool, 0, bb, q, out, sh.Hq, sh.scale, ws)
+
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        samples.append((batch, e0.elapsed_time(e1) / reps * 1e-3))
+    m, rel = fit(samples)
+    r = {"shape": "32/8/128", "samples": len(samples), "k_token_s": m.k_p, "k2_attention_s": m.k2,
+         "k4_memory_s": m.k4, "k5_constant_s": m.k5,
+         "mean_rel_err": round(float(rel.mean()), 4), "max_rel_err": round(float(rel.max()), 4),
+         "can_schedule_2048_tokens_ctx0_vs_ctx32768_at_1ms": [
+             m.can_schedule([(1, 4096)] * 64, 2048, 0, 1e-3), m.can_schedule([(1, 4096)] * 64, 2048, 32768, 1e-3)]}
+    log("  latency model over %d batches: k_token %.3e s, k2 %.3e s/pair, k4 %.3e s/token, k5 %.3e s; "
+        "relative error mean %.1f%% max %.1f%%" % (len(samples), m.k_p, m.k2, m.k4, m.k5, 100 * rel.mean(), 100 * rel.max()))
+    for (batch, t), e in zip(samples, rel):
+        log("    %-34s %9.1f us  err %5.1f%%" % ("%d req, P=%d, C<=%d" % (len(batch), sum(p for p, _ in batch), max(c for _, c in batch)), t * 1e6, 100 * e))
+    return r
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
     p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
@@ -335,6 +396,8 @@ def main():
     ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
+    ap.add_argument("--fit-latency-model", action="store_true",
+                    help="also run the (P, C) timing grid and fit the paper's latency model to this path")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run the plain copy kernel on this many GiB three times (the known-size "
                          "reference that hardware byte counters are scaled by)")
@@ -393,6 +456,9 @@ def main():
         "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=dom.name),
         "legs": {l.name: {"us": round(l.us, 2), "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }
+    if args.fit_latency_model:
+        del info["keep"][:]
+        result["latency_model"] = fit_latency_model()
     if args.detail and args.workload == "qwen7b_mixed":
         del info["keep"][:]
         result["preemption_loop"] = preemption_loop(b)
