@@ -122,10 +122,11 @@ def build(name):
         bb_pre = cs.Batch(b.block_tables[n_on:n_act], b.ctx_lens[n_on:n_act], cu)
         T_on = int(b.cu_q_lens[n_on])
         q_pre, out_pre = q[T_on:], out[T_on:]
-        keep += [bb_dec, ws_dec, bb_pre, q_pre, out_pre]
+        ws_pre = cs.workspace_for(bb_pre, sh.Hq, sh.Hkv, sh.D)
+        keep += [bb_dec, ws_dec, bb_pre, q_pre, out_pre, ws_pre]
         detail.append(Leg("decode_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_dec, q, out, sh.Hq, sh.scale, ws_dec),
                           "hbm", dec_bytes))
-        detail.append(Leg("prefill_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_pre, q_pre, out_pre, sh.Hq, sh.scale, None),
+        detail.append(Leg("prefill_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_pre, q_pre, out_pre, sh.Hq, sh.scale, ws_pre),
                           "mfma", pre_flops))
     info = {"T": T, "S": b.S, "dec_bytes": dec_bytes, "pre_flops": pre_flops, "pre_bytes": pre_bytes,
             "append_bytes": append_bytes, "pool_gb": pool.tensor.numel() * 2 / 1e9, "name": b.name,

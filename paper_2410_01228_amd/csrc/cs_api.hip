@@ -146,7 +146,8 @@ size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t Hq, int
     if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return 0;
     if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return 0;
     const DecodePlan p = plan_decode(batch, Hkv, D);
-    return decode_workspace(p, batch->num_seqs, Hq, D).total;
+    const PrefillPlan pp = p.num_prefill ? plan_prefill(batch, Hq, Hkv, D) : PrefillPlan{};
+    return decode_workspace(p, batch->num_seqs, Hq, D).total + pp.bytes;
 }
 
 int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
@@ -163,12 +164,14 @@ int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_bat
     if (!q || !out || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return CS_ERR_INVALID_ARG;
     if (!(softmax_scale > 0.f) || softmax_scale > 3.0e38f) return CS_ERR_INVALID_ARG;   // positive, finite
     const DecodePlan plan = plan_decode(batch, pool->num_kv_heads, pool->head_dim);
-    const size_t need = decode_workspace(plan, batch->num_seqs, Hq, pool->head_dim).total;
+    const size_t decode_bytes = decode_workspace(plan, batch->num_seqs, Hq, pool->head_dim).total;
+    const PrefillPlan pplan = plan.num_prefill ? plan_prefill(batch, Hq, pool->num_kv_heads, pool->head_dim) : PrefillPlan{};
+    const size_t need = decode_bytes + pplan.bytes;
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
     if (plan.num_prefill > 0) {
-        rc = launch_prefill(*pool, layer, *batch, q, out, Hq, softmax_scale, st);
+        rc = launch_prefill(*pool, layer, *batch, pplan, q, out, Hq, softmax_scale, (char*)workspace + decode_bytes, st);
         if (rc) return rc;
     }
     return launch_decode(*pool, layer, *batch, plan, q, out, Hq, softmax_scale, workspace, st);

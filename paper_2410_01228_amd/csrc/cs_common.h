@@ -60,7 +60,16 @@ int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_
 int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st);
-int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
-                   const void* q, void* out, int32_t Hq, float scale, hipStream_t st);
+// Key-range split of the prefill path (pure function of the host lengths).
+struct PrefillPlan {
+    int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
+    int32_t max_ranges;        // grid depth: ranges of the longest tile
+    int32_t base_slot;         // first workgroup slot that can belong to a prefill sequence
+    int32_t num_slots;         // slots from base_slot on (partials are indexed by slot)
+    size_t  bytes;             // workspace for the partials (0 when nothing is cut)
+};
+PrefillPlan plan_prefill(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
+int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
+                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st);
 
 }  // namespace cs

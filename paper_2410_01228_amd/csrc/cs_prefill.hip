@@ -23,6 +23,7 @@
 // maximum is only raised (and the accumulators rescaled) when a new score exceeds it by
 // more than 2^kLazyLog2, which keeps the rescale out of the steady-state loop.
 #include "cs_common.h"
+#include <algorithm>
 #include <type_traits>
 
 namespace cs {
@@ -37,6 +38,7 @@ constexpr int kPrefillThreads = kPrefillWaves * 64;
 constexpr int kNCT = 2;                       // column tiles per wavefront
 constexpr int kKeysPerStep = 32;              // two pages
 constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
+constexpr float kNoMax = -1.0e30f;            // "no score seen yet": finite, so that -inf minus it stays -inf
 constexpr int kRing = 5;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
 
 // s_waitcnt on the vector-memory counter alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
@@ -81,12 +83,14 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     int32_t Hkv, int32_t G, int32_t S,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
-    const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e)
+    const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
+    int32_t range_steps, int32_t base_slot, float* __restrict__ part)
 {
     constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block of a page
     constexpr int kStepUnits = 2 * kUnits;            // K (or V) units of one step (two pages)
     constexpr int kLoads = kStepUnits / kPrefillThreads;   // 16-byte loads per lane, for K and for V
     constexpr int kStepLoads = 2 * kLoads;            // LDS-DMA instructions per wavefront and step
+    constexpr int kPartRow = D + 4;                   // floats per query row of a partial: D outputs, max, sum, pad
     __shared__ u32x4 lds_k[kRing][kStepUnits];
     __shared__ u32x4 lds_v[kRing][kStepUnits];
 
@@ -112,6 +116,12 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t n_keys = C + min(q_len, (tb_max + 1) * 16);   // keys visible to the tile's last token
     const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
     const int32_t first_edge = (C + tb_min * 16 + 1) / kKeysPerStep;   // steps before it need no causal mask
+    // key range of this workgroup: a tile whose keys need more than range_steps steps is cut
+    // into ranges handled by gridDim.z workgroups, each leaving a partial (max, sum, output)
+    const int32_t n_ranges = (n_steps + range_steps - 1) / range_steps;
+    const int32_t step_begin = blockIdx.z * range_steps;
+    if (step_begin >= n_steps) return;
+    const int32_t step_end = min(n_steps, step_begin + range_steps);
     const int32_t n_pages = min((n_seq_keys + kPage - 1) >> 4, max_blocks);
     const int32_t* table = block_tables + (int64_t)s * max_blocks;
     const int32_t Hq = Hkv * G;
@@ -144,7 +154,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     float x[kNCT][8];                                  // raw scores of the current step
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) {
-        m_run[c] = -INFINITY;
+        m_run[c] = kNoMax;
         lacc[c] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) o[c][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -162,8 +172,8 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     // pages and a step's two ids are read out with v_readlane, so the steady state has no
     // scalar-memory load (whose unordered return would turn every LDS wait into a full
     // lgkmcnt(0)).  The register is refilled once per 32 steps.
-    int32_t idbase = 0;
-    int32_t idvec = lane < n_pages ? table[lane] : 0;
+    int32_t idbase = (2 * step_begin) & ~63;
+    int32_t idvec = idbase + lane < n_pages ? table[idbase + lane] : 0;
     auto page_id_raw = [&](int32_t pg) -> int32_t {    // wave-uniform table entry, unchecked
         if (pg - idbase >= 64) {                       // pg only ever grows, two pages per step
             idbase += 64;
@@ -258,15 +268,17 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         }
     };
 
-    // ---- prologue: steps 0 .. kRing-2 in flight, steps 0 and 1 landed, scores of step 0 ----
+    // ---- prologue: the first kRing-1 steps of the range in flight, the first two landed,
+    // scores of the first step ----
     int32_t id_a = 0, id_b = 0;                        // pages of the step issued next
 #pragma unroll
-    for (int j = 0; j < kRing - 1; ++j) dma_step(j, page_id_raw(2 * j), page_id_raw(2 * j + 1));
-    id_a = page_id_raw(2 * (kRing - 1));
-    id_b = page_id_raw(2 * (kRing - 1) + 1);
+    for (int j = 0; j < kRing - 1; ++j)
+        dma_step(step_begin + j, page_id_raw(2 * (step_begin + j)), page_id_raw(2 * (step_begin + j) + 1));
+    id_a = page_id_raw(2 * (step_begin + kRing - 1));
+    id_b = page_id_raw(2 * (step_begin + kRing - 1) + 1);
     wait_vmcnt<(kRing - 3) * kStepLoads>();
     __syncthreads();
-    scores(std::true_type{}, 0, x);
+    scores(std::true_type{}, step_begin, x);
     raise_max(x);
 
     // ---- iteration i: scores of step i+1 (into xn) and weights of step i (from xc) side by
@@ -346,13 +358,13 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         __syncthreads();
     };
     float xb[kNCT][8];
-    int32_t i = 0;
+    int32_t i = step_begin;
     // steady state in pairs, the scores ping-ponging between x and xb; step i+2 fully visible
-    for (; i + 2 < first_edge; i += 2) {
+    for (; i + 2 < min(first_edge, step_end); i += 2) {
         iteration(std::false_type{}, std::false_type{}, i, x, xb);
         iteration(std::false_type{}, std::false_type{}, i + 1, xb, x);
     }
-    for (; i + 1 < n_steps; ++i) {
+    for (; i + 1 < step_end; ++i) {
         iteration(std::true_type{}, std::false_type{}, i, x, xb);
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
@@ -362,27 +374,148 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     iteration(std::true_type{}, std::true_type{}, i, x, xb);
     wait_vmcnt<0>();                                   // no copy may outlive the workgroup's LDS
 
-    // ---- normalise and store: lane holds 4 consecutive features of one query row per tile ----
+    // ---- store: lane holds 4 consecutive features of one query row per tile ----
+    if (n_ranges == 1) {
 #pragma unroll
-    for (int c = 0; c < kNCT; ++c) {
-        const int32_t ct = ct0 + wave * kNCT + c;
-        const int32_t tb = ct / G, hh = ct - tb * G;
-        const int32_t tl = tb * 16 + (lane & 15);
-        if (ct < n_ct && tl < q_len) {
-            const float inv = 1.f / lacc[c][0];
-            uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + (lane >> 4) * 4;
+        for (int c = 0; c < kNCT; ++c) {
+            const int32_t ct = ct0 + wave * kNCT + c;
+            const int32_t tb = ct / G, hh = ct - tb * G;
+            const int32_t tl = tb * 16 + (lane & 15);
+            if (ct < n_ct && tl < q_len) {
+                const float inv = 1.f / lacc[c][0];
+                uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + (lane >> 4) * 4;
 #pragma unroll
-            for (int dt = 0; dt < D / 16; ++dt) {
-                u32x2 w = { pack2_bf16(o[c][dt][0] * inv, o[c][dt][1] * inv),
-                            pack2_bf16(o[c][dt][2] * inv, o[c][dt][3] * inv) };
-                *(u32x2*)(dst + dt * 16) = w;
+                for (int dt = 0; dt < D / 16; ++dt) {
+                    u32x2 w = { pack2_bf16(o[c][dt][0] * inv, o[c][dt][1] * inv),
+                                pack2_bf16(o[c][dt][2] * inv, o[c][dt][3] * inv) };
+                    *(u32x2*)(dst + dt * 16) = w;
+                }
             }
+        }
+    } else {
+        // partial of this key range: unnormalised output, running max and sum per query row
+        float* wg = part + (((int64_t)(b - base_slot) * Hkv + g) * gridDim.z + blockIdx.z) * (kTileCols * 16 * kPartRow);
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c) {
+            float* row = wg + ((wave * kNCT + c) * 16 + (lane & 15)) * kPartRow;
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt) *(f32x4*)(row + dt * 16 + (lane >> 4) * 4) = o[c][dt];
+            if (lane < 16) { row[D] = m_run[c]; row[D + 1] = lacc[c][0]; }
         }
     }
 }
 
-int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
-                   const void* q, void* out, int32_t Hq, float scale, hipStream_t st)
+// Merge of the key-range partials of the tiles that were cut: grid = (Hkv, slots), 256
+// lanes, two lanes per query row (half of the features each).
+template <int D>
+__global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
+    int32_t Hkv, int32_t G, int32_t S, const int32_t* __restrict__ ctx_lens,
+    const int32_t* __restrict__ cu_q_lens, uint16_t* __restrict__ out,
+    int32_t range_steps, int32_t max_ranges, int32_t base_slot, const float* __restrict__ part)
+{
+    constexpr int kPartRow = D + 4;
+    const int32_t g = blockIdx.x, b = blockIdx.y + base_slot;
+    int32_t lo = 0, hi = S;
+    while (hi - lo > 1) {
+        const int32_t mid = (lo + hi) >> 1;
+        if (prefill_slot_start(cu_q_lens[mid], mid, G) <= b) lo = mid; else hi = mid;
+    }
+    const int32_t s = lo;
+    const int32_t t_seq = cu_q_lens[s];
+    const int32_t q_len = cu_q_lens[s + 1] - t_seq;
+    if (q_len <= 1) return;
+    const int32_t n_ct = ((q_len + 15) >> 4) * G;
+    const int32_t ct0 = (int32_t)(b - prefill_slot_start(t_seq, s, G)) * kTileCols;
+    if (ct0 >= n_ct) return;
+    const int32_t tb_max = (min(ct0 + kTileCols, n_ct) - 1) / G;
+    const int32_t n_keys = ctx_lens[s] + min(q_len, (tb_max + 1) * 16);
+    const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
+    const int32_t n_ranges = (n_steps + range_steps - 1) / range_steps;
+    if (n_ranges <= 1) return;                               // written directly by the tile kernel
+    const int32_t row_id = threadIdx.x >> 1, half = threadIdx.x & 1;
+    const int32_t ct = ct0 + (row_id >> 4);
+    const int32_t tb = ct / G, hh = ct - tb * G;
+    const int32_t tl = tb * 16 + (row_id & 15);
+    if (ct >= n_ct || tl >= q_len) return;
+    const float* base = part + (((int64_t)(b - base_slot) * Hkv + g) * max_ranges) * (kTileCols * 16 * kPartRow)
+                      + row_id * kPartRow;
+    const int64_t rstride = (int64_t)kTileCols * 16 * kPartRow;
+    float M = kNoMax;
+    for (int32_t r = 0; r < n_ranges; ++r) M = fmaxf(M, base[r * rstride + D]);
+    float L = 0.f;
+    float acc[D / 2];
+#pragma unroll
+    for (int d = 0; d < D / 2; ++d) acc[d] = 0.f;
+    for (int32_t r = 0; r < n_ranges; ++r) {
+        const float* p = base + r * rstride;
+        const float f = exp2f(p[D] - M);                     // 0 for a range the row sees nothing of
+        L += p[D + 1] * f;
+#pragma unroll
+        for (int d = 0; d < D / 2; d += 4) {
+            const f32x4 v = *(const f32x4*)(p + half * (D / 2) + d);
+            acc[d] += v[0] * f; acc[d + 1] += v[1] * f; acc[d + 2] += v[2] * f; acc[d + 3] += v[3] * f;
+        }
+    }
+    const float inv = 1.f / L;
+    const int32_t Hq = Hkv * G;
+    uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + half * (D / 2);
+#pragma unroll
+    for (int d = 0; d < D / 2; d += 4) {
+        u32x2 w = { pack2_bf16(acc[d] * inv, acc[d + 1] * inv), pack2_bf16(acc[d + 2] * inv, acc[d + 3] * inv) };
+        *(u32x2*)(dst + d) = w;
+    }
+}
+
+// Host plan of the key-range split (a pure function of the host lengths).
+PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) {
+    PrefillPlan p = {};
+    const int32_t G = Hq / Hkv;
+    int64_t total_steps = 0, tiles = 0;
+    int32_t max_steps = 0, first = -1;
+    for (int32_t s = 0; s < b->num_seqs; ++s) {
+        const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+        if (ql <= 1) continue;
+        if (first < 0) first = s;
+        const int32_t C = b->h_ctx_lens[s];
+        const int32_t n_ct = ((ql + 15) >> 4) * G;
+        for (int32_t ct0 = 0; ct0 < n_ct; ct0 += kTileCols) {
+            const int32_t tb_max = (std::min(ct0 + kTileCols, n_ct) - 1) / G;
+            const int32_t n_keys = C + std::min(ql, (tb_max + 1) * 16);
+            const int32_t steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
+            total_steps += steps;
+            max_steps = std::max(max_steps, steps);
+            ++tiles;
+        }
+    }
+    p.range_steps = std::max(max_steps, 1);
+    p.max_ranges = 1;
+    if (tiles == 0) return p;
+    const int64_t wgs = tiles * Hkv;
+    const int64_t avg = total_steps / tiles;
+    // Cut key ranges only when the tiles alone would leave CUs without any workgroup (a small
+    // chunk on a long context: few tiles, each walking thousands of keys).  Measured: once
+    // every CU has a workgroup, uneven tiles cost less than the partials of a split would --
+    // the long tiles speed up as the short ones retire.  When cutting, aim at about four
+    // workgroups per CU with ranges of at least 32 steps (1024 keys), at most 8 per tile.
+    (void)avg;
+    if (wgs < 256) {
+        int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 1023) / 1024);
+        rs = std::max<int64_t>(rs, (max_steps + 7) / 8);
+        if (rs < max_steps) {
+            p.range_steps = (int32_t)rs;
+            p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
+        }
+    }
+    if (p.max_ranges > 1) {
+        p.base_slot = (int32_t)prefill_slot_start(b->h_cu_q_lens[first], first, G);
+        p.num_slots = (int32_t)(prefill_slot_start(b->num_tokens, b->num_seqs, G) - p.base_slot);
+        p.bytes = (size_t)p.num_slots * Hkv * p.max_ranges * kTileCols * 16 * (D + 4) * sizeof(float);
+    }
+    return p;
+}
+
+int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
+                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
@@ -390,16 +523,30 @@ int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
     const int64_t slots64 = prefill_slot_start(b.num_tokens, b.num_seqs, G);
     if (slots64 > 65535) return CS_ERR_UNSUPPORTED;
     const uint32_t slots = (uint32_t)slots64;
-    dim3 grid((uint32_t)Hkv, slots);
+    dim3 grid((uint32_t)Hkv, slots, (uint32_t)plan.max_ranges);
+    float* part = (float*)workspace;
     if (D == 128)
         hipLaunchKernelGGL(prefill_kernel<128>, grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
-                           b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e);
+                           b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
+                           plan.range_steps, plan.base_slot, part);
     else
         hipLaunchKernelGGL(prefill_kernel<64>, grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
-                           b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e);
-    return check_launch("prefill_kernel");
+                           b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
+                           plan.range_steps, plan.base_slot, part);
+    if (plan.max_ranges > 1) {
+        dim3 mgrid((uint32_t)Hkv, (uint32_t)plan.num_slots);
+        if (D == 128)
+            hipLaunchKernelGGL(prefill_merge_kernel<128>, mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
+                               b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
+                               plan.base_slot, part);
+        else
+            hipLaunchKernelGGL(prefill_merge_kernel<64>, mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
+                               b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
+                               plan.base_slot, part);
+    }
+    return check_launch("prefill kernels");
 }
 
 }  // namespace cs

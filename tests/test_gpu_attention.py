@@ -185,3 +185,15 @@ def test_attention_argument_errors():
         assert e.value.status == cs.CS_ERR_INVALID_ARG                # layer out of range
     finally:
         cs.cs_set_decode_split_tokens(0)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,gain", [(8, 2, 128, 1.0), (28, 4, 128, 1.0), (16, 1, 64, 1.0), (8, 2, 128, 6.0)])
+def test_prefill_key_range_split(Hq, Hkv, D, gain):
+    # few chunk tokens on long contexts: the tiles are cut into key ranges whose partials a
+    # second kernel merges (some ranges lie wholly beyond what the earlier token blocks see)
+    sh = synth.Shape(Hq, Hkv, D)
+    b = synth.make_batch(sh, [3000, 1501, 0, 4100], [40, 17, 33, 1], synth.generator(61))
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    assert cs.cs_paged_attention_workspace_bytes(bb, Hq, Hkv, D) > 0
+    out, st, _, _ = run_step(b, 61, q_gain=gain)
+    assert_attention_close(out, st.oracle_attention(), "prefill split %d/%d/%d" % (Hq, Hkv, D))
