@@ -24,6 +24,11 @@ HBM_PEAK = 8.0e12            # B/s, MI355X HBM3E
 MFMA_BF16_PEAK = 2.5e15      # FLOP/s, dense bf16
 
 WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b_ckpt"]
+# the kernel behind the call a roofline line is quoted for
+KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, true> (the call's only kernel here)",
+             ("qwen14b_ckpt", "ckpt_gather"): "cs::page_copy_kernel<true>",
+             ("qwen7b_mixed", "prefill_only"): "cs::prefill_kernel<128>",
+             ("llama70b_long", "prefill_only"): "cs::prefill_kernel<128>"}
 
 
 def log(*a):
@@ -377,6 +382,42 @@ def fit_latency_model(reps=8):
     return r
 
 
+def append_sweep():
+    """cs_kv_append away from the launch-bound sizes of the stated workloads: prefill chunks of
+    2048 tokens (page-ordered writer) and single decode tokens (per-token kernel), growing T."""
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    from paper_2410_01228_amd import synth
+    sh = synth.Shape(32, 8, 128)
+    rows = []
+    for T, chunk in ((256, 1), (4096, 1), (32768, 1), (4096, 512), (65536, 2048), (262144, 2048), (1048576, 4096)):
+        S = T // chunk
+        g = synth.generator(5)
+        ctx = synth.uniform_int(0, 64, S, g) if chunk > 1 else synth.uniform_int(16, 256, S, g)
+        b = synth.make_batch(sh, ctx, [chunk] * S, g)
+        pool = cs.Pool.empty(1, b.num_pages, sh.Hkv, sh.D)
+        bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+        k = torch.randn((T, sh.Hkv, sh.D), device="cuda").to(torch.bfloat16)
+        v = torch.randn_like(k)
+        for _ in range(3):
+            cs.cs_kv_append(pool, 0, bb, k, v)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            cs.cs_kv_append(pool, 0, bb, k, v)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) / 10 * 1e3
+        nbytes = 2 * T * 2 * sh.Hkv * sh.D * 2
+        rows.append({"tokens": T, "tokens_per_seq": chunk, "us": round(us, 1), "GBps": round(nbytes / us / 1e3, 1),
+                     "frac_hbm": round(nbytes / (us * 1e-6) / HBM_PEAK, 4)})
+        log("  append T=%-8d %4d tokens/seq: %9.1f us  %7.1f GB/s (read+write)  %.1f%% of hbm peak"
+            % (T, chunk, us, rows[-1]["GBps"], 100 * rows[-1]["frac_hbm"]))
+        del pool, k, v
+    return rows
+
+
 def read_traffic(name):
     """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
     p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
@@ -397,6 +438,7 @@ def main():
     ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
+    ap.add_argument("--append-sweep", action="store_true", help="also time cs_kv_append over growing token counts")
     ap.add_argument("--fit-latency-model", action="store_true",
                     help="also run the (P, C) timing grid and fit the paper's latency model to this path")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
@@ -454,9 +496,12 @@ def main():
         "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
                    "page_size": 16, "layers_per_step": 1,
                    "step": "+".join(l.name for l in legs)},
-        "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=dom.name),
+        "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=KERNEL_OF.get((args.workload, dom.name), dom.name)),
         "legs": {l.name: {"us": round(l.us, 2), "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }
+    if args.append_sweep:
+        del info["keep"][:]
+        result["append_sweep"] = append_sweep()
     if args.fit_latency_model:
         del info["keep"][:]
         result["latency_model"] = fit_latency_model()

@@ -199,12 +199,17 @@ __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     const int32_t u = (int32_t)(gid - (int64_t)t * units_per_tok);
     const int32_t h = u / (D >> 3);
     const int32_t dblk = u - h * (D >> 3);
-    int32_t lo = 0, hi = S;                                       // invariant: cu[lo] <= t < cu[hi]
-    while (hi - lo > 1) {
-        const int32_t mid = (lo + hi) >> 1;
-        if (cu_q_lens[mid] <= t) lo = mid; else hi = mid;
+    // sequence of token t.  In an online-first batch the decode sequences lead, so token t is
+    // usually sequence t: try that before bisecting the prefix sums.
+    int32_t s = min(t, S - 1);
+    if (!(cu_q_lens[s] <= t && t < cu_q_lens[s + 1])) {
+        int32_t lo = 0, hi = S;                                   // invariant: cu[lo] <= t < cu[hi]
+        while (hi - lo > 1) {
+            const int32_t mid = (lo + hi) >> 1;
+            if (cu_q_lens[mid] <= t) lo = mid; else hi = mid;
+        }
+        s = lo;
     }
-    const int32_t s = lo;
     if (cu_q_lens[s + 1] - cu_q_lens[s] != 1) return;
     const int32_t pos = ctx_lens[s];
     const int32_t blk = pos >> 4;
