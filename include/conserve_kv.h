@@ -30,10 +30,11 @@
  * blob of 2 * num_kv_heads * 16 * head_dim elements ("page_elems").  Inside a block
  * (token t = 0..15 of the page, feature d):
  *     K:  ((d / 8) * 16 + t) * 8 + d % 8                 [D/8][16 tokens][8 features]
- *     V:  (((d / 16) * 4 + t / 4) * 16 + d % 16) * 4 + t % 4
- *                                                        [D/16][4 token groups][16][4 tokens]
- * These are the register layouts the gfx950 matrix instructions take for Q.K^T and P.V, so
- * a wavefront reads a block with fully coalesced 16- and 8-byte loads and no shuffles.
+ *     V:  (((d / 16) * 2 + t / 8) * 16 + d % 16) * 8 + t % 8
+ *                                                        [D/16][2 token halves][16][8 tokens]
+ * A 16-byte unit of K is 8 features of one token, a 16-byte unit of V is one feature of 8
+ * tokens: these are the operand registers the gfx950 matrix instructions take for Q.K^T and
+ * P.V, so wavefronts read blocks with fully coalesced loads and no shuffles.
  */
 #ifndef CONSERVE_KV_H
 #define CONSERVE_KV_H

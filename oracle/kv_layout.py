@@ -13,9 +13,9 @@ Inside a K block (one page, one kv head; token t in 0..15, feature d in 0..D-1):
     i.e. [D/8 feature blocks][16 tokens][8 features]: a 16-byte unit is 8 consecutive
     features of one token, and the 16 tokens of a feature block are adjacent.
 Inside a V block:
-    element index = (((d // 16) * 4 + t // 4) * 16 + d % 16) * 4 + t % 4
-    i.e. [D/16 feature tiles][4 token groups][16 features][4 tokens]: an 8-byte unit is one
-    feature of 4 consecutive tokens.
+    element index = (((d // 16) * 2 + t // 8) * 16 + d % 16) * 8 + t % 8
+    i.e. [D/16 feature tiles][2 token halves][16 features][8 tokens]: a 16-byte unit is one
+    feature of 8 consecutive tokens.
 
 Arrays here are numpy uint16 (bf16 bit patterns); copies are bit copies.
 """
@@ -35,7 +35,7 @@ def v_index(t, d, D):
     """Element index of V[token t][feature d] inside its block."""
     t = np.asarray(t)
     d = np.asarray(d)
-    return (((d // 16) * 4 + t // 4) * 16 + d % 16) * 4 + t % 4
+    return (((d // 16) * 2 + t // 8) * 16 + d % 16) * 8 + t % 8
 
 
 def page_elems(Hkv, D):

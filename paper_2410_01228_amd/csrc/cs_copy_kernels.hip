@@ -103,9 +103,9 @@ int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 // single new token go through append_token_kernel below instead.  Wavefront w moves features 32w .. 32w+31:
 //   K: lane (feature block dl = lane/16, token = lane%16) loads 16 bytes of its token's row
 //      and stores them to unit (dblk*16 + token) -- consecutive lanes, consecutive units;
-//   V: lane (tile dt = lane/32, token group tg, feature pair i) loads one dword (two
-//      features) from each of the group's 4 token rows, regroups them into two 8-byte
-//      pieces (one feature x 4 tokens each) and stores 16 bytes -- again consecutive.
+//   V: lane (tile, token half, feature pair) loads one dword (two features) from each of the
+//      half's 8 token rows, regroups them into two 16-byte units (one feature x 8 tokens
+//      each) and stores 32 consecutive bytes.
 // Workgroup slots are dealt to sequences as start(s) = cu_q_lens[s]/16 + 2s (a step of q
 // tokens touches at most q/16 + 2 pages), found by bisection.
 // ------------------------------------------------------------------------------------
@@ -152,29 +152,35 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
             *(u32x4*)(kblk + (dblk * 16 + tok) * 8) = v;
         }
     }
-    {   // V: tile dt = wave*2 + lane/32, token group tg = (lane/8)%4, features dt*16 + 2i, +1
-        const int32_t dt = wave * 2 + (lane >> 5), tg = (lane >> 3) & 3, i = lane & 7;
-        const int32_t pos = p0 + tg * 4;                          // first position of the group
-        const uint16_t* src = v_new + ((tok_base + tg * 4) * Hkv + h) * D + dt * 16 + 2 * i;
-        uint16_t* dst = vblk + ((dt * 4 + tg) * 16 + 2 * i) * 4;  // two adjacent 8-byte pieces
-        if (pos >= first && pos + 4 <= last) {
-            uint32_t w[4];
+    if (wave * 64 < D) {
+        // V: a 16-byte unit is one feature of 8 consecutive tokens.  Lane (tile dtl = lane/16,
+        // token half th = (lane/8)%2, feature pair i = lane%8) loads one dword (two features)
+        // from each of the half's 8 token rows and regroups them into two units; wavefront w
+        // covers features 64w .. 64w+63, the lanes of a (tile, half) write 256 consecutive bytes.
+        const int32_t dt = wave * 4 + (lane >> 4), th = (lane >> 3) & 1, i = lane & 7;
+        const int32_t pos = p0 + th * 8;                          // first position of the half
+        const uint16_t* src = v_new + ((tok_base + th * 8) * Hkv + h) * D + dt * 16 + 2 * i;
+        uint16_t* dst = vblk + ((dt * 2 + th) * 16 + 2 * i) * 8;  // two adjacent 16-byte units
+        if (pos >= first && pos + 8 <= last) {
+            uint32_t w[8];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) w[j] = *(const uint32_t*)(src + j * row);
-            u32x4 o;
-            o[0] = (w[0] & 0xffffu) | (w[1] << 16);               // feature 2i:   tokens 0,1
-            o[1] = (w[2] & 0xffffu) | (w[3] << 16);               //               tokens 2,3
-            o[2] = (w[0] >> 16) | (w[1] & 0xffff0000u);           // feature 2i+1: tokens 0,1
-            o[3] = (w[2] >> 16) | (w[3] & 0xffff0000u);           //               tokens 2,3
-            *(u32x4*)dst = o;
-        } else {
-            // a group the step fills only partly: element by element
+            for (int j = 0; j < 8; ++j) w[j] = *(const uint32_t*)(src + j * row);
+            u32x4 lo, hi;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                lo[j] = (w[2 * j] & 0xffffu) | (w[2 * j + 1] << 16);          // feature 2i:   tokens 2j, 2j+1
+                hi[j] = (w[2 * j] >> 16) | (w[2 * j + 1] & 0xffff0000u);      // feature 2i+1
+            }
+            *(u32x4*)dst = lo;
+            *(u32x4*)(dst + 8) = hi;
+        } else {
+            // a half the step fills only partly: element by element
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
                 if (pos + j >= first && pos + j < last) {
                     const uint32_t w = *(const uint32_t*)(src + j * row);
                     dst[j] = (uint16_t)(w & 0xffffu);
-                    dst[4 + j] = (uint16_t)(w >> 16);
+                    dst[8 + j] = (uint16_t)(w >> 16);
                 }
             }
         }
@@ -183,7 +189,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
 
 // Single new tokens (decode): one lane per 16-byte unit (8 features) of the token's K row
 // and V row.  The K unit is stored as it is; the V unit is scattered as 8 two-byte stores
-// (the V block keeps 4 consecutive TOKENS of one feature together).  Sequences with more
+// (the V block keeps 8 consecutive TOKENS of one feature together).  Sequences with more
 // than one new token are left to append_page_kernel.
 __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -223,12 +229,12 @@ __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     const int64_t src = ((int64_t)t * Hkv + h) * D + dblk * 8;
     *(u32x4*)(kblk + (dblk * 16 + slot) * 8) = *(const u32x4*)(k_new + src);
     const u32x4 vv = *(const u32x4*)(v_new + src);
-    // feature d = dblk*8 + e  ->  (((d/16)*4 + slot/4)*16 + d%16)*4 + slot%4
-    const int32_t vbase = (((dblk >> 1) * 4 + (slot >> 2)) * 16 + (dblk & 1) * 8) * 4 + (slot & 3);
+    // feature d = dblk*8 + e  ->  (((d/16)*2 + slot/8)*16 + d%16)*8 + slot%8
+    const int32_t vbase = (((dblk >> 1) * 2 + (slot >> 3)) * 16 + (dblk & 1) * 8) * 8 + (slot & 7);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const uint32_t w = vv[e >> 1];
-        vblk[vbase + e * 4] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
+        vblk[vbase + e * 8] = (uint16_t)((e & 1) ? (w >> 16) : (w & 0xffffu));
     }
 }
 

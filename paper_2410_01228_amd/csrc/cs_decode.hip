@@ -38,7 +38,7 @@ __device__ __forceinline__ float xor_max(float v, int mask) {
 template <int D>
 struct PageRegs {
     u32x4 k[D / 32];     // K block: unit (kk*64 + lane)
-    u32x2 v[D / 16];     // V block: unit (dt*64 + lane)
+    u32x2 v[D / 16];     // V block: tokens 4*(lane/16)..+4 of feature dt*16 + lane%16
 };
 
 template <int D>
@@ -50,9 +50,13 @@ __device__ __forceinline__ void load_page(PageRegs<D>& r, const uint16_t* __rest
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
         r.k[kk] = __builtin_nontemporal_load((const u32x4*)kblk + kk * 64 + lane);
+    // V unit (dt*2 + half)*16 + feature holds 8 tokens of one feature; this lane's 4 tokens
+    // 4*(lane/16) .. +4 are the 8-byte half (lane/16)%2 of the unit of token half lane/32.  A
+    // wavefront load still covers 512 consecutive bytes.
+    const int voff = (((lane >> 5) * 16 + (lane & 15)) * 2) + ((lane >> 4) & 1);   // in 8-byte pieces
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt)
-        r.v[dt] = __builtin_nontemporal_load((const u32x2*)vblk + dt * 64 + lane);
+        r.v[dt] = __builtin_nontemporal_load((const u32x2*)vblk + dt * 64 + voff);
 }
 
 // One wavefront's running state.

@@ -9,8 +9,8 @@
 // workgroups share a CU.  It walks the sequence's keys 32 at a time
 // (two pages).  The pages' K and V blocks are copied global -> LDS by LDS-DMA loads into a
 // ring of slots several steps ahead (one barrier per step, no staging registers); every
-// wavefront reads them back as MFMA operands -- the
-// page format is the operand layout, so the LDS reads are linear in the lane id -- and
+// wavefront reads them back as MFMA operands -- a page's 16-byte units are operand
+// fragments, and the copy places them so that the LDS reads are linear in the lane id -- and
 //   S^T[key][query]   = K . Q^T                      v_mfma_f32_16x16x32_bf16
 //   O^T[d][query]    += V^T[d][32 keys] . P^T        v_mfma_f32_16x16x32_bf16
 // with P^T taken straight from the S^T accumulators of the two pages (their C layout is
@@ -183,44 +183,59 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         return __builtin_amdgcn_readlane(idvec, pg - idbase);
     };
     auto checked = [&](int32_t id) -> int32_t { return (id < 0 || id >= num_pages) ? 0 : id; };
+    // LDS arrangement of a step (two pages A, B; 32 keys), chosen so that every operand read
+    // below is linear in the lane id (b128, conflict-free):
+    //   K unit ((kk*2 + tile)*4 + kg)*16 + r : features kk*32 + kg*8 .. +8 of row r of tile X
+    //     (tile 0) or Y (tile 1).  Row r = 8*page + 4*half + i stands for token
+    //     8*half + i (+4 for tile Y) of that page: a lane group of the S^T accumulators then
+    //     owns, over X and Y together, 8 CONSECUTIVE tokens of ONE page -- exactly one 16-byte
+    //     V unit;
+    //   V unit dt*64 + (page*2 + half)*16 + f : feature dt*16 + f, tokens 8*half .. +8 of page.
+    // The copy engine takes one global address per lane, so this regrouping costs nothing.
     auto dma_step = [&](int32_t step, int32_t id0, int32_t id1) {
         const int slot = step % kRing;
+        const uint16_t* pg0 = layer_base + (int64_t)checked(id0) * page_stride + (int64_t)g * (kPage * D);
+        const uint16_t* pg1 = layer_base + (int64_t)checked(id1) * page_stride + (int64_t)g * (kPage * D);
+        const int64_t v_off = (int64_t)Hkv * (kPage * D);                 // K block -> V block of a page
 #pragma unroll
-        for (int kv = 0; kv < 2; ++kv) {
-#pragma unroll
-            for (int r = 0; r < kLoads; ++r) {
-                const int unit0 = (r * kPrefillWaves + wave) * 64;          // wave-uniform
-                const int pg_in = unit0 / kUnits;
-                const int32_t id = checked(pg_in ? id1 : id0);
-                const uint16_t* blk = layer_base + (int64_t)id * page_stride + ((int64_t)kv * Hkv + g) * (kPage * D);
-                const u32x4* src = (const u32x4*)blk + (unit0 - pg_in * kUnits) + lane;
-                u32x4* dst = kv ? &lds_v[slot][unit0] : &lds_k[slot][unit0];
-                lds_dma16(src, dst);
+        for (int r = 0; r < kLoads; ++r) {
+            const int unit0 = (r * kPrefillWaves + wave) * 64;            // wave-uniform
+            {   // K
+                const int kk = unit0 >> 7, tile = (unit0 >> 6) & 1;
+                const int kg = lane >> 4, row = lane & 15;
+                const int tok = ((row >> 2) & 1) * 8 + (row & 3) + 4 * tile;
+                const uint16_t* blk = (row & 8) ? pg1 : pg0;
+                lds_dma16((const u32x4*)blk + (kk * 4 + kg) * 16 + tok, &lds_k[slot][unit0]);
+            }
+            {   // V
+                const int dt = unit0 >> 6;
+                const int half = (lane >> 4) & 1, f = lane & 15;
+                const uint16_t* blk = ((lane & 32) ? pg1 : pg0) + v_off;
+                lds_dma16((const u32x4*)blk + (dt * 2 + half) * 16 + f, &lds_v[slot][unit0]);
             }
         }
     };
 
-    // Raw scores of one step (before the softmax scale): xs[c][0..3] = keys
-    // 32*step + 4*(lane/16) + i of the first page, xs[c][4..7] the same rows of the second page.
-    // Masked entries become -inf.
+    // Raw scores of one step (before the softmax scale).  With hi = lane/16: xs[c][0..3] are
+    // rows 4*hi + i of tile X, xs[c][4..7] of tile Y, i.e. together the 8 consecutive keys
+    // 32*step + 16*(hi/2) + 8*(hi%2) + 0..7.  Masked entries become -inf.
     auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8]) {
         constexpr bool kMask = decltype(masked)::value;
-        const u32x4* kA0 = &lds_k[step % kRing][0];
-        const u32x4* kA1 = &lds_k[step % kRing][kUnits];
+        const u32x4* kA = &lds_k[step % kRing][0];
         f32x4 s0[kNCT], s1[kNCT];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
-            const bf16x8 ka0 = __builtin_bit_cast(bf16x8, kA0[kk * 64 + lane]);
-            const bf16x8 ka1 = __builtin_bit_cast(bf16x8, kA1[kk * 64 + lane]);
+            const bf16x8 ka0 = __builtin_bit_cast(bf16x8, kA[(kk * 2 + 0) * 64 + lane]);   // tile X
+            const bf16x8 ka1 = __builtin_bit_cast(bf16x8, kA[(kk * 2 + 1) * 64 + lane]);   // tile Y
 #pragma unroll
             for (int c = 0; c < kNCT; ++c) {
                 s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka0, qb[c][kk], s0[c], 0, 0, 0);
                 s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka1, qb[c][kk], s1[c], 0, 0, 0);
             }
         }
-        const int32_t key0 = step * kKeysPerStep + (lane >> 4) * 4;
+        const int32_t key0 = step * kKeysPerStep + (lane >> 5) * 16 + ((lane >> 4) & 1) * 8;
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
 #pragma unroll
@@ -229,7 +244,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
                 xs[c][4 + i] = s1[c][i];
                 if (kMask) {
                     if (key0 + i > pos_q[c]) xs[c][i] = -INFINITY;
-                    if (key0 + 16 + i > pos_q[c]) xs[c][4 + i] = -INFINITY;
+                    if (key0 + 4 + i > pos_q[c]) xs[c][4 + i] = -INFINITY;
                 }
             }
         }
@@ -304,27 +319,23 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
             const u32x4 pk = { pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]) };
             pb[c] = __builtin_bit_cast(bf16x8, pk);
         }
-        const u32x2* vA0 = (const u32x2*)&lds_v[i % kRing][0];
-        const u32x2* vA1 = (const u32x2*)&lds_v[i % kRing][kUnits];
+        const u32x4* vA = &lds_v[i % kRing][0];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
             lacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[c], lacc[c], 0, 0, 0);
         // V slots at or past the end of the sequence hold stale bits (or nothing at all): zero
-        // them so that a zero weight times the slot stays zero.  Lane holds tokens
-        // 4*(lane/16) .. +4 of each page.
+        // them so that a zero weight times the slot stays zero.  The lane's unit holds the 8
+        // tokens 32*i + 16*(hi/2) + 8*(hi%2) + 0..7, two per dword.
         uint32_t vm[4] = {0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu};
         if (kMask && (i + 1) * kKeysPerStep > n_seq_keys) {
-            const int32_t v0 = n_seq_keys - (i * kKeysPerStep + (lane >> 4) * 4);
-            const int32_t v1 = v0 - kPage;
-            vm[0] = v0 >= 2 ? 0xffffffffu : (v0 == 1 ? 0x0000ffffu : 0u);
-            vm[1] = v0 >= 4 ? 0xffffffffu : (v0 == 3 ? 0x0000ffffu : 0u);
-            vm[2] = v1 >= 2 ? 0xffffffffu : (v1 == 1 ? 0x0000ffffu : 0u);
-            vm[3] = v1 >= 4 ? 0xffffffffu : (v1 == 3 ? 0x0000ffffu : 0u);
+            const int32_t valid = n_seq_keys - (i * kKeysPerStep + (lane >> 5) * 16 + ((lane >> 4) & 1) * 8);
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                vm[j] = valid >= 2 * j + 2 ? 0xffffffffu : (valid == 2 * j + 1 ? 0x0000ffffu : 0u);
         }
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
-            const u32x2 a0 = vA0[dt * 64 + lane], a1 = vA1[dt * 64 + lane];
-            u32x4 av = { a0[0], a0[1], a1[0], a1[1] };
+            u32x4 av = vA[dt * 64 + lane];
             if (kMask) { av[0] &= vm[0]; av[1] &= vm[1]; av[2] &= vm[2]; av[3] &= vm[3]; }
             const bf16x8 va = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
@@ -343,7 +354,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
             for (int r = 0; r < kQK; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // 1 MFMA
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);               // 2 VALU
-                if (r < D / 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // V: one LDS read
+                if (r < D / 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // V: one ds_read_b128
             }
 #pragma unroll
             for (int r = 0; r < kPV; ++r) {

@@ -48,10 +48,10 @@ def test_format_is_a_bijection_with_the_stated_units(D):
     assert np.all(ki[:, 1:8] - ki[:, 0:7] == 1)
     assert np.all(ki[1:, 0] - ki[:-1, 0] == 8)
     assert np.all(ki[:, 8:] - ki[:, :-8] == 128)
-    # V: an 8-byte unit = one feature of 4 consecutive tokens
-    assert np.all(vi[1:4, :] - vi[0:3, :] == 1)
-    assert np.all(vi[0, 1:16] - vi[0, 0:15] == 4)
-    assert np.all(vi[4:, :] - vi[:-4, :] == 64)
+    # V: a 16-byte unit = one feature of 8 consecutive tokens
+    assert np.all(vi[1:8, :] - vi[0:7, :] == 1)
+    assert np.all(vi[0, 1:16] - vi[0, 0:15] == 8)
+    assert np.all(vi[8:, :] - vi[:-8, :] == 128)
     assert np.all(vi[:, 16:] - vi[:, :-16] == 256)
 
 
@@ -82,7 +82,7 @@ def test_append_touches_only_the_new_slots_and_reads_back():
             for h in range(sh.Hkv):
                 for d in (0, 7, 8, 31, sh.D - 1):
                     assert pool[0, page, 0, h, ((d // 8) * 16 + t) * 8 + d % 8] == k_new[tok, h, d]
-                    assert pool[0, page, 1, h, (((d // 16) * 4 + t // 4) * 16 + d % 16) * 4 + t % 4] == v_new[tok, h, d]
+                    assert pool[0, page, 1, h, (((d // 16) * 2 + t // 8) * 16 + d % 16) * 8 + t % 8] == v_new[tok, h, d]
     # reading back through the block table returns the appended rows at the new positions
     for s in range(b.S):
         c, q = int(b.ctx_lens[s]), int(b.q_lens[s])
