@@ -60,6 +60,23 @@ __device__ __forceinline__ void lds_dma16(const void* src, void* dst_wave_base) 
                  :: "s"(lds_addr), "v"(src) : "memory", "m0");
 }
 
+// Two LDS-DMA loads for one run of 64 LDS units whose lanes read from two different pages:
+// the lanes in mask_a fetch from base_a + off, the others from base_b + off (off = this
+// lane's byte offset inside a page's K or V block).  Scalar bases and a per-lane 32-bit
+// offset keep all address arithmetic out of the vector ALU; EXEC is narrowed to each lane
+// set in turn and restored.  Must be called with all 64 lanes active.
+__device__ __forceinline__ void lds_dma16_two_pages(const void* base_a, const void* base_b, uint32_t off,
+                                                    uint64_t mask_a, void* dst_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_base;
+    asm volatile("s_mov_b32 m0, %0\n\t"
+                 "s_mov_b64 exec, %4\n\t"
+                 "global_load_lds_dwordx4 %1, %2\n\t"
+                 "s_not_b64 exec, exec\n\t"
+                 "global_load_lds_dwordx4 %1, %3\n\t"
+                 "s_mov_b64 exec, -1"
+                 :: "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0");
+}
+
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     bf16x2 v = { (__bf16)lo, (__bf16)hi };
@@ -89,7 +106,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block of a page
     constexpr int kStepUnits = 2 * kUnits;            // K (or V) units of one step (two pages)
     constexpr int kLoads = kStepUnits / kPrefillThreads;   // 16-byte loads per lane, for K and for V
-    constexpr int kStepLoads = 2 * kLoads;            // LDS-DMA instructions per wavefront and step
+    constexpr int kStepLoads = 4 * kLoads;            // LDS-DMA instructions per wavefront and step
     constexpr int kPartRow = D + 4;                   // floats per query row of a partial: D outputs, max, sum, pad
     __shared__ u32x4 lds_k[kRing][kStepUnits];
     __shared__ u32x4 lds_v[kRing][kStepUnits];
@@ -192,27 +209,29 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     //     V unit;
     //   V unit dt*64 + (page*2 + half)*16 + f : feature dt*16 + f, tokens 8*half .. +8 of page.
     // The copy engine takes one global address per lane, so this regrouping costs nothing.
+    // per-lane byte offsets of the units this lane copies, inside a page's K block / V block
+    uint32_t k_off[kLoads], v_off_lane[kLoads];
+#pragma unroll
+    for (int r = 0; r < kLoads; ++r) {
+        const int unit0 = (r * kPrefillWaves + wave) * 64;
+        const int kk = unit0 >> 7, tile = (unit0 >> 6) & 1, kg = lane >> 4, row = lane & 15;
+        const int tok = ((row >> 2) & 1) * 8 + (row & 3) + 4 * tile;
+        k_off[r] = (uint32_t)(((kk * 4 + kg) * 16 + tok) * 16);
+        const int dt = unit0 >> 6, half = (lane >> 4) & 1, f = lane & 15;
+        v_off_lane[r] = (uint32_t)(((dt * 2 + half) * 16 + f) * 16);
+    }
     auto dma_step = [&](int32_t step, int32_t id0, int32_t id1) {
         const int slot = step % kRing;
         const uint16_t* pg0 = layer_base + (int64_t)checked(id0) * page_stride + (int64_t)g * (kPage * D);
         const uint16_t* pg1 = layer_base + (int64_t)checked(id1) * page_stride + (int64_t)g * (kPage * D);
-        const int64_t v_off = (int64_t)Hkv * (kPage * D);                 // K block -> V block of a page
+        const int64_t v_blk = (int64_t)Hkv * (kPage * D);                 // K block -> V block of a page
 #pragma unroll
         for (int r = 0; r < kLoads; ++r) {
             const int unit0 = (r * kPrefillWaves + wave) * 64;            // wave-uniform
-            {   // K
-                const int kk = unit0 >> 7, tile = (unit0 >> 6) & 1;
-                const int kg = lane >> 4, row = lane & 15;
-                const int tok = ((row >> 2) & 1) * 8 + (row & 3) + 4 * tile;
-                const uint16_t* blk = (row & 8) ? pg1 : pg0;
-                lds_dma16((const u32x4*)blk + (kk * 4 + kg) * 16 + tok, &lds_k[slot][unit0]);
-            }
-            {   // V
-                const int dt = unit0 >> 6;
-                const int half = (lane >> 4) & 1, f = lane & 15;
-                const uint16_t* blk = ((lane & 32) ? pg1 : pg0) + v_off;
-                lds_dma16((const u32x4*)blk + (dt * 2 + half) * 16 + f, &lds_v[slot][unit0]);
-            }
+            // K rows 0..7 of a tile come from the first page, rows 8..15 from the second
+            lds_dma16_two_pages(pg0, pg1, k_off[r], 0x00ff00ff00ff00ffull, &lds_k[slot][unit0]);
+            // V lanes 0..31 hold the first page's two halves, lanes 32..63 the second page's
+            lds_dma16_two_pages(pg0 + v_blk, pg1 + v_blk, v_off_lane[r], 0x00000000ffffffffull, &lds_v[slot][unit0]);
         }
     };
 
