@@ -77,6 +77,17 @@ __device__ __forceinline__ void lds_dma16_two_pages(const void* base_a, const vo
                  :: "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0");
 }
 
+// max(a, b, c) in one instruction.  fmaxf() makes the compiler canonicalise every operand
+// first (one extra v_max per value, to quiet signalling NaNs); the scores need no such care.
+__device__ __forceinline__ float max3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float max8(const float (&x)[8]) {
+    return max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[7]));
+}
+
 __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
     typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
     bf16x2 v = { (__bf16)lo, (__bf16)hi };
@@ -280,15 +291,12 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         bool need = false;
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
-            const float m = fmaxf(fmaxf(fmaxf(xs[c][0], xs[c][1]), fmaxf(xs[c][2], xs[c][3])),
-                                  fmaxf(fmaxf(xs[c][4], xs[c][5]), fmaxf(xs[c][6], xs[c][7])));
-            need |= m > thr[c];
+            need |= max8(xs[c]) > thr[c];
         }
         if (__any(need)) {
 #pragma unroll
             for (int c = 0; c < kNCT; ++c) {
-                float m = fmaxf(fmaxf(fmaxf(xs[c][0], xs[c][1]), fmaxf(xs[c][2], xs[c][3])),
-                                fmaxf(fmaxf(xs[c][4], xs[c][5]), fmaxf(xs[c][6], xs[c][7])));
+                float m = max8(xs[c]);
                 m = fmaxf(m, __shfl_xor(m, 16, 64));
                 m = fmaxf(m, __shfl_xor(m, 32, 64));
                 const float m_new = fmaxf(m_run[c], m * scale_log2e);
