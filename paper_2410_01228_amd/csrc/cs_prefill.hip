@@ -39,7 +39,7 @@ constexpr int kNCT = 2;                       // column tiles per wavefront
 constexpr int kKeysPerStep = 32;              // two pages
 constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
 constexpr float kNoMax = -1.0e30f;            // "no score seen yet": finite, so that -inf minus it stays -inf
-constexpr int kRing = 5;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
+constexpr int kRing = 4;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
 
 // s_waitcnt on the vector-memory counter alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14,
 // expcnt 6:4 and lgkmcnt 11:8 left at "no wait").
@@ -196,21 +196,38 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     // lie inside one page.  A page the sequence does not have is replaced by page 0 of the
     // pool: every step issues the same number of instructions (the vmcnt arithmetic below
     // relies on it) and whatever lands is masked where it is used. ----
-    // Page ids travel in a lane register: idvec holds table[idbase + lane] for 64 consecutive
-    // pages and a step's two ids are read out with v_readlane, so the steady state has no
-    // scalar-memory load (whose unordered return would turn every LDS wait into a full
-    // lgkmcnt(0)).  The register is refilled once per 32 steps.
+    // Page addresses travel in lane registers: lane j of (pgoff_lo, pgoff_hi) holds the byte
+    // offset of page idbase + j (this kv head's K block) from the layer base, already checked
+    // against the pool size, and a step's two addresses are read out with v_readlane.  So the
+    // steady state has no scalar-memory load (whose unordered return would turn every LDS wait
+    // into a full lgkmcnt(0)) and no 64-bit multiply.  The registers are refilled once per 32
+    // steps; a page the sequence does not have (or a bad id) reads as page 0.
     int32_t idbase = (2 * step_begin) & ~63;
-    int32_t idvec = idbase + lane < n_pages ? table[idbase + lane] : 0;
-    auto page_id_raw = [&](int32_t pg) -> int32_t {    // wave-uniform table entry, unchecked
-        if (pg - idbase >= 64) {                       // pg only ever grows, two pages per step
-            idbase += 64;
-            idvec = idbase + lane < n_pages ? table[idbase + lane] : 0;
-            asm volatile("" : "+v"(idvec));            // take the load's wait here, not at every readlane
-        }
-        return __builtin_amdgcn_readlane(idvec, pg - idbase);
+    uint32_t pgoff_lo, pgoff_hi;
+    auto load_window = [&]() {
+        const int32_t id = idbase + lane < n_pages ? table[idbase + lane] : 0;
+        const uint64_t off = ((uint64_t)((id < 0 || id >= num_pages) ? 0 : id) * (uint64_t)page_stride
+                              + (uint64_t)g * (kPage * D)) * 2;
+        pgoff_lo = (uint32_t)off;
+        pgoff_hi = (uint32_t)(off >> 32);
+        asm volatile("" : "+v"(pgoff_lo), "+v"(pgoff_hi));   // take the load's wait here, not at every readlane
     };
-    auto checked = [&](int32_t id) -> int32_t { return (id < 0 || id >= num_pages) ? 0 : id; };
+    load_window();
+    struct StepPages { const char* a; const char* b; };
+    auto step_pages = [&](int32_t step) -> StepPages {  // wave-uniform addresses of the step's two pages
+        if (2 * step - idbase >= 64) {                   // steps only ever grow
+            idbase += 64;
+            load_window();
+        }
+        const int j = 2 * step - idbase;
+        // (readlane returns a signed int: widen through uint32_t or the low half's sign bit
+        // would smear over the high half)
+        const uint64_t oa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_hi, j) << 32)
+                          | (uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_lo, j);
+        const uint64_t ob = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_hi, j + 1) << 32)
+                          | (uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_lo, j + 1);
+        return StepPages{ (const char*)layer_base + oa, (const char*)layer_base + ob };
+    };
     // LDS arrangement of a step (two pages A, B; 32 keys), chosen so that every operand read
     // below is linear in the lane id (b128, conflict-free):
     //   K unit ((kk*2 + tile)*4 + kg)*16 + r : features kk*32 + kg*8 .. +8 of row r of tile X
@@ -231,18 +248,16 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         const int dt = unit0 >> 6, half = (lane >> 4) & 1, f = lane & 15;
         v_off_lane[r] = (uint32_t)(((dt * 2 + half) * 16 + f) * 16);
     }
-    auto dma_step = [&](int32_t step, int32_t id0, int32_t id1) {
-        const int slot = step % kRing;
-        const uint16_t* pg0 = layer_base + (int64_t)checked(id0) * page_stride + (int64_t)g * (kPage * D);
-        const uint16_t* pg1 = layer_base + (int64_t)checked(id1) * page_stride + (int64_t)g * (kPage * D);
-        const int64_t v_blk = (int64_t)Hkv * (kPage * D);                 // K block -> V block of a page
+    auto dma_step = [&](int32_t step, StepPages pg) {
+        const uint32_t slot = (uint32_t)step % kRing;
+        const int64_t v_blk = (int64_t)Hkv * (kPage * D) * 2;             // K block -> V block of a page, bytes
 #pragma unroll
         for (int r = 0; r < kLoads; ++r) {
             const int unit0 = (r * kPrefillWaves + wave) * 64;            // wave-uniform
             // K rows 0..7 of a tile come from the first page, rows 8..15 from the second
-            lds_dma16_two_pages(pg0, pg1, k_off[r], 0x00ff00ff00ff00ffull, &lds_k[slot][unit0]);
+            lds_dma16_two_pages(pg.a, pg.b, k_off[r], 0x00ff00ff00ff00ffull, &lds_k[slot][unit0]);
             // V lanes 0..31 hold the first page's two halves, lanes 32..63 the second page's
-            lds_dma16_two_pages(pg0 + v_blk, pg1 + v_blk, v_off_lane[r], 0x00000000ffffffffull, &lds_v[slot][unit0]);
+            lds_dma16_two_pages(pg.a + v_blk, pg.b + v_blk, v_off_lane[r], 0x00000000ffffffffull, &lds_v[slot][unit0]);
         }
     };
 
@@ -251,7 +266,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     // 32*step + 16*(hi/2) + 8*(hi%2) + 0..7.  Masked entries become -inf.
     auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8]) {
         constexpr bool kMask = decltype(masked)::value;
-        const u32x4* kA = &lds_k[step % kRing][0];
+        const u32x4* kA = &lds_k[(uint32_t)step % kRing][0];
         f32x4 s0[kNCT], s1[kNCT];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
@@ -312,12 +327,9 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
 
     // ---- prologue: the first kRing-1 steps of the range in flight, the first two landed,
     // scores of the first step ----
-    int32_t id_a = 0, id_b = 0;                        // pages of the step issued next
 #pragma unroll
-    for (int j = 0; j < kRing - 1; ++j)
-        dma_step(step_begin + j, page_id_raw(2 * (step_begin + j)), page_id_raw(2 * (step_begin + j) + 1));
-    id_a = page_id_raw(2 * (step_begin + kRing - 1));
-    id_b = page_id_raw(2 * (step_begin + kRing - 1) + 1);
+    for (int j = 0; j < kRing - 1; ++j) dma_step(step_begin + j, step_pages(step_begin + j));
+    StepPages pg_next = step_pages(step_begin + kRing - 1);       // pages of the step issued next
     wait_vmcnt<(kRing - 3) * kStepLoads>();
     __syncthreads();
     scores(std::true_type{}, step_begin, x);
@@ -332,9 +344,8 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         constexpr bool kLast = decltype(last)::value;
         // step i+kRing-1 goes into the slot step i-1 left (its last reader finished before the
         // barrier that ended iteration i-1)
-        dma_step(i + kRing - 1, id_a, id_b);
-        id_a = page_id_raw(2 * (i + kRing));          // consumed by the next iteration
-        id_b = page_id_raw(2 * (i + kRing) + 1);
+        dma_step(i + kRing - 1, pg_next);
+        pg_next = step_pages(i + kRing);               // consumed by the next iteration
 
         if (!kLast) scores(masked, i + 1, xn);
         bf16x8 pb[kNCT];
@@ -346,7 +357,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
             const u32x4 pk = { pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]) };
             pb[c] = __builtin_bit_cast(bf16x8, pk);
         }
-        const u32x4* vA = &lds_v[i % kRing][0];
+        const u32x4* vA = &lds_v[(uint32_t)i % kRing][0];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
             lacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[c], lacc[c], 0, 0, 0);
