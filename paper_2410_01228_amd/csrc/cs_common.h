@@ -34,6 +34,14 @@ __host__ __device__ inline int32_t decode_chunk_keys(int32_t n_keys, int32_t n_s
     return (c + kPage - 1) & ~(kPage - 1);
 }
 
+// Small batches carry their work-item list inside the kernel arguments: the host already has
+// the lengths, so it lists the items itself, longest first, and no planning kernel and no
+// host-to-device copy is needed.  One word per item: sequence (bits 0-15), piece (16-23),
+// pieces of that sequence (24-31).  One word per cut sequence for the merge: sequence (bits
+// 0-15), its first item (16-31).  The list must fit the 4 KiB argument block of a launch.
+constexpr int kMaxArgItems = 880;
+struct ItemsInArgs { uint32_t e[kMaxArgItems]; };
+
 // Plan of the decode path, a pure function of the host lengths (used by both the
 // workspace query and the launch).
 struct DecodePlan {
@@ -43,6 +51,9 @@ struct DecodePlan {
     int32_t total_items;       // sum over decode sequences of their split count
     int32_t num_multi;         // decode sequences cut into more than one item
     int64_t decode_keys;       // total keys read by decode sequences
+    bool    in_args;           // the item list below is valid and replaces the planning kernel
+    ItemsInArgs arg_items;     // total_items words
+    ItemsInArgs arg_multi;     // num_multi words
 };
 DecodePlan plan_decode(const cs_batch* batch, int32_t num_kv_heads, int32_t head_dim);
 // Workspace layout (all 16-byte aligned): work items | per-sequence item offsets |

@@ -181,34 +181,54 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(
     if (tid == kPlanThreads - 1) cu_items[S] = sh_items[tid];
 }
 
-// grid = total_items * Hkv workgroups, kv head fastest (the heads of one page are neighbours
+// Where a workgroup's item comes from.
+struct ItemsInMemory { const DecodeItem* items; };     // written by decode_plan_kernel
+struct ItemsIdentity { int32_t unused; };              // no sequence is cut: item x is sequence x
+
+__device__ inline bool fetch_item(const ItemsInMemory& src, int32_t item, const int32_t*, const int32_t*, DecodeItem& it) {
+    it = src.items[item];
+    return true;
+}
+__device__ inline bool fetch_item(const ItemsIdentity&, int32_t item, const int32_t* ctx_lens, const int32_t* cu_q_lens, DecodeItem& it) {
+    it.seq = item;
+    it.token = cu_q_lens[item];
+    if (cu_q_lens[item + 1] - it.token != 1) return false;
+    it.n_keys = ctx_lens[item] + 1;
+    it.key_begin = 0;
+    it.key_end = it.n_keys;
+    it.n_splits = 1;
+    return true;
+}
+__device__ inline bool fetch_item(const ItemsInArgs& src, int32_t item, const int32_t* ctx_lens, const int32_t* cu_q_lens, DecodeItem& it) {
+    const uint32_t w = src.e[item];
+    const int32_t piece = (int32_t)((w >> 16) & 0xffu), k = (int32_t)(w >> 24);
+    it.seq = (int32_t)(w & 0xffffu);
+    it.token = cu_q_lens[it.seq];
+    it.n_keys = ctx_lens[it.seq] + 1;
+    const int32_t chunk = decode_chunk_keys(it.n_keys, k);
+    it.key_begin = k > 1 ? min(it.n_keys, piece * chunk) : 0;
+    it.key_end = k > 1 ? min(it.n_keys, (piece + 1) * chunk) : it.n_keys;
+    it.n_splits = k;
+    return true;
+}
+
+// grid = items * Hkv workgroups, kv head fastest (the heads of one page are neighbours
 // in memory, so neighbouring workgroups share DRAM pages and translations); block = 4
-// wavefronts.  kIdentity: no sequence is cut, so the
-// item list is not built at all: workgroup x is sequence x (and leaves at once if that
-// sequence is not a decode).
-template <int D, bool kIdentity>
+// wavefronts.  Src says where the item list is: in memory, in the kernel arguments, or
+// nowhere (workgroup x is sequence x and leaves at once if that sequence is not a decode).
+template <int D, class Src>
 __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
-    const DecodeItem* __restrict__ items,
+    const Src src,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out,
     float scale_log2e, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     const int32_t item = blockIdx.x / Hkv, g = blockIdx.x - item * Hkv;
     DecodeItem it;
-    if (kIdentity) {
-        it.seq = item;
-        it.token = cu_q_lens[item];
-        if (cu_q_lens[item + 1] - it.token != 1) return;
-        it.n_keys = ctx_lens[item] + 1;
-        it.key_begin = 0;
-        it.key_end = it.n_keys;
-        it.n_splits = 1;
-    } else {
-        it = items[item];
-    }
+    if (!fetch_item(src, item, ctx_lens, cu_q_lens, it)) return;
     const int32_t s = it.seq, t = it.token, n_keys = it.n_keys;
     const int32_t page_begin = it.key_begin >> 4;
     // an item can come out empty when a short sequence is cut very finely
@@ -305,16 +325,32 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
 }
 
 // Merge of the split partials of the sequences that were cut: grid = (Hq, num_multi),
-// block = D lanes.
-template <int D>
+// block = D lanes.  The list of cut sequences comes from the planning kernel or, like the
+// items, from the kernel arguments.
+struct MultiInMemory { const int32_t* multi; const int32_t* cu_items; };
+struct MultiInArgs { ItemsInArgs list; const int32_t* ctx_lens; int32_t split_tokens, total_items; };
+
+__device__ inline void fetch_multi(const MultiInMemory& src, int32_t idx, int32_t& s, int32_t& i0, int32_t& i1) {
+    s = src.multi[idx];
+    i0 = src.cu_items[s];
+    i1 = src.cu_items[s + 1];
+}
+__device__ inline void fetch_multi(const MultiInArgs& src, int32_t idx, int32_t& s, int32_t& i0, int32_t& i1) {
+    const uint32_t w = src.list.e[idx];
+    s = (int32_t)(w & 0xffffu);
+    i0 = (int32_t)(w >> 16);
+    i1 = min(src.total_items, i0 + decode_num_splits(src.ctx_lens[s] + 1, src.split_tokens));
+}
+
+template <int D, class Src>
 __global__ __launch_bounds__(D) void decode_merge_kernel(
-    const int32_t* __restrict__ multi, const int32_t* __restrict__ cu_items,
-    const int32_t* __restrict__ cu_q_lens, int32_t Hq,
+    const Src src, const int32_t* __restrict__ cu_q_lens, int32_t Hq,
     const float* __restrict__ part_o, const float* __restrict__ part_ml, uint16_t* __restrict__ out)
 {
-    const int32_t s = multi[blockIdx.y], hq = blockIdx.x, d = threadIdx.x;
+    const int32_t hq = blockIdx.x, d = threadIdx.x;
+    int32_t s, i0, i1;
+    fetch_multi(src, blockIdx.y, s, i0, i1);
     const int32_t t = cu_q_lens[s];
-    const int32_t i0 = cu_items[s], i1 = cu_items[s + 1];
     float M = -INFINITY;
     for (int32_t i = i0; i < i1; ++i) M = fmaxf(M, part_ml[((int64_t)i * Hq + hq) * 2]);
     float L = 0.f, O = 0.f;
@@ -343,28 +379,36 @@ int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, cons
     float* part_ml = (float*)(ws + w.part_ml);
     float* part_o = (float*)(ws + w.part_o);
     const bool identity = plan.num_multi == 0;
-    if (!identity)
+    const uint32_t n_items = plan.in_args ? plan.total_items : identity ? b.num_seqs : plan.total_items;
+    dim3 grid(n_items * (uint32_t)Hkv);
+    dim3 mgrid((uint32_t)Hq, (uint32_t)plan.num_multi);
+#define CS_LAUNCH_DECODE(DD, SRC, src)                                                                 \
+    hipLaunchKernelGGL((decode_split_kernel<DD, SRC>), grid, dim3(kDecodeThreads), 0, st, layer_base,  \
+                       pool.page_stride, pool.num_pages, Hkv, G, b.block_tables, b.max_blocks_per_seq, \
+                       src, b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out,               \
+                       scale_log2e, part_o, part_ml);
+#define CS_LAUNCH_MERGE(DD, SRC, src)                                                                  \
+    hipLaunchKernelGGL((decode_merge_kernel<DD, SRC>), mgrid, dim3(DD), 0, st, src, b.cu_q_lens, Hq,   \
+                       part_o, part_ml, (uint16_t*)out);
+    if (plan.in_args) {
+        if (D == 128) { CS_LAUNCH_DECODE(128, ItemsInArgs, plan.arg_items) } else { CS_LAUNCH_DECODE(64, ItemsInArgs, plan.arg_items) }
+        if (!identity) {
+            const MultiInArgs msrc = {plan.arg_multi, b.ctx_lens, plan.split_tokens, plan.total_items};
+            if (D == 128) { CS_LAUNCH_MERGE(128, MultiInArgs, msrc) } else { CS_LAUNCH_MERGE(64, MultiInArgs, msrc) }
+        }
+    } else if (identity) {
+        const ItemsIdentity src = {0};
+        if (D == 128) { CS_LAUNCH_DECODE(128, ItemsIdentity, src) } else { CS_LAUNCH_DECODE(64, ItemsIdentity, src) }
+    } else {
         hipLaunchKernelGGL(decode_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, b.num_seqs, b.ctx_lens,
                            b.cu_q_lens, plan.split_tokens, plan.total_items, plan.num_multi, items, cu_items, multi);
-    dim3 grid((uint32_t)(identity ? b.num_seqs : plan.total_items) * (uint32_t)Hkv);
-    dim3 mgrid((uint32_t)Hq, (uint32_t)plan.num_multi);
-#define CS_LAUNCH_DECODE(DD, ID)                                                                      \
-    hipLaunchKernelGGL((decode_split_kernel<DD, ID>), grid, dim3(kDecodeThreads), 0, st, layer_base,  \
-                       pool.page_stride, pool.num_pages, Hkv, G, b.block_tables, b.max_blocks_per_seq, \
-                       items, b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out,            \
-                       scale_log2e, part_o, part_ml);
-    if (identity) {
-        if (D == 128) { CS_LAUNCH_DECODE(128, true) } else { CS_LAUNCH_DECODE(64, true) }
-    } else {
-        if (D == 128) { CS_LAUNCH_DECODE(128, false) } else { CS_LAUNCH_DECODE(64, false) }
-        if (D == 128)
-            hipLaunchKernelGGL(decode_merge_kernel<128>, mgrid, dim3(128), 0, st, multi, cu_items,
-                               b.cu_q_lens, Hq, part_o, part_ml, (uint16_t*)out);
-        else
-            hipLaunchKernelGGL(decode_merge_kernel<64>, mgrid, dim3(64), 0, st, multi, cu_items,
-                               b.cu_q_lens, Hq, part_o, part_ml, (uint16_t*)out);
+        const ItemsInMemory src = {items};
+        const MultiInMemory msrc = {multi, cu_items};
+        if (D == 128) { CS_LAUNCH_DECODE(128, ItemsInMemory, src) } else { CS_LAUNCH_DECODE(64, ItemsInMemory, src) }
+        if (D == 128) { CS_LAUNCH_MERGE(128, MultiInMemory, msrc) } else { CS_LAUNCH_MERGE(64, MultiInMemory, msrc) }
     }
 #undef CS_LAUNCH_DECODE
+#undef CS_LAUNCH_MERGE
     return check_launch("decode kernels");
 }
 

@@ -61,6 +61,19 @@ def test_decode_peaked_softmax():
     assert_attention_close(out, st.oracle_attention(), "decode peaked")
 
 
+@pytest.mark.parametrize("S,split", [(880, 0), (881, 0), (1000, 128), (300, 64), (500, 64)])
+def test_decode_item_list_sources(S, split):
+    """The work-item list travels in the kernel arguments up to 880 items (longest first) and
+    is built by the planning kernel beyond that: 880 and 881 uncut sequences sit either side
+    of the limit, 1000 sequences cut at 128 keys need the planning kernel and the merge, 300
+    sequences cut at 64 keys exceed the limit through their pieces."""
+    sh = synth.Shape(4, 2, 64)
+    ctxs = synth.uniform_int(0, 300, S, synth.generator(40 + S)).tolist()
+    b = decode_batch(sh, ctxs, 41)
+    out, st, _, _ = run_step(b, 41, split=split, check_append=False)
+    assert_attention_close(out, st.oracle_attention(), "decode S=%d split=%d" % (S, split))
+
+
 def test_decode_llama8b_shrunk():
     b = synth.config_llama8b_decode(shrink=8)
     out, st, _, _ = run_step(b, 1)
