@@ -119,6 +119,44 @@ def ref_restore(pool, layer_begin, layer_end, page_ids, staging):
     return pool
 
 
+def ref_gather_tokens(pool, layer_begin, layer_end, token_slots):
+    """Token-granular checkpoint gather (paper Sec. 4.4: KV state is managed per token, and
+    after each generation step only the newly generated tokens are checkpointed).
+    token_slots[i] = page * 16 + slot names one cached token;
+        staging[l - layer_begin][i][0] = its K rows [Hkv][D],  staging[...][i][1] = its V rows,
+    i.e. plain row layout, no page format left in the buffer."""
+    L, P, _, Hkv, BD = pool.shape
+    D = BD // PAGE
+    d = np.arange(D)
+    n = len(token_slots)
+    staging = np.empty((layer_end - layer_begin, n, 2, Hkv, D), dtype=np.uint16)
+    for l in range(layer_begin, layer_end):
+        for i in range(n):
+            page, t = divmod(int(token_slots[i]), PAGE)
+            assert 0 <= page < P, "token slot out of range"
+            for h in range(Hkv):
+                staging[l - layer_begin, i, 0, h, :] = pool[l, page, 0, h, k_index(t, d, D)]
+                staging[l - layer_begin, i, 1, h, :] = pool[l, page, 1, h, v_index(t, d, D)]
+    return staging
+
+
+def ref_restore_tokens(pool, layer_begin, layer_end, token_slots, staging):
+    """Inverse of ref_gather_tokens: the rows of staging[l][i] go to the token slot
+    token_slots[i] of every layer; every other element of the pool is left untouched.
+    In place; the slots are distinct."""
+    L, P, _, Hkv, BD = pool.shape
+    D = BD // PAGE
+    d = np.arange(D)
+    for l in range(layer_begin, layer_end):
+        for i in range(len(token_slots)):
+            page, t = divmod(int(token_slots[i]), PAGE)
+            assert 0 <= page < P, "token slot out of range"
+            for h in range(Hkv):
+                pool[l, page, 0, h, k_index(t, d, D)] = staging[l - layer_begin, i, 0, h, :]
+                pool[l, page, 1, h, v_index(t, d, D)] = staging[l - layer_begin, i, 1, h, :]
+    return pool
+
+
 def bf16_bits_to_f32(bits):
     """Widen bf16 bit patterns (uint16) to float32 exactly."""
     return (np.asarray(bits).astype(np.uint32) << 16).view(np.float32)

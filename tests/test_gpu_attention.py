@@ -120,6 +120,16 @@ def test_prefill_chunks_ragged(Hq, Hkv, D):
     assert_attention_close(out, st.oracle_attention(), "prefill ragged %d/%d/%d" % (Hq, Hkv, D))
 
 
+def test_prefill_interleaved_with_decodes_and_idle():
+    # chunks, decode tokens and idle sequences in arbitrary order: workgroup slots without a
+    # tile sit between the tiles
+    sh = synth.Shape(8, 2, 128)
+    b = synth.make_batch(sh, [700, 30, 0, 0, 99, 15, 2000, 64], [40, 1, 33, 0, 1, 1, 64, 300], synth.generator(34))
+    out, st, _, _ = run_step(b, 34)
+    active = [s for s in range(b.S) if int(b.q_lens[s]) > 0]
+    assert_attention_close(out, st.oracle_attention(active), "interleaved")
+
+
 def test_prefill_first_row_is_v0_exactly():
     # the first token of a first chunk sees only itself: out = v0, exact in bf16
     sh = synth.Shape(4, 2, 64)

@@ -183,6 +183,59 @@ def test_gather_layer_range_and_duplicates():
     np.testing.assert_array_equal(p2, pool)
 
 
+def test_token_gather_returns_the_appended_rows_and_restore_inverts_it():
+    """Token-granular checkpoint: gathering the slots a step has just appended to returns
+    exactly that step's k_new / v_new rows (the append is pinned slot by slot above); restoring
+    them into other slots moves those rows and nothing else."""
+    b, pool, k_new, v_new = _tiny_pool_and_step()
+    sh = b.shape
+    kv_layout.ref_append(pool, 0, b.block_tables.numpy(), b.ctx_lens.numpy(), b.cu_q_lens.numpy(), k_new, v_new)
+    slots = []
+    for s in range(b.S):
+        for i in range(int(b.q_lens[s])):
+            pos = int(b.ctx_lens[s]) + i
+            slots.append(int(b.block_tables[s, pos // 16]) * 16 + pos % 16)
+    st = kv_layout.ref_gather_tokens(pool, 0, 1, slots)
+    assert st.shape == (1, b.T, 2, sh.Hkv, sh.D)
+    np.testing.assert_array_equal(st[0, :, 0], k_new)
+    np.testing.assert_array_equal(st[0, :, 1], v_new)
+    # restore into the slots of spare pages, in a different order of slots within the pages
+    spare = [int(p) for p in b.spare_pages.numpy()]
+    assert len(spare) * 16 >= len(slots)
+    new_slots = [spare[i // 16] * 16 + (15 - i % 16) for i in range(len(slots))]
+    before = pool.copy()
+    kv_layout.ref_restore_tokens(pool, 0, 1, new_slots, st)
+    assert (pool != before).sum() == b.T * 2 * sh.Hkv * sh.D         # the fill never equals a drawn value
+    np.testing.assert_array_equal(kv_layout.ref_gather_tokens(pool, 0, 1, new_slots), st)
+    # a restored slot reads back through a block table that names its page
+    K, V = kv_layout.read_logical(pool, 0, np.array([spare[0]]), 16)
+    for i in range(min(16, len(slots))):
+        np.testing.assert_array_equal(K[15 - i], k_new[i])
+        np.testing.assert_array_equal(V[15 - i], v_new[i])
+    # the sixteen slots of one page, gathered token by token, are the page's blob re-ordered:
+    # element counts and multiset agree with the page gather
+    page = int(b.block_tables[4, 0])
+    tok = kv_layout.ref_gather_tokens(pool, 0, 1, [page * 16 + t for t in range(16)])
+    blob = kv_layout.ref_gather(pool, 0, 1, [page])
+    np.testing.assert_array_equal(np.sort(tok.reshape(-1)), np.sort(blob.reshape(-1)))
+
+
+def test_token_gather_layer_range():
+    sh = synth.Shape(4, 2, 64, L=3)
+    g = synth.generator(7)
+    pool = bits(synth.randn_bf16((3, 5, 2, sh.Hkv, 16 * sh.D), g)).copy()
+    slots = [3 * 16 + 15, 0, 4 * 16 + 7, 3 * 16 + 15]                 # duplicates allowed in a gather
+    st = kv_layout.ref_gather_tokens(pool, 1, 3, slots)
+    assert st.shape == (2, 4, 2, sh.Hkv, sh.D)
+    np.testing.assert_array_equal(st[:, 0], st[:, 3])
+    for l in (1, 2):
+        K, V = kv_layout.read_logical(pool, l, np.array([4]), 16)
+        np.testing.assert_array_equal(st[l - 1, 2, 0], K[7])
+        np.testing.assert_array_equal(st[l - 1, 2, 1], V[7])
+    with pytest.raises(AssertionError):
+        kv_layout.ref_gather_tokens(pool, 0, 1, [5 * 16])
+
+
 def test_bf16_widening_is_exact():
     x = synth.randn_bf16((1000,), synth.generator(9))
     np.testing.assert_array_equal(kv_layout.bf16_bits_to_f32(bits(x)), x.float().numpy())
