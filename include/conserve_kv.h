@@ -132,6 +132,24 @@ int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t layer_begin, int32_t laye
                        const int32_t* page_ids, int32_t n,
                        const void* staging, size_t staging_bytes, void* stream);
 
+/* Token-granular checkpoint (Sec. 4.4: the KV state is managed per token, and after each
+ * generation step only the newly generated tokens are checkpointed).  token_slots[i] =
+ * page * 16 + slot names one cached token;
+ *     staging[l - layer_begin][i][0][h][:] = its K row of kv head h,  [...][1][h][:] = its V row
+ * (plain rows of head_dim bf16, the layout of k_new / v_new; nothing of the page format is
+ * left in the buffer).  token_slots: device [n]; a slot outside the pool is skipped.
+ * staging: device, (layer_end-layer_begin) * n * 2 * num_kv_heads * head_dim * 2 bytes,
+ * 16-byte aligned.  n == 0 is a no-op.  Whole pages are cheaper through cs_kv_ckpt_gather. */
+int cs_kv_ckpt_gather_tokens(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                             const int32_t* token_slots, int32_t n,
+                             void* staging, size_t staging_bytes, void* stream);
+
+/* The inverse copy: the rows of staging[l][i] go to token slot token_slots[i] of every layer
+ * in range; nothing else in the pool is written.  Slots must be distinct. */
+int cs_kv_ckpt_restore_tokens(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                              const int32_t* token_slots, int32_t n,
+                              const void* staging, size_t staging_bytes, void* stream);
+
 /* Incremental checkpoint to host memory and back (Sec. 4.4: checkpoint the newly filled
  * pages after each step, prefetch them back on resume; Sec. 5: gather into one contiguous
  * buffer, transfer it once, on a stream of its own so the copy overlaps the model's work --

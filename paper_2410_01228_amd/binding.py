@@ -89,7 +89,7 @@ def lib():
         L.cs_paged_attention_workspace_bytes.argtypes = [BP, i32, i32, i32]
         L.cs_paged_attention_mixed.restype = ctypes.c_int
         L.cs_paged_attention_mixed.argtypes = [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp, sz, vp]
-        for f in (L.cs_kv_ckpt_gather, L.cs_kv_ckpt_restore):
+        for f in (L.cs_kv_ckpt_gather, L.cs_kv_ckpt_restore, L.cs_kv_ckpt_gather_tokens, L.cs_kv_ckpt_restore_tokens):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
         for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp, vp]
@@ -107,7 +107,8 @@ def lib():
 
 EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
-    "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_save",
+    "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
+    "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_run_layers", "cs_debug_copy",
     "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
 ]
@@ -216,6 +217,22 @@ def cs_kv_ckpt_restore(pool: Pool, layer_begin: int, layer_end: int, page_ids: t
     _check(lib().cs_kv_ckpt_restore(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids),
                                     page_ids.numel(), _ptr(staging), staging.numel() * staging.element_size(),
                                     _stream(stream)), "cs_kv_ckpt_restore")
+
+
+def cs_kv_ckpt_gather_tokens(pool: Pool, layer_begin: int, layer_end: int, token_slots: torch.Tensor,
+                             staging: torch.Tensor, stream=None):
+    _check(lib().cs_kv_ckpt_gather_tokens(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(token_slots),
+                                          token_slots.numel(), _ptr(staging),
+                                          staging.numel() * staging.element_size(), _stream(stream)),
+           "cs_kv_ckpt_gather_tokens")
+
+
+def cs_kv_ckpt_restore_tokens(pool: Pool, layer_begin: int, layer_end: int, token_slots: torch.Tensor,
+                              staging: torch.Tensor, stream=None):
+    _check(lib().cs_kv_ckpt_restore_tokens(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(token_slots),
+                                           token_slots.numel(), _ptr(staging),
+                                           staging.numel() * staging.element_size(), _stream(stream)),
+           "cs_kv_ckpt_restore_tokens")
 
 
 def cs_kv_ckpt_save(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,

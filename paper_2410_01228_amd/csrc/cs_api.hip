@@ -229,6 +229,33 @@ int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int
     return launch_page_copy(*pool, l0, l1, ids, n, (void*)staging, false, (hipStream_t)stream);
 }
 
+static int ckpt_tokens_common(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* slots, int32_t n,
+                              const void* staging, size_t staging_bytes) {
+    int rc = validate_pool(pool);
+    if (rc) return rc;
+    if (l0 < 0 || l1 < l0 || l1 > pool->num_layers || n < 0) return CS_ERR_INVALID_ARG;
+    if (n == 0 || l1 == l0) return CS_OK;
+    if (!slots || !staging || ((uintptr_t)staging & 15)) return CS_ERR_INVALID_ARG;
+    const size_t need = (size_t)(l1 - l0) * n * 2 * pool->num_kv_heads * pool->head_dim * 2;
+    if (staging_bytes < need) return CS_ERR_STAGING_TOO_SMALL;
+    if (l1 - l0 > 65535) return CS_ERR_INVALID_ARG;
+    return 1;   // proceed
+}
+
+int cs_kv_ckpt_gather_tokens(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* token_slots, int32_t n,
+                             void* staging, size_t staging_bytes, void* stream) {
+    const int rc = ckpt_tokens_common(pool, l0, l1, token_slots, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    return launch_token_copy(*pool, l0, l1, token_slots, n, staging, true, (hipStream_t)stream);
+}
+
+int cs_kv_ckpt_restore_tokens(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* token_slots, int32_t n,
+                              const void* staging, size_t staging_bytes, void* stream) {
+    const int rc = ckpt_tokens_common(pool, l0, l1, token_slots, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    return launch_token_copy(*pool, l0, l1, token_slots, n, (void*)staging, false, (hipStream_t)stream);
+}
+
 int cs_kv_ckpt_save(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
                     void* staging, size_t staging_bytes, void* host_buf, void* stream) {
     const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);

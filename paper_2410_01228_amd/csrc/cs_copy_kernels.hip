@@ -67,6 +67,75 @@ int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_
 }
 
 // ------------------------------------------------------------------------------------
+// Token-granular checkpoint copies (paper Sec. 4.4: KV state is kept per token; after a
+// generation step only the newly generated tokens are checkpointed).  The staging buffer
+// holds plain rows, [layer][token][K|V][kv head][D]; one lane moves one 16-byte unit of a
+// row (8 features): a K unit is one 16-byte unit of the page too, a V unit is 8 elements
+// that lie 16 bytes apart in the page (one per feature's token group).
+// ------------------------------------------------------------------------------------
+constexpr int kTokenCopyThreads = 256;
+
+template <bool kToStaging>
+__global__ __launch_bounds__(kTokenCopyThreads) void token_copy_kernel(
+    uint16_t* __restrict__ pool_base, int64_t layer_stride, int64_t page_stride,
+    int32_t num_pages, int32_t layer_begin, const int32_t* __restrict__ token_slots, int32_t n,
+    uint16_t* __restrict__ staging, int32_t Hkv, int32_t D)
+{
+    const int32_t units_per_head = D / 8, units_per_side = Hkv * units_per_head;
+    const int32_t units_per_token = 2 * units_per_side;
+    const int64_t gid = (int64_t)blockIdx.x * kTokenCopyThreads + threadIdx.x;
+    if (gid >= (int64_t)n * units_per_token) return;
+    const int32_t i = (int32_t)(gid / units_per_token), u = (int32_t)(gid - (int64_t)i * units_per_token);
+    const int32_t l = blockIdx.y;
+    const int32_t slot = token_slots[i];
+    const int32_t page = slot >> 4, t = slot & (kPage - 1);
+    if (slot < 0 || page >= num_pages) return;                   // never touch a bad slot
+    const int32_t kv = u / units_per_side, r = u - kv * units_per_side;
+    const int32_t h = r / units_per_head, d8 = r - h * units_per_head;
+    uint16_t* blk = pool_base + (int64_t)(layer_begin + l) * layer_stride + (int64_t)page * page_stride
+                  + (int64_t)(kv * Hkv + h) * (kPage * D);
+    uint16_t* row = staging + ((int64_t)l * n + i) * (2 * Hkv * D) + (int64_t)u * 8;
+    if (kv == 0) {
+        u32x4* unit = (u32x4*)(blk + (d8 * kPage + t) * 8);
+        if (kToStaging) *(u32x4*)row = *unit; else *unit = *(const u32x4*)row;
+    } else {
+        // features d8*8 .. +8 of token t: element (((d/16)*2 + t/8)*16 + d%16)*8 + t%8
+        const int32_t d0 = d8 * 8;
+        uint16_t* first = blk + ((((d0 >> 4) * 2 + (t >> 3)) * 16 + (d0 & 15)) * 8 + (t & 7));
+        if (kToStaging) {
+            uint16_t e[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[j] = first[j * 8];
+            u32x4 v = { (uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
+                        (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16) };
+            *(u32x4*)row = v;
+        } else {
+            const u32x4 v = *(const u32x4*)row;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) first[j * 8] = (uint16_t)(v[j >> 1] >> ((j & 1) * 16));
+        }
+    }
+}
+
+int launch_token_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_end,
+                      const int32_t* token_slots, int32_t n, void* staging, bool to_staging, hipStream_t st)
+{
+    const int32_t layers = layer_end - layer_begin;
+    if (n == 0 || layers == 0) return CS_OK;
+    const int64_t units = (int64_t)n * 2 * pool.num_kv_heads * pool.head_dim / 8;
+    dim3 grid((uint32_t)((units + kTokenCopyThreads - 1) / kTokenCopyThreads), (uint32_t)layers);
+    if (to_staging)
+        hipLaunchKernelGGL(token_copy_kernel<true>, grid, dim3(kTokenCopyThreads), 0, st, (uint16_t*)pool.base,
+                           pool.layer_stride, pool.page_stride, pool.num_pages, layer_begin, token_slots, n,
+                           (uint16_t*)staging, pool.num_kv_heads, pool.head_dim);
+    else
+        hipLaunchKernelGGL(token_copy_kernel<false>, grid, dim3(kTokenCopyThreads), 0, st, (uint16_t*)pool.base,
+                           pool.layer_stride, pool.page_stride, pool.num_pages, layer_begin, token_slots, n,
+                           (uint16_t*)staging, pool.num_kv_heads, pool.head_dim);
+    return check_launch("token_copy_kernel");
+}
+
+// ------------------------------------------------------------------------------------
 // Plain copy: the same inner loop without the page indirection.
 // ------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kCopyThreads) void plain_copy_kernel(
@@ -100,16 +169,15 @@ int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 // owns one (page touched this step, kv head) and writes that page's K and V blocks in the
 // order they lie in memory, so every store instruction of a wavefront covers 1 KiB of
 // consecutive bytes; slots the step does not fill are simply masked out.  Sequences with a
-// single new token go through append_token_kernel below instead.  Wavefront w moves features 32w .. 32w+31:
-//   K: lane (feature block dl = lane/16, token = lane%16) loads 16 bytes of its token's row
-//      and stores them to unit (dblk*16 + token) -- consecutive lanes, consecutive units;
-//   V: lane (tile, token half, feature pair) loads one dword (two features) from each of the
-//      half's 8 token rows, regroups them into two 16-byte units (one feature x 8 tokens
-//      each) and stores 32 consecutive bytes.
+// single new token go through append_token_kernel below instead.
 // Workgroup slots are dealt to sequences as start(s) = cu_q_lens[s]/16 + 2s (a step of q
 // tokens touches at most q/16 + 2 pages), found by bisection.
 // ------------------------------------------------------------------------------------
 constexpr int kAppendThreads = 256;
+
+constexpr int kAppendPagesLog2 = 0;      // log2 of the pages one workgroup fills
+constexpr int kAppendPages = 1 << kAppendPagesLog2;
+constexpr int kAppendSlotShift = 4 + kAppendPagesLog2;
 
 __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -123,66 +191,69 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     int32_t lo = 0, hi = S;                                       // largest s with start(s) <= slot_id
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
-        if ((cu_q_lens[mid] >> 4) + 2 * mid <= slot_id) lo = mid; else hi = mid;
+        if ((cu_q_lens[mid] >> kAppendSlotShift) + 2 * mid <= slot_id) lo = mid; else hi = mid;
     }
     const int32_t s = lo;
     const int32_t t_seq = cu_q_lens[s];
     const int32_t first = ctx_lens[s];                            // the step fills positions [first, last)
     const int32_t last = first + (cu_q_lens[s + 1] - t_seq);
     if (last - first == 1) return;                               // single tokens: append_token_kernel
-    const int32_t blk = (first >> 4) + (slot_id - ((t_seq >> 4) + 2 * s));
-    const int32_t p0 = blk << 4;                                  // first position of the page
-    if (p0 >= last || blk >= max_blocks) return;
-    const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
-    if (page < 0 || page >= num_pages) return;
+    const int32_t blk0 = (first >> 4) + kAppendPages * (slot_id - ((t_seq >> kAppendSlotShift) + 2 * s));
+    if ((blk0 << 4) >= last) return;
     const int32_t block_elems = kPage * D;
-    uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
-    uint16_t* vblk = kblk + (int64_t)Hkv * block_elems;
     const int64_t row = (int64_t)Hkv * D;                         // elements between consecutive tokens
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (wave * 32 >= D) return;                                   // head_dim 64: two wavefronts suffice
-    // packed token index of page position p0 (may lie before the step's first token)
-    const int64_t tok_base = (int64_t)t_seq + (p0 - first);
 
-    {   // K: features wave*32 + dl*8 .. +8 of token lane%16
-        const int32_t tok = lane & 15, dblk = wave * 4 + (lane >> 4);
+    // Wavefront w moves features 32w .. 32w+31 of the page's 16 tokens.
+    // K: lane (feature block dl = lane/16, token = lane%16) loads the 16 bytes of its token's
+    //    row and stores them as unit dblk*16 + token.
+    // V: a 16-byte unit is one feature of 8 consecutive tokens.  Lane (tile = lane/32, token
+    //    half th = (lane/16)%2, feature f = lane%16) loads its feature from each of the half's
+    //    8 token rows and stores the unit; the unit index is 64w + lane.
+    // Either way consecutive lanes store consecutive units: 1 KiB per store instruction.
+    const int32_t tok = lane & 15, dblk = wave * 4 + (lane >> 4);
+    const int32_t th = (lane >> 4) & 1, feat = wave * 32 + (lane >> 5) * 16 + (lane & 15);
+    uint16_t* kblk[kAppendPages];
+    bool k_ok[kAppendPages], v_full[kAppendPages], v_part[kAppendPages];
+    u32x4 kv[kAppendPages];
+    uint16_t e[kAppendPages][8];
+    const uint16_t* vsrc[kAppendPages];
+    int32_t vpos[kAppendPages];
+#pragma unroll
+    for (int p = 0; p < kAppendPages; ++p) {
+        const int32_t blk = blk0 + p, p0 = blk << 4;              // first position of the page
+        int32_t page = -1;
+        if (p0 < last && blk < max_blocks) page = block_tables[(int64_t)s * max_blocks + blk];
+        const bool ok = page >= 0 && page < num_pages;
+        kblk[p] = layer_base + (int64_t)(ok ? page : 0) * page_stride + (int64_t)h * block_elems;
+        // packed token index of page position p0 (may lie before the step's first token)
+        const int64_t tok_base = (int64_t)t_seq + (p0 - first);
         const int32_t pos = p0 + tok;
-        if (pos >= first && pos < last) {
-            const u32x4 v = *(const u32x4*)(k_new + ((tok_base + tok) * Hkv + h) * D + dblk * 8);
-            *(u32x4*)(kblk + (dblk * 16 + tok) * 8) = v;
+        k_ok[p] = ok && pos >= first && pos < last;
+        if (k_ok[p]) kv[p] = __builtin_nontemporal_load((const u32x4*)(k_new + ((tok_base + tok) * Hkv + h) * D + dblk * 8));
+        vpos[p] = p0 + th * 8;                                    // first position of the half
+        vsrc[p] = v_new + ((tok_base + th * 8) * Hkv + h) * D + feat;
+        v_full[p] = ok && vpos[p] >= first && vpos[p] + 8 <= last;
+        v_part[p] = ok && !v_full[p];
+        if (v_full[p]) {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) e[p][j] = __builtin_nontemporal_load(vsrc[p] + j * row);
         }
     }
-    if (wave * 64 < D) {
-        // V: a 16-byte unit is one feature of 8 consecutive tokens.  Lane (tile dtl = lane/16,
-        // token half th = (lane/8)%2, feature pair i = lane%8) loads one dword (two features)
-        // from each of the half's 8 token rows and regroups them into two units; wavefront w
-        // covers features 64w .. 64w+63, the lanes of a (tile, half) write 256 consecutive bytes.
-        const int32_t dt = wave * 4 + (lane >> 4), th = (lane >> 3) & 1, i = lane & 7;
-        const int32_t pos = p0 + th * 8;                          // first position of the half
-        const uint16_t* src = v_new + ((tok_base + th * 8) * Hkv + h) * D + dt * 16 + 2 * i;
-        uint16_t* dst = vblk + ((dt * 2 + th) * 16 + 2 * i) * 8;  // two adjacent 16-byte units
-        if (pos >= first && pos + 8 <= last) {
-            uint32_t w[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) w[j] = *(const uint32_t*)(src + j * row);
-            u32x4 lo, hi;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                lo[j] = (w[2 * j] & 0xffffu) | (w[2 * j + 1] << 16);          // feature 2i:   tokens 2j, 2j+1
-                hi[j] = (w[2 * j] >> 16) | (w[2 * j + 1] & 0xffff0000u);      // feature 2i+1
-            }
-            *(u32x4*)dst = lo;
-            *(u32x4*)(dst + 8) = hi;
-        } else {
+    for (int p = 0; p < kAppendPages; ++p) {
+        if (k_ok[p]) __builtin_nontemporal_store(kv[p], (u32x4*)(kblk[p] + (dblk * 16 + tok) * 8));
+        uint16_t* dst = kblk[p] + (int64_t)Hkv * block_elems + (wave * 64 + lane) * 8;
+        if (v_full[p]) {
+            const u32x4 unit = { (uint32_t)e[p][0] | ((uint32_t)e[p][1] << 16), (uint32_t)e[p][2] | ((uint32_t)e[p][3] << 16),
+                                 (uint32_t)e[p][4] | ((uint32_t)e[p][5] << 16), (uint32_t)e[p][6] | ((uint32_t)e[p][7] << 16) };
+            __builtin_nontemporal_store(unit, (u32x4*)dst);
+        } else if (v_part[p]) {
             // a half the step fills only partly: element by element
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                if (pos + j >= first && pos + j < last) {
-                    const uint32_t w = *(const uint32_t*)(src + j * row);
-                    dst[j] = (uint16_t)(w & 0xffffu);
-                    dst[8 + j] = (uint16_t)(w >> 16);
-                }
-            }
+            for (int j = 0; j < 8; ++j)
+                if (vpos[p] + j >= first && vpos[p] + j < last) dst[j] = vsrc[p][j * row];
         }
     }
 }
@@ -250,7 +321,7 @@ int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
     }
     uint16_t* layer_base = (uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     if (any_chunk) {
-        const int64_t slots = (int64_t)(b.num_tokens >> 4) + 2ll * b.num_seqs;
+        const int64_t slots = (int64_t)(b.num_tokens >> kAppendSlotShift) + 2ll * b.num_seqs;
         const int64_t blocks = slots * pool.num_kv_heads;
         if (blocks > 2147483647ll) return CS_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(append_page_kernel, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,

@@ -178,6 +178,28 @@ def test_preemption_drops_offline_tail_without_touching_online_rows():
     assert torch.isnan(out_on[T_on:].float()).all()                  # offline rows were not written
 
 
+def test_online_prefill_with_offline_decodes():
+    """The other mix the paper describes (Sec. 4.2): an online request in its prefill phase
+    batched with offline requests that are decoding.  Online sequences still come first, so
+    cutting the batch after them leaves the online rows bit-identical."""
+    sh = synth.Shape(28, 4, 128)
+    ctx = [0, 300, 1200, 64, 2047, 801, 33, 1500, 500]
+    ql = [200, 96, 1, 1, 1, 1, 1, 1, 64]          # 2 online prompts + 2 online decodes | 4 offline decodes + 1 offline chunk
+    n_on = 4
+    b = synth.make_batch(sh, ctx, ql, synth.generator(35))
+    out, st, pool, bb = run_step(b, 35)
+    assert_attention_close(out, st.oracle_attention(), "online prefill + offline decode")
+    bb_on = bb.truncated(n_on)
+    out_on = torch.full_like(out, float("nan"))
+    cs.cs_paged_attention_mixed(pool, 0, bb_on, st.q.cuda(), out_on, sh.Hq, sh.scale,
+                                cs.workspace_for(bb_on, sh.Hq, sh.Hkv, sh.D))
+    torch.cuda.synchronize()
+    T_on = int(b.cu_q_lens[n_on])
+    assert_attention_close(out_on[:T_on], st.oracle_attention(list(range(n_on)))[:T_on], "online prefix alone")
+    assert (out[:T_on].float() - out_on[:T_on].float()).abs().max().item() <= 2e-2
+    assert torch.isnan(out_on[T_on:].float()).all()                 # offline rows are not touched
+
+
 def test_page_permutation_leaves_output_bit_identical():
     sh = synth.Shape(8, 2, 128)
     ctx, ql = [100, 700, 31, 0, 260], [1, 1, 1, 48, 33]

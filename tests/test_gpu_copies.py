@@ -117,6 +117,94 @@ def test_gather_restore_multilayer(L, P, Hkv, D, n, lrange, strided):
     np.testing.assert_array_equal(after, expect_flat)
 
 
+@pytest.mark.parametrize("L,P,Hkv,D,n,lrange,strided", [
+    (3, 40, 8, 128, 300, (0, 3), False),
+    (4, 33, 4, 128, 77, (1, 3), False),
+    (2, 21, 3, 64, 21 * 16, (0, 2), True),    # every slot of the pool, padded strides
+    (2, 9, 2, 64, 1, (1, 2), False),
+])
+def test_token_gather_restore(L, P, Hkv, D, n, lrange, strided):
+    """Token-granular checkpoint: bit-exact against the oracle, pool untouched by the gather,
+    restore writes the named slots and nothing else (padding included)."""
+    rng = np.random.default_rng(L * 1000 + P + n)
+    pe = kv_layout.page_elems(Hkv, D)
+    ps = pe + 64 if strided else pe
+    ls = P * ps + (128 if strided else 0)
+    flat = rng.integers(0, 2 ** 16, size=L * ls, dtype=np.uint16)
+    dev = from_bits(flat, "cuda")
+    pool = cs.Pool(dev, L, P, Hkv, D, layer_stride=ls, page_stride=ps)
+
+    def view(a):
+        return np.lib.stride_tricks.as_strided(a, (L, P, pe), (ls * 2, ps * 2, 2))
+
+    slots = rng.permutation(P * 16)[:n].astype(np.int32)
+    l0, l1 = lrange
+    staging = torch.full(((l1 - l0), n, 2, Hkv, D), -1.0, dtype=torch.bfloat16, device="cuda")
+    cs.cs_kv_ckpt_gather_tokens(pool, l0, l1, torch.from_numpy(slots).cuda(), staging)
+    torch.cuda.synchronize()
+    cpu = view(flat).reshape(L, P, 2, Hkv, 16 * D).copy()
+    want = kv_layout.ref_gather_tokens(cpu, l0, l1, slots)
+    np.testing.assert_array_equal(bits(staging), want)
+    np.testing.assert_array_equal(bits(dev), flat)
+    dst = rng.permutation(P * 16)[:n].astype(np.int32)
+    cs.cs_kv_ckpt_restore_tokens(pool, l0, l1, torch.from_numpy(dst).cuda(), staging)
+    torch.cuda.synchronize()
+    after = bits(dev)
+    kv_layout.ref_restore_tokens(cpu, l0, l1, dst, want)
+    expect_flat = flat.copy()
+    view(expect_flat)[...] = cpu.reshape(L, P, pe)
+    np.testing.assert_array_equal(after, expect_flat)
+
+
+def test_token_checkpoint_of_a_decode_step_restores_attention():
+    """The paper's per-step use: checkpoint the tokens a decode step has just appended, drop
+    them, bring them back into fresh pages, and the next attention call is bit-identical."""
+    b = synth.config_llama8b_decode(shrink=16)
+    sh = b.shape
+    st = Step(b, 5)
+    cpu_pool = st.prior_pool()
+    pool = _dev_pool(cpu_pool, sh)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    cs.cs_kv_append(pool, 0, bb, st.k_new.cuda(), st.v_new.cuda())
+    q = st.q.cuda()
+    out = torch.empty_like(q)
+    cs.cs_paged_attention_mixed(pool, 0, bb, q, out, sh.Hq, sh.scale, cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D))
+    pos = b.ctx_lens.long()
+    pages = b.block_tables[torch.arange(b.S), pos // 16].long()
+    slots = (pages * 16 + pos % 16).to(torch.int32).cuda()
+    staging = torch.empty((1, b.S, 2, sh.Hkv, sh.D), dtype=torch.bfloat16, device="cuda")
+    cs.cs_kv_ckpt_gather_tokens(pool, 0, 1, slots, staging)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(staging[0, :, 0]), bits(st.k_new))
+    np.testing.assert_array_equal(bits(staging[0, :, 1]), bits(st.v_new))
+    # overwrite the new tokens' slots with NaN bits, then restore them from the buffer
+    junk = torch.full_like(staging, float("nan"))
+    cs.cs_kv_ckpt_restore_tokens(pool, 0, 1, slots, junk)
+    cs.cs_kv_ckpt_restore_tokens(pool, 0, 1, slots, staging)
+    out2 = torch.empty_like(q)
+    cs.cs_paged_attention_mixed(pool, 0, bb, q, out2, sh.Hq, sh.scale, cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D))
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), out2.view(torch.int16))
+
+
+def test_token_gather_bad_slots_and_errors():
+    pool = cs.Pool.empty(2, 8, 2, 64)
+    pool.tensor.view(torch.int16).fill_(0x1234)
+    staging = torch.zeros((2, 3, 2, 2, 64), dtype=torch.bfloat16, device="cuda")
+    cs.cs_kv_ckpt_gather_tokens(pool, 0, 2, torch.zeros(0, dtype=torch.int32, device="cuda"), staging)
+    slots = torch.tensor([5 * 16 + 3, -1, 8 * 16], dtype=torch.int32, device="cuda")   # -1 and page 8 are outside
+    cs.cs_kv_ckpt_gather_tokens(pool, 0, 2, slots, staging)
+    torch.cuda.synchronize()
+    s = staging.view(torch.int16).cpu()
+    assert s[:, 0].eq(0x1234).all() and s[:, 1:].eq(0).all()
+    with pytest.raises(cs.CsError) as e:
+        cs.cs_kv_ckpt_gather_tokens(pool, 0, 2, slots, staging[:1])
+    assert e.value.status == cs.CS_ERR_STAGING_TOO_SMALL
+    with pytest.raises(cs.CsError) as e:
+        cs.cs_kv_ckpt_restore_tokens(pool, 1, 3, slots, staging)
+    assert e.value.status == cs.CS_ERR_INVALID_ARG
+
+
 def test_gather_zero_pages_and_bad_ids_are_harmless():
     pool = cs.Pool.empty(2, 8, 2, 64)
     pool.tensor.view(torch.int16).fill_(0x1234)
