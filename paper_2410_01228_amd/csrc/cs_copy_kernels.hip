@@ -186,8 +186,12 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
 {
-    const int32_t h = blockIdx.x % Hkv;
-    const int32_t slot_id = blockIdx.x / Hkv;
+    // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Groups of 8 page
+    // slots are numbered head-major, so the workgroups of one page -- which together read
+    // whole token rows and write one whole page -- all land on the same XCD.
+    const int32_t group = blockIdx.x / (8 * Hkv), in_group = blockIdx.x - group * (8 * Hkv);
+    const int32_t h = in_group >> 3;
+    const int32_t slot_id = group * 8 + (in_group & 7);
     int32_t lo = 0, hi = S;                                       // largest s with start(s) <= slot_id
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
@@ -321,7 +325,7 @@ int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
     }
     uint16_t* layer_base = (uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     if (any_chunk) {
-        const int64_t slots = (int64_t)(b.num_tokens >> kAppendSlotShift) + 2ll * b.num_seqs;
+        const int64_t slots = (((int64_t)(b.num_tokens >> kAppendSlotShift) + 2ll * b.num_seqs) + 7) & ~7ll;   // whole groups of 8
         const int64_t blocks = slots * pool.num_kv_heads;
         if (blocks > 2147483647ll) return CS_ERR_UNSUPPORTED;
         hipLaunchKernelGGL(append_page_kernel, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
