@@ -25,23 +25,25 @@ MFMA_BF16_PEAK = 2.5e15      # FLOP/s, dense bf16
 
 WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b_ckpt"]
 # the kernel behind the call a roofline line is quoted for
-KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, cs::ItemsInArgs> (the call's only kernel here)",
+KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16> (the call's only kernel here)",
              ("qwen14b_ckpt", "ckpt_gather"): "cs::page_copy_kernel<true>",
-             ("qwen7b_mixed", "prefill_only"): "cs::prefill_kernel<128>",
-             ("llama70b_long", "prefill_only"): "cs::prefill_kernel<128>"}
+             ("qwen7b_mixed", "prefill_only"): "cs::prefill_kernel<128, cs::Bf16>",
+             ("llama70b_long", "prefill_only"): "cs::prefill_kernel<128, cs::Bf16>"}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def fill_randn_bf16(t, gen):
-    """N(0,1) rounded to bf16, written in place in chunks (t is a flat bf16 device tensor)."""
+def fill_randn_bf16(t, gen, dtype=None):
+    """N(0,1) rounded to bf16 (or to `dtype`, stored bit for bit), written in place in chunks
+    (t is a flat bf16 device tensor)."""
     import torch
     step = 1 << 27
     for o in range(0, t.numel(), step):
         n = min(step, t.numel() - o)
-        t[o:o + n] = torch.randn(n, generator=gen, device=t.device, dtype=torch.float32).to(torch.bfloat16)
+        r = torch.randn(n, generator=gen, device=t.device, dtype=torch.float32)
+        t[o:o + n] = r.to(torch.bfloat16) if dtype in (None, torch.bfloat16) else r.to(dtype).view(torch.bfloat16)
 
 
 class Leg:
@@ -76,11 +78,14 @@ def attention_work(b, seqs=None):
     return dec_bytes, pre_flops, pre_bytes
 
 
-def build(name):
-    """Allocate and fill the workload on the GPU; returns (batch, legs, dominant leg name, info)."""
+def build(name, f16=False):
+    """Allocate and fill the workload on the GPU; returns (batch, legs, dominant leg name, info).
+    f16: the pool and the queries hold IEEE half and the fp16 attention entry point is timed."""
     import torch
     from paper_2410_01228_amd import binding as cs
     from paper_2410_01228_amd import synth
+    edt = torch.float16 if f16 else torch.bfloat16
+    attend = cs.cs_paged_attention_mixed_f16 if f16 else cs.cs_paged_attention_mixed
 
     idx = WORKLOADS.index(name)
     b = synth.CONFIGS[idx]()
@@ -88,12 +93,13 @@ def build(name):
     gen = torch.Generator(device="cuda")
     gen.manual_seed(synth.BASE_SEED + idx)
     pool = cs.Pool.empty(sh.L, b.num_pages, sh.Hkv, sh.D)
-    fill_randn_bf16(pool.tensor.view(-1), gen)
+    fill_randn_bf16(pool.tensor.view(-1), gen, edt)
     bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
     T = b.T
-    q = synth.randn_bf16((T, sh.Hq, sh.D), gen, "cuda")
-    k_new = synth.randn_bf16((T, sh.Hkv, sh.D), gen, "cuda")
-    v_new = synth.randn_bf16((T, sh.Hkv, sh.D), gen, "cuda")
+    draw = synth.randn_f16 if f16 else synth.randn_bf16
+    q = draw((T, sh.Hq, sh.D), gen, "cuda")
+    k_new = draw((T, sh.Hkv, sh.D), gen, "cuda")
+    v_new = draw((T, sh.Hkv, sh.D), gen, "cuda")
     out = torch.empty_like(q)
     ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
     keep = [pool, bb, q, k_new, v_new, out, ws]
@@ -113,7 +119,7 @@ def build(name):
     legs.append(Leg("kv_append", lambda: cs.cs_kv_append(pool, layer[0], bb, k_new, v_new), "hbm", append_bytes))
     att_bound = "hbm" if pre_flops / MFMA_BF16_PEAK < dec_bytes / HBM_PEAK else "mfma"
     legs.append(Leg("paged_attention_mixed",
-                    lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb, q, out, sh.Hq, sh.scale, ws),
+                    lambda: attend(pool, layer[0], bb, q, out, sh.Hq, sh.scale, ws),
                     att_bound, dec_bytes if att_bound == "hbm" else pre_flops))
 
     detail = []
@@ -129,9 +135,9 @@ def build(name):
         q_pre, out_pre = q[T_on:], out[T_on:]
         ws_pre = cs.workspace_for(bb_pre, sh.Hq, sh.Hkv, sh.D)
         keep += [bb_dec, ws_dec, bb_pre, q_pre, out_pre, ws_pre]
-        detail.append(Leg("decode_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_dec, q, out, sh.Hq, sh.scale, ws_dec),
+        detail.append(Leg("decode_only", lambda: attend(pool, layer[0], bb_dec, q, out, sh.Hq, sh.scale, ws_dec),
                           "hbm", dec_bytes))
-        detail.append(Leg("prefill_only", lambda: cs.cs_paged_attention_mixed(pool, layer[0], bb_pre, q_pre, out_pre, sh.Hq, sh.scale, ws_pre),
+        detail.append(Leg("prefill_only", lambda: attend(pool, layer[0], bb_pre, q_pre, out_pre, sh.Hq, sh.scale, ws_pre),
                           "mfma", pre_flops))
     info = {"T": T, "S": b.S, "dec_bytes": dec_bytes, "pre_flops": pre_flops, "pre_bytes": pre_bytes,
             "append_bytes": append_bytes, "pool_gb": pool.tensor.numel() * 2 / 1e9, "name": b.name,
@@ -437,6 +443,8 @@ def main():
     ap.add_argument("--workload", default="llama8b_decode", choices=WORKLOADS)
     ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
+                    help="element type of the pool and the queries (f16: the fp16 attention entry point)")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
     ap.add_argument("--append-sweep", action="store_true", help="also time cs_kv_append over growing token counts")
     ap.add_argument("--fit-latency-model", action="store_true",
@@ -464,7 +472,7 @@ def main():
         torch.cuda.synchronize()
         log("calibration: plain_copy_kernel moved %d bytes (read) + %d bytes (written) per launch" % (n, n))
         del src, dst
-    b, legs, detail, info = build(args.workload)
+    b, legs, detail, info = build(args.workload, f16=args.dtype == "f16")
     log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
         % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))
     sec_per_step = time_legs(legs, args.steps, args.warmup)
@@ -492,7 +500,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(sec_per_step * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
+        "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
                    "page_size": 16, "layers_per_step": 1,
                    "step": "+".join(l.name for l in legs)},

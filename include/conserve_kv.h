@@ -12,7 +12,7 @@
  *   - every pointer is owned by the caller and must stay valid until the enqueued work has
  *     run.  "device" pointers are HIP device memory of the current device, "host" pointers
  *     are ordinary host memory read during the call only;
- *   - bf16 data only, 16 tokens per page (the paper's page granularity, Sec. 5),
+ *   - 16-bit data (bf16; fp16 through cs_paged_attention_mixed_f16), 16 tokens per page (the paper's page granularity, Sec. 5),
  *     head_dim 64 or 128, num_q_heads / num_kv_heads <= 16;
  *   - each call works on ONE decoder layer (attention, append) or a layer range (gather,
  *     restore), so that a scheduler can stop between layers (layer-wise preemption,
@@ -115,6 +115,15 @@ int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_bat
                              const void* q, void* out, int32_t num_q_heads,
                              float softmax_scale, void* workspace, size_t workspace_bytes,
                              void* stream);
+
+/* The same call for IEEE half data (the precision the paper's system served in, Sec. 6.1):
+ * the pool, q and out hold fp16 instead of bf16; scores, softmax and accumulation stay in
+ * fp32.  The pool format and every other call (append, gather, restore) only move 16-bit
+ * words and serve both element types unchanged. */
+int cs_paged_attention_mixed_f16(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                                 const void* q, void* out, int32_t num_q_heads,
+                                 float softmax_scale, void* workspace, size_t workspace_bytes,
+                                 void* stream);
 
 /* Checkpoint gather (Sec. 5: the KV of scattered pages is gathered into one contiguous
  * buffer and transferred once; Sec. 4.4: only newly filled pages are checkpointed).

@@ -87,8 +87,8 @@ def lib():
         L.cs_kv_append.restype, L.cs_kv_append.argtypes = ctypes.c_int, [PP, i32, BP, vp, vp, vp]
         L.cs_paged_attention_workspace_bytes.restype = sz
         L.cs_paged_attention_workspace_bytes.argtypes = [BP, i32, i32, i32]
-        L.cs_paged_attention_mixed.restype = ctypes.c_int
-        L.cs_paged_attention_mixed.argtypes = [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp, sz, vp]
+        for f in (L.cs_paged_attention_mixed, L.cs_paged_attention_mixed_f16):
+            f.restype, f.argtypes = ctypes.c_int, [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp, sz, vp]
         for f in (L.cs_kv_ckpt_gather, L.cs_kv_ckpt_restore, L.cs_kv_ckpt_gather_tokens, L.cs_kv_ckpt_restore_tokens):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
         for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
@@ -107,7 +107,7 @@ def lib():
 
 EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
-    "cs_paged_attention_mixed", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
+    "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_run_layers", "cs_debug_copy",
     "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
@@ -203,6 +203,14 @@ def cs_paged_attention_mixed(pool: Pool, layer: int, batch: Batch, q: torch.Tens
     _check(lib().cs_paged_attention_mixed(ctypes.byref(pool.c), layer, ctypes.byref(batch.c), _ptr(q), _ptr(out),
                                           Hq, softmax_scale, _ptr(workspace), wb, _stream(stream)),
            "cs_paged_attention_mixed")
+
+
+def cs_paged_attention_mixed_f16(pool: Pool, layer: int, batch: Batch, q: torch.Tensor, out: torch.Tensor,
+                                 Hq: int, softmax_scale: float, workspace: Optional[torch.Tensor], stream=None):
+    wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib().cs_paged_attention_mixed_f16(ctypes.byref(pool.c), layer, ctypes.byref(batch.c), _ptr(q),
+                                              _ptr(out), Hq, softmax_scale, _ptr(workspace), wb, _stream(stream)),
+           "cs_paged_attention_mixed_f16")
 
 
 def cs_kv_ckpt_gather(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,

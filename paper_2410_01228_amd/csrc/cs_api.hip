@@ -175,9 +175,9 @@ size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t Hq, int
     return decode_workspace(p, batch->num_seqs, Hq, D).total + pp.bytes;
 }
 
-int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
-                             const void* q, void* out, int32_t Hq, float softmax_scale,
-                             void* workspace, size_t workspace_bytes, void* stream) {
+static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                           const void* q, void* out, int32_t Hq, float softmax_scale,
+                           void* workspace, size_t workspace_bytes, void* stream, bool f16) {
     int rc = validate_pool(pool);
     if (rc) return rc;
     if (layer < 0 || layer >= pool->num_layers) return CS_ERR_INVALID_ARG;
@@ -196,10 +196,22 @@ int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_bat
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
     if (plan.num_prefill > 0) {
-        rc = launch_prefill(*pool, layer, *batch, pplan, q, out, Hq, softmax_scale, (char*)workspace + decode_bytes, st);
+        rc = launch_prefill(*pool, layer, *batch, pplan, q, out, Hq, softmax_scale, (char*)workspace + decode_bytes, st, f16);
         if (rc) return rc;
     }
-    return launch_decode(*pool, layer, *batch, plan, q, out, Hq, softmax_scale, workspace, st);
+    return launch_decode(*pool, layer, *batch, plan, q, out, Hq, softmax_scale, workspace, st, f16);
+}
+
+int cs_paged_attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                             const void* q, void* out, int32_t Hq, float softmax_scale,
+                             void* workspace, size_t workspace_bytes, void* stream) {
+    return attention_mixed(pool, layer, batch, q, out, Hq, softmax_scale, workspace, workspace_bytes, stream, false);
+}
+
+int cs_paged_attention_mixed_f16(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                                 const void* q, void* out, int32_t Hq, float softmax_scale,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    return attention_mixed(pool, layer, batch, q, out, Hq, softmax_scale, workspace, workspace_bytes, stream, true);
 }
 
 static int ckpt_common(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,

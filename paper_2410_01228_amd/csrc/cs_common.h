@@ -71,8 +71,9 @@ int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_
 int launch_token_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_end,
                       const int32_t* token_slots, int32_t n, void* staging, bool to_staging, hipStream_t st);
 int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
+// f16: the pool, q and out hold IEEE half instead of bf16.
 int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
-                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st);
+                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16);
 // Key-range split of the prefill path (pure function of the host lengths).
 struct PrefillPlan {
     int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
@@ -83,6 +84,6 @@ struct PrefillPlan {
 };
 PrefillPlan plan_prefill(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
 int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
-                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st);
+                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16);
 
 }  // namespace cs

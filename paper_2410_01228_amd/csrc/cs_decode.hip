@@ -7,29 +7,21 @@
 // unnormalised output) per split; a second kernel merges the splits.
 //
 // Tile algebra per 16-token page and kv head (G = query heads sharing it, padded to 16):
-//   S^T[token][head] = K[token][:] . Q[head][:]      v_mfma_f32_16x16x32_bf16, D/32 steps
-//   O^T[d][head]    += V^T[d][token] . P^T[token][head]   v_mfma_f32_16x16x16_bf16, D/16 tiles
+//   S^T[token][head] = K[token][:] . Q[head][:]      v_mfma_f32_16x16x32_{bf16,f16}, D/32 steps
+//   O^T[d][head]    += V^T[d][token] . P^T[token][head]   v_mfma_f32_16x16x16_{bf16,f16}, D/16 tiles
 // The C layout of S^T (lane = head + 16*(token/4), register = token%4) is exactly the B
 // layout the second product wants, so P never leaves its registers.
 #include "cs_common.h"
+#include "cs_elem.h"
 
 namespace cs {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kDecodeWaves = 4;
 constexpr int kDecodeThreads = kDecodeWaves * 64;
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-    // round-to-nearest-even conversion of two floats into one dword of bf16
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    bf16x2 v = { (__bf16)lo, (__bf16)hi };
-    return __builtin_bit_cast(uint32_t, v);
-}
 
 __device__ __forceinline__ float xor_max(float v, int mask) {
     return fmaxf(v, __shfl_xor(v, mask, 64));
@@ -67,14 +59,14 @@ struct WaveState {
     float l;             // this lane's share of the running sum
 };
 
-template <int D>
-__device__ __forceinline__ void process_page(WaveState<D>& st, const PageRegs<D>& r, const bf16x8* qb,
+template <int D, class E>
+__device__ __forceinline__ void process_page(WaveState<D>& st, const PageRegs<D>& r, const u32x4* qb,
                                              float scale_log2e, int32_t tok0, int32_t n_keys, int lane)
 {
     f32x4 s = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
-        s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, r.k[kk]), qb[kk], s, 0, 0, 0);
+        s = E::mfma32(r.k[kk], qb[kk], s);
     const int32_t row0 = tok0 + (lane >> 4) * 4;      // first of this lane's 4 tokens
     const bool tail = tok0 + kPage > n_keys;           // wave-uniform
     float x[4];
@@ -97,11 +89,9 @@ __device__ __forceinline__ void process_page(WaveState<D>& st, const PageRegs<D>
     float p[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - st.m);
-    u32x2 pb = { pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]) };
-    // the sum uses the same bf16-rounded weights that multiply V
-    st.l += (__builtin_bit_cast(float, pb[0] << 16) + __builtin_bit_cast(float, pb[0] & 0xffff0000u))
-          + (__builtin_bit_cast(float, pb[1] << 16) + __builtin_bit_cast(float, pb[1] & 0xffff0000u));
-    const s16x4 pbv = __builtin_bit_cast(s16x4, pb);
+    u32x2 pb = { E::pack(p[0], p[1]), E::pack(p[2], p[3]) };
+    // the sum uses the same rounded weights that multiply V
+    st.l += E::sum2(pb[0]) + E::sum2(pb[1]);
     if (tail) {
         // slots past the sequence end hold stale bits (possibly NaN): zero them so 0 * x stays 0
         const int32_t valid = n_keys - row0;           // tokens of this lane's group that exist
@@ -111,12 +101,12 @@ __device__ __forceinline__ void process_page(WaveState<D>& st, const PageRegs<D>
         for (int dt = 0; dt < D / 16; ++dt) {
             u32x2 v = r.v[dt];
             v[0] &= m0; v[1] &= m1;
-            st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, v), pbv, st.o[dt], 0, 0, 0);
+            st.o[dt] = E::mfma16(v, pb, st.o[dt]);
         }
     } else {
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt)
-            st.o[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, r.v[dt]), pbv, st.o[dt], 0, 0, 0);
+            st.o[dt] = E::mfma16(r.v[dt], pb, st.o[dt]);
     }
 }
 
@@ -216,7 +206,7 @@ __device__ inline bool fetch_item(const ItemsInArgs& src, int32_t item, const in
 // in memory, so neighbouring workgroups share DRAM pages and translations); block = 4
 // wavefronts.  Src says where the item list is: in memory, in the kernel arguments, or
 // nowhere (workgroup x is sequence x and leaves at once if that sequence is not a decode).
-template <int D, class Src>
+template <int D, class Src, class E>
 __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G,
@@ -240,7 +230,7 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
 
     // Q as the B operand of S^T = K.Q^T: lane (head = lane%16, k-group = lane/16) holds
     // features kk*32 + (lane/16)*8 .. +8 of head g*G + lane%16; heads >= G are zero rows.
-    bf16x8 qb[D / 32];
+    u32x4 qb[D / 32];
     {
         const int head = lane & 15;
         const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -249,7 +239,7 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
             u32x4 v = zero;
             if (head < G)
                 v = *(const u32x4*)(q + ((int64_t)t * Hq + g * G + head) * D + kk * 32 + (lane >> 4) * 8);
-            qb[kk] = __builtin_bit_cast(bf16x8, v);
+            qb[kk] = v;
         }
     }
 
@@ -274,7 +264,7 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
         const bool ok_n = have_n && id_nxt >= 0 && id_nxt < num_pages;
         if (ok_n) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
         if (id_cur >= 0 && id_cur < num_pages)
-            process_page<D>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
+            process_page<D, E>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
         cur = nxt;
         id_cur = id_nxt;
         id_nxt = id_n2;
@@ -315,7 +305,7 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
         const int32_t hq = g * G + head;
         if (it.n_splits == 1) {
             const float r = O / L;
-            out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(pack_bf16(r, 0.f) & 0xffffu);
+            out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(E::pack(r, 0.f) & 0xffffu);
         } else {
             const int64_t slot = (int64_t)item * Hq + hq;
             part_o[slot * D + d] = O;
@@ -342,7 +332,7 @@ __device__ inline void fetch_multi(const MultiInArgs& src, int32_t idx, int32_t&
     i1 = min(src.total_items, i0 + decode_num_splits(src.ctx_lens[s] + 1, src.split_tokens));
 }
 
-template <int D, class Src>
+template <int D, class Src, class E>
 __global__ __launch_bounds__(D) void decode_merge_kernel(
     const Src src, const int32_t* __restrict__ cu_q_lens, int32_t Hq,
     const float* __restrict__ part_o, const float* __restrict__ part_ml, uint16_t* __restrict__ out)
@@ -361,11 +351,12 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(
         L += part_ml[slot * 2 + 1] * f;
         O += part_o[slot * D + d] * f;
     }
-    out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(pack_bf16(O / L, 0.f) & 0xffffu);
+    out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(E::pack(O / L, 0.f) & 0xffffu);
 }
 
-int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
-                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
+template <class E>
+static int launch_decode_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
+                            const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
 {
     if (plan.num_decode == 0) return CS_OK;
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
@@ -383,12 +374,12 @@ int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, cons
     dim3 grid(n_items * (uint32_t)Hkv);
     dim3 mgrid((uint32_t)Hq, (uint32_t)plan.num_multi);
 #define CS_LAUNCH_DECODE(DD, SRC, src)                                                                 \
-    hipLaunchKernelGGL((decode_split_kernel<DD, SRC>), grid, dim3(kDecodeThreads), 0, st, layer_base,  \
+    hipLaunchKernelGGL((decode_split_kernel<DD, SRC, E>), grid, dim3(kDecodeThreads), 0, st, layer_base,  \
                        pool.page_stride, pool.num_pages, Hkv, G, b.block_tables, b.max_blocks_per_seq, \
                        src, b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out,               \
                        scale_log2e, part_o, part_ml);
 #define CS_LAUNCH_MERGE(DD, SRC, src)                                                                  \
-    hipLaunchKernelGGL((decode_merge_kernel<DD, SRC>), mgrid, dim3(DD), 0, st, src, b.cu_q_lens, Hq,   \
+    hipLaunchKernelGGL((decode_merge_kernel<DD, SRC, E>), mgrid, dim3(DD), 0, st, src, b.cu_q_lens, Hq,   \
                        part_o, part_ml, (uint16_t*)out);
     if (plan.in_args) {
         if (D == 128) { CS_LAUNCH_DECODE(128, ItemsInArgs, plan.arg_items) } else { CS_LAUNCH_DECODE(64, ItemsInArgs, plan.arg_items) }
@@ -410,6 +401,13 @@ int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, cons
 #undef CS_LAUNCH_DECODE
 #undef CS_LAUNCH_MERGE
     return check_launch("decode kernels");
+}
+
+int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
+                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16)
+{
+    return f16 ? launch_decode_as<F16>(pool, layer, b, plan, q, out, Hq, scale, workspace, st)
+               : launch_decode_as<Bf16>(pool, layer, b, plan, q, out, Hq, scale, workspace, st);
 }
 
 }  // namespace cs

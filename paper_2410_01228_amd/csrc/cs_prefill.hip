@@ -1,7 +1,7 @@
 // Prefill-chunk path of the mixed-batch paged attention: q_s > 1 new tokens of a sequence
 // attend its prior context and, causally, their own chunk (paper Sec. 4.2: the attention
-// term grows as P(P+C); chunked prefill).  Compute-bound, so the tiles run on the bf16
-// matrix cores with an fp32 online softmax.
+// term grows as P(P+C); chunked prefill).  Compute-bound, so the tiles run on the 16-bit
+// (bf16 or f16) matrix cores with an fp32 online softmax.
 //
 // A workgroup (4 wavefronts) owns one kv head and kTileCols "column tiles" of 16 query rows
 // each (16 consecutive chunk tokens of one of the G query heads sharing the kv head; tiles
@@ -11,11 +11,11 @@
 // ring of slots several steps ahead (one barrier per step, no staging registers); every
 // wavefront reads them back as MFMA operands -- a page's 16-byte units are operand
 // fragments, and the copy places them so that the LDS reads are linear in the lane id -- and
-//   S^T[key][query]   = K . Q^T                      v_mfma_f32_16x16x32_bf16
-//   O^T[d][query]    += V^T[d][32 keys] . P^T        v_mfma_f32_16x16x32_bf16
+//   S^T[key][query]   = K . Q^T                      v_mfma_f32_16x16x32_{bf16,f16}
+//   O^T[d][query]    += V^T[d][32 keys] . P^T        v_mfma_f32_16x16x32_{bf16,f16}
 // with P^T taken straight from the S^T accumulators of the two pages (their C layout is
 // the B layout of the second product).  The softmax denominators come from one more MFMA
-// per tile with an all-ones A operand, so they sum exactly the bf16 weights that multiply V.
+// per tile with an all-ones A operand, so they sum exactly the rounded weights that multiply V.
 //
 // The loop is software-pipelined: iteration i exponentiates the scores of step i and
 // multiplies them with V(i) while the matrix cores already compute the scores of step
@@ -23,6 +23,7 @@
 // maximum is only raised (and the accumulators rescaled) when a new score exceeds it by
 // more than 2^kLazyLog2, which keeps the rescale out of the steady-state loop.
 #include "cs_common.h"
+#include "cs_elem.h"
 #include <algorithm>
 #include <type_traits>
 
@@ -31,7 +32,6 @@ namespace cs {
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kPrefillWaves = 4;
 constexpr int kPrefillThreads = kPrefillWaves * 64;
@@ -88,12 +88,6 @@ __device__ __forceinline__ float max8(const float (&x)[8]) {
     return max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[7]));
 }
 
-__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    bf16x2 v = { (__bf16)lo, (__bf16)hi };
-    return __builtin_bit_cast(uint32_t, v);
-}
-
 constexpr int kTileCols = kPrefillWaves * kNCT;   // column tiles per workgroup
 
 // Workgroup slots.  A sequence with q new tokens has ceil(q/16) * G column tiles, numbered
@@ -105,7 +99,7 @@ __host__ __device__ inline int64_t prefill_slot_start(int32_t cu_q, int32_t s, i
     return ((int64_t)cu_q + 16ll * s) * G / (16 * kTileCols) + s;
 }
 
-template <int D>
+template <int D, class E>
 __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G, int32_t S,
@@ -157,7 +151,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
     // ---- this wavefront's column tiles: ct = wave*4 + c -> (token block, head) ----
-    bf16x8 qb[kNCT][D / 32];
+    u32x4 qb[kNCT][D / 32];
     int32_t pos_q[kNCT];                               // absolute position of this lane's query
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
 #pragma unroll
@@ -172,7 +166,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
             u32x4 v = zero4;
             if (valid)
                 v = *(const u32x4*)(q + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + kk * 32 + (lane >> 4) * 8);
-            qb[c][kk] = __builtin_bit_cast(bf16x8, v);
+            qb[c][kk] = v;
         }
     }
 
@@ -187,8 +181,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) o[c][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
     }
-    const u32x4 ones4 = {0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u};
-    const bf16x8 ones = __builtin_bit_cast(bf16x8, ones4);
+    const u32x4 ones = {E::kOnes, E::kOnes, E::kOnes, E::kOnes};
 
     // ---- global -> LDS copies (LDS-DMA: each lane hands its 16 bytes straight to LDS at
     // base + lane*16, no staging registers).  Per step and wavefront kLoads instructions for K
@@ -272,12 +265,12 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
-            const bf16x8 ka0 = __builtin_bit_cast(bf16x8, kA[(kk * 2 + 0) * 64 + lane]);   // tile X
-            const bf16x8 ka1 = __builtin_bit_cast(bf16x8, kA[(kk * 2 + 1) * 64 + lane]);   // tile Y
+            const u32x4 ka0 = kA[(kk * 2 + 0) * 64 + lane];   // tile X
+            const u32x4 ka1 = kA[(kk * 2 + 1) * 64 + lane];   // tile Y
 #pragma unroll
             for (int c = 0; c < kNCT; ++c) {
-                s0[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka0, qb[c][kk], s0[c], 0, 0, 0);
-                s1[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka1, qb[c][kk], s1[c], 0, 0, 0);
+                s0[c] = E::mfma32(ka0, qb[c][kk], s0[c]);
+                s1[c] = E::mfma32(ka1, qb[c][kk], s1[c]);
             }
         }
         const int32_t key0 = step * kKeysPerStep + (lane >> 5) * 16 + ((lane >> 4) & 1) * 8;
@@ -348,19 +341,18 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         pg_next = step_pages(i + kRing);               // consumed by the next iteration
 
         if (!kLast) scores(masked, i + 1, xn);
-        bf16x8 pb[kNCT];
+        u32x4 pb[kNCT];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
             float p[8];
 #pragma unroll
             for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(xc[c][j], scale_log2e, -m_run[c]));
-            const u32x4 pk = { pack2_bf16(p[0], p[1]), pack2_bf16(p[2], p[3]), pack2_bf16(p[4], p[5]), pack2_bf16(p[6], p[7]) };
-            pb[c] = __builtin_bit_cast(bf16x8, pk);
+            pb[c] = u32x4{ E::pack(p[0], p[1]), E::pack(p[2], p[3]), E::pack(p[4], p[5]), E::pack(p[6], p[7]) };
         }
         const u32x4* vA = &lds_v[(uint32_t)i % kRing][0];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
-            lacc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[c], lacc[c], 0, 0, 0);
+            lacc[c] = E::mfma32(ones, pb[c], lacc[c]);
         // V slots at or past the end of the sequence hold stale bits (or nothing at all): zero
         // them so that a zero weight times the slot stays zero.  The lane's unit holds the 8
         // tokens 32*i + 16*(hi/2) + 8*(hi%2) + 0..7, two per dword.
@@ -375,10 +367,9 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         for (int dt = 0; dt < D / 16; ++dt) {
             u32x4 av = vA[dt * 64 + lane];
             if (kMask) { av[0] &= vm[0]; av[1] &= vm[1]; av[2] &= vm[2]; av[3] &= vm[3]; }
-            const bf16x8 va = __builtin_bit_cast(bf16x8, av);
 #pragma unroll
             for (int c = 0; c < kNCT; ++c)
-                o[c][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(va, pb[c], o[c][dt], 0, 0, 0);
+                o[c][dt] = E::mfma32(av, pb[c], o[c][dt]);
         }
         if (!kMask && !kLast) {
             // steady state: tell the scheduler the order we want.  K operands leave LDS first;
@@ -435,8 +426,8 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
                 uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + (lane >> 4) * 4;
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
-                    u32x2 w = { pack2_bf16(o[c][dt][0] * inv, o[c][dt][1] * inv),
-                                pack2_bf16(o[c][dt][2] * inv, o[c][dt][3] * inv) };
+                    u32x2 w = { E::pack(o[c][dt][0] * inv, o[c][dt][1] * inv),
+                                E::pack(o[c][dt][2] * inv, o[c][dt][3] * inv) };
                     *(u32x2*)(dst + dt * 16) = w;
                 }
             }
@@ -456,7 +447,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
 
 // Merge of the key-range partials of the tiles that were cut: grid = (Hkv, slots), 256
 // lanes, two lanes per query row (half of the features each).
-template <int D>
+template <int D, class E>
 __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     int32_t Hkv, int32_t G, int32_t S, const int32_t* __restrict__ ctx_lens,
     const int32_t* __restrict__ cu_q_lens, uint16_t* __restrict__ out,
@@ -510,7 +501,7 @@ __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + half * (D / 2);
 #pragma unroll
     for (int d = 0; d < D / 2; d += 4) {
-        u32x2 w = { pack2_bf16(acc[d] * inv, acc[d + 1] * inv), pack2_bf16(acc[d + 2] * inv, acc[d + 3] * inv) };
+        u32x2 w = { E::pack(acc[d] * inv, acc[d + 1] * inv), E::pack(acc[d + 2] * inv, acc[d + 3] * inv) };
         *(u32x2*)(dst + d) = w;
     }
 }
@@ -563,8 +554,9 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     return p;
 }
 
-int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
-                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
+template <class E>
+static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
+                             const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
@@ -575,27 +567,34 @@ int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, con
     dim3 grid((uint32_t)Hkv, slots, (uint32_t)plan.max_ranges);
     float* part = (float*)workspace;
     if (D == 128)
-        hipLaunchKernelGGL(prefill_kernel<128>, grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
+        hipLaunchKernelGGL((prefill_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
                            b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
                            plan.range_steps, plan.base_slot, part);
     else
-        hipLaunchKernelGGL(prefill_kernel<64>, grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
+        hipLaunchKernelGGL((prefill_kernel<64, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
                            b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
                            plan.range_steps, plan.base_slot, part);
     if (plan.max_ranges > 1) {
         dim3 mgrid((uint32_t)Hkv, (uint32_t)plan.num_slots);
         if (D == 128)
-            hipLaunchKernelGGL(prefill_merge_kernel<128>, mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
+            hipLaunchKernelGGL((prefill_merge_kernel<128, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
                                b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
                                plan.base_slot, part);
         else
-            hipLaunchKernelGGL(prefill_merge_kernel<64>, mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
+            hipLaunchKernelGGL((prefill_merge_kernel<64, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
                                b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
                                plan.base_slot, part);
     }
     return check_launch("prefill kernels");
+}
+
+int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
+                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16)
+{
+    return f16 ? launch_prefill_as<F16>(pool, layer, b, plan, q, out, Hq, scale, workspace, st)
+               : launch_prefill_as<Bf16>(pool, layer, b, plan, q, out, Hq, scale, workspace, st);
 }
 
 }  // namespace cs

@@ -77,6 +77,11 @@ def randn_bf16(shape, gen: torch.Generator, device="cpu") -> torch.Tensor:
     return torch.randn(shape, generator=gen, device=device, dtype=torch.float32).to(torch.bfloat16)
 
 
+def randn_f16(shape, gen: torch.Generator, device="cpu") -> torch.Tensor:
+    """N(0,1) in fp32, rounded to nearest-even IEEE half (for the fp16 variant of the path)."""
+    return torch.randn(shape, generator=gen, device=device, dtype=torch.float32).to(torch.float16)
+
+
 def uniform_int(lo: int, hi: int, n: int, gen) -> torch.Tensor:
     """Integers uniform in [lo, hi], both ends inclusive."""
     return torch.randint(lo, hi + 1, (n,), generator=gen, dtype=torch.int64).to(torch.int32)

@@ -15,24 +15,27 @@ def bits(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().cpu().view(torch.int16).numpy().view(np.uint16)
 
 
-def from_bits(a: np.ndarray, device="cpu") -> torch.Tensor:
-    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+def from_bits(a: np.ndarray, device="cpu", dtype=torch.bfloat16) -> torch.Tensor:
+    return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(dtype).to(device)
 
 
 class Step:
     """Logical data of one step of a synth.Batch: prior context K/V per sequence, this
     step's new K/V and queries (all bf16 bit patterns / float32 views)."""
 
-    def __init__(self, batch: synth.Batch, seed_index: int, q_gain: float = 1.0, layer: int = 0):
+    def __init__(self, batch: synth.Batch, seed_index: int, q_gain: float = 1.0, layer: int = 0,
+                 dtype=torch.bfloat16):
         self.b = batch
+        self.dtype = dtype
         sh = batch.shape
         g = synth.generator(seed_index)
         C = int(batch.ctx_lens.sum())
-        self.k_prior = synth.randn_bf16((C, sh.Hkv, sh.D), g)
-        self.v_prior = synth.randn_bf16((C, sh.Hkv, sh.D), g)
-        self.k_new = synth.randn_bf16((batch.T, sh.Hkv, sh.D), g)
-        self.v_new = synth.randn_bf16((batch.T, sh.Hkv, sh.D), g)
-        self.q = (synth.randn_bf16((batch.T, sh.Hq, sh.D), g).float() * q_gain).to(torch.bfloat16)
+        draw = synth.randn_bf16 if dtype == torch.bfloat16 else synth.randn_f16
+        self.k_prior = draw((C, sh.Hkv, sh.D), g)
+        self.v_prior = draw((C, sh.Hkv, sh.D), g)
+        self.k_new = draw((batch.T, sh.Hkv, sh.D), g)
+        self.v_new = draw((batch.T, sh.Hkv, sh.D), g)
+        self.q = (draw((batch.T, sh.Hq, sh.D), g).float() * q_gain).to(dtype)
         self.layer = layer
         self.cu_ctx = torch.zeros(batch.S + 1, dtype=torch.int32)
         self.cu_ctx[1:] = torch.cumsum(batch.ctx_lens, 0)

@@ -10,12 +10,13 @@ from helpers import Step, assert_attention_close, bits, from_bits
 pytestmark = pytest.mark.gpu
 
 
-def run_step(batch, seed, q_gain=1.0, split=0, check_append=True):
+def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16):
     """append + attention through the C ABI; returns (gpu_out, Step, device pool, cs.Batch)."""
-    st = Step(batch, seed, q_gain=q_gain)
+    st = Step(batch, seed, q_gain=q_gain, dtype=dtype)
     sh = batch.shape
     cpu_pool = st.prior_pool()
-    pool = cs.Pool(from_bits(cpu_pool, "cuda"), cpu_pool.shape[0], cpu_pool.shape[1], sh.Hkv, sh.D)
+    pool = cs.Pool(from_bits(cpu_pool, "cuda", dtype), cpu_pool.shape[0], cpu_pool.shape[1], sh.Hkv, sh.D)
+    attend = cs.cs_paged_attention_mixed if dtype == torch.bfloat16 else cs.cs_paged_attention_mixed_f16
     bb = cs.Batch(batch.block_tables, batch.ctx_lens, batch.cu_q_lens)
     cs.cs_kv_append(pool, 0, bb, st.k_new.cuda(), st.v_new.cuda())
     if check_append:
@@ -24,8 +25,8 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True):
     cs.cs_set_decode_split_tokens(split)
     try:
         ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
-        out = torch.full((batch.T, sh.Hq, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
-        cs.cs_paged_attention_mixed(pool, 0, bb, st.q.cuda(), out, sh.Hq, sh.scale, ws)
+        out = torch.full((batch.T, sh.Hq, sh.D), float("nan"), dtype=dtype, device="cuda")
+        attend(pool, 0, bb, st.q.cuda(), out, sh.Hq, sh.scale, ws)
         torch.cuda.synchronize()
     finally:
         cs.cs_set_decode_split_tokens(0)
@@ -198,6 +199,47 @@ def test_online_prefill_with_offline_decodes():
     assert_attention_close(out_on[:T_on], st.oracle_attention(list(range(n_on)))[:T_on], "online prefix alone")
     assert (out[:T_on].float() - out_on[:T_on].float()).abs().max().item() <= 2e-2
     assert torch.isnan(out_on[T_on:].float()).all()                 # offline rows are not touched
+
+
+# ------------------------------------------------------------------------------------
+# fp16 variant (the paper's serving precision, Sec. 6.1): same kernels on the f16 matrix
+# instructions; append and the copies are shared (they move 16-bit words)
+# ------------------------------------------------------------------------------------
+
+def assert_close_f16(out, ref, what):
+    """fp16 keeps 3 more mantissa bits than bf16: besides the common bar, the error must be
+    well inside it (a bf16 rounding slipped into the f16 path would not be)."""
+    assert_attention_close(out, ref, what)
+    g = out.detach().float().cpu().numpy().astype(np.float64)
+    rows = ~np.isnan(ref).any(axis=(1, 2))
+    rel = np.linalg.norm(g[rows] - ref[rows]) / np.linalg.norm(ref[rows])
+    assert rel <= 2e-3, "%s: relative Frobenius error %.2e, expected fp16-level accuracy" % (what, rel)
+
+
+@pytest.mark.parametrize("split", [0, 64])
+def test_f16_decode(split):
+    sh = synth.Shape(28, 4, 128)
+    b = decode_batch(sh, [0, 15, 16, 700, 33, 1024, 257, 2047], 51)
+    out, st, _, _ = run_step(b, 51, split=split, dtype=torch.float16)
+    assert_close_f16(out, st.oracle_attention(), "f16 decode split=%d" % split)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,gain", [(32, 8, 128, 1.0), (4, 2, 64, 1.0), (8, 2, 128, 6.0)])
+def test_f16_prefill_and_mixed(Hq, Hkv, D, gain):
+    sh = synth.Shape(Hq, Hkv, D)
+    b = synth.make_batch(sh, [300, 64, 0, 48, 17, 1500, 5], [1, 1, 32, 50, 77, 40, 2], synth.generator(52))
+    out, st, _, _ = run_step(b, 52, q_gain=gain, dtype=torch.float16)
+    assert_close_f16(out, st.oracle_attention(), "f16 mixed %d/%d/%d" % (Hq, Hkv, D))
+
+
+def test_f16_key_range_split_and_shrunk_config():
+    sh = synth.Shape(8, 2, 128)
+    b = synth.make_batch(sh, [3000, 1501, 0, 4100], [40, 17, 33, 1], synth.generator(61))
+    out, st, _, _ = run_step(b, 61, dtype=torch.float16)
+    assert_close_f16(out, st.oracle_attention(), "f16 prefill key ranges")
+    b = synth.config_qwen7b_mixed(shrink=8)
+    out, st, _, _ = run_step(b, 2, dtype=torch.float16)
+    assert_close_f16(out, st.oracle_attention(), "f16 qwen7b/8")
 
 
 def test_page_permutation_leaves_output_bit_identical():
