@@ -271,6 +271,55 @@ def checkpoint_pipeline(info, layers=8, reps=5):
     return r
 
 
+def graph_replay(b, layers=32, iters=20):
+    """A launch-bound batch: `layers` layers of append + attention issued call by call, and the
+    same calls recorded once into a HIP graph and replayed."""
+    import torch
+    from paper_2410_01228_amd import binding as cs
+    from paper_2410_01228_amd import synth
+    sh = b.shape
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(78)
+    pool = cs.Pool.empty(layers, b.num_pages, sh.Hkv, sh.D)
+    fill_randn_bf16(pool.tensor.view(-1), gen)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+    q = synth.randn_bf16((layers, b.T, sh.Hq, sh.D), gen, "cuda")
+    kn = synth.randn_bf16((layers, b.T, sh.Hkv, sh.D), gen, "cuda")
+    vn = synth.randn_bf16((layers, b.T, sh.Hkv, sh.D), gen, "cuda")
+    out = torch.empty_like(q)
+
+    def run():
+        for l in range(layers):
+            cs.cs_kv_append(pool, l, bb, kn[l], vn[l])
+            cs.cs_paged_attention_mixed(pool, l, bb, q[l], out[l], sh.Hq, sh.scale, ws)
+
+    def timed(fn):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(iters):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / iters * 1e6
+
+    eager_us = timed(run)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    graph_us = timed(graph.replay)
+    log("  %d layers of append + attention: %.0f us call by call, %.0f us as one HIP graph replay"
+        % (layers, eager_us, graph_us))
+    return {"layers": layers, "eager_us": round(eager_us, 1), "graph_us": round(graph_us, 1)}
+
+
 def preemption_loop(b, layers=32, iters=10):
     """Layer-wise preemption driver (cs_run_layers) over `layers` layers of this batch: cost
     of the safepoints (every 4 layers) with and without waiting for the stream, and the time
@@ -516,6 +565,9 @@ def main():
     if args.detail and args.workload == "qwen7b_mixed":
         del info["keep"][:]
         result["preemption_loop"] = preemption_loop(b)
+    if args.detail and args.workload == "tiny":
+        del info["keep"][:]
+        result["graph_replay"] = graph_replay(b)
     if args.detail and args.workload == "qwen14b_ckpt":
         result["ckpt_pipeline"] = checkpoint_pipeline(info)
     if not args.no_cpu_baseline:
