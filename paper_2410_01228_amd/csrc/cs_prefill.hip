@@ -257,20 +257,26 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     // Raw scores of one step (before the softmax scale).  With hi = lane/16: xs[c][0..3] are
     // rows 4*hi + i of tile X, xs[c][4..7] of tile Y, i.e. together the 8 consecutive keys
     // 32*step + 16*(hi/2) + 8*(hi%2) + 0..7.  Masked entries become -inf.
+    // K operands of the step whose scores are computed next.  They are fetched from LDS one
+    // phase ahead (while the P.V products of the previous step run), so that the score
+    // products never wait for an LDS round trip.
+    u32x4 kreg[2 * (D / 32)];
+    auto load_k = [&](int32_t step) {
+        const u32x4* kA = &lds_k[(uint32_t)step % kRing][0];
+#pragma unroll
+        for (int u = 0; u < 2 * (D / 32); ++u) kreg[u] = kA[u * 64 + lane];   // (kk*2 + tile)
+    };
     auto scores = [&](auto masked, int32_t step, float (&xs)[kNCT][8]) {
         constexpr bool kMask = decltype(masked)::value;
-        const u32x4* kA = &lds_k[(uint32_t)step % kRing][0];
         f32x4 s0[kNCT], s1[kNCT];
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
-            const u32x4 ka0 = kA[(kk * 2 + 0) * 64 + lane];   // tile X
-            const u32x4 ka1 = kA[(kk * 2 + 1) * 64 + lane];   // tile Y
 #pragma unroll
             for (int c = 0; c < kNCT; ++c) {
-                s0[c] = E::mfma32(ka0, qb[c][kk], s0[c]);
-                s1[c] = E::mfma32(ka1, qb[c][kk], s1[c]);
+                s0[c] = E::mfma32(kreg[kk * 2 + 0], qb[c][kk], s0[c]);   // tile X
+                s1[c] = E::mfma32(kreg[kk * 2 + 1], qb[c][kk], s1[c]);   // tile Y
             }
         }
         const int32_t key0 = step * kKeysPerStep + (lane >> 5) * 16 + ((lane >> 4) & 1) * 8;
@@ -319,24 +325,29 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     };
 
     // ---- prologue: the first kRing-1 steps of the range in flight, the first two landed,
-    // scores of the first step ----
+    // scores of the first step, K operands of the second ----
 #pragma unroll
     for (int j = 0; j < kRing - 1; ++j) dma_step(step_begin + j, step_pages(step_begin + j));
     StepPages pg_next = step_pages(step_begin + kRing - 1);       // pages of the step issued next
     wait_vmcnt<(kRing - 3) * kStepLoads>();
     __syncthreads();
+    load_k(step_begin);
     scores(std::true_type{}, step_begin, x);
     raise_max(x);
+    load_k(step_begin + 1);
 
-    // ---- iteration i: scores of step i+1 (into xn) and weights of step i (from xc) side by
-    // side, then O += V(i) P(i) while the new scores are tested against the running maxima.
+    // ---- iteration i.  First half: scores of step i+1 (into xn, from the K operands already in
+    // registers) side by side with the weights of step i (from xc); the V operands of step i
+    // leave LDS meanwhile.  Then the barrier: every wavefront is done reading V(i) and K(i+1),
+    // and K(i+2), V(i+1) have landed.  Second half: O += V(i) P(i) while the K operands of step
+    // i+2 are fetched and the new scores are tested against the running maxima.
     // kMask: causal / end-of-sequence masking (needed from the first edge step on);
     // kLast: there is no step i+1. ----
     auto iteration = [&](auto masked, auto last, int32_t i, float (&xc)[kNCT][8], float (&xn)[kNCT][8]) {
         constexpr bool kMask = decltype(masked)::value;
         constexpr bool kLast = decltype(last)::value;
         // step i+kRing-1 goes into the slot step i-1 left (its last reader finished before the
-        // barrier that ended iteration i-1)
+        // barrier inside iteration i-1)
         dma_step(i + kRing - 1, pg_next);
         pg_next = step_pages(i + kRing);               // consumed by the next iteration
 
@@ -350,9 +361,6 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
             pb[c] = u32x4{ E::pack(p[0], p[1]), E::pack(p[2], p[3]), E::pack(p[4], p[5]), E::pack(p[6], p[7]) };
         }
         const u32x4* vA = &lds_v[(uint32_t)i % kRing][0];
-#pragma unroll
-        for (int c = 0; c < kNCT; ++c)
-            lacc[c] = E::mfma32(ones, pb[c], lacc[c]);
         // V slots at or past the end of the sequence hold stale bits (or nothing at all): zero
         // them so that a zero weight times the slot stays zero.  The lane's unit holds the 8
         // tokens 32*i + 16*(hi/2) + 8*(hi%2) + 0..7, two per dword.
@@ -363,39 +371,54 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
             for (int j = 0; j < 4; ++j)
                 vm[j] = valid >= 2 * j + 2 ? 0xffffffffu : (valid == 2 * j + 1 ? 0x0000ffffu : 0u);
         }
+        u32x4 av[D / 16];
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
-            u32x4 av = vA[dt * 64 + lane];
-            if (kMask) { av[0] &= vm[0]; av[1] &= vm[1]; av[2] &= vm[2]; av[3] &= vm[3]; }
-#pragma unroll
-            for (int c = 0; c < kNCT; ++c)
-                o[c][dt] = E::mfma32(av, pb[c], o[c][dt]);
+            av[dt] = vA[dt * 64 + lane];
+            if (kMask) { av[dt][0] &= vm[0]; av[dt][1] &= vm[1]; av[dt][2] &= vm[2]; av[dt][3] &= vm[3]; }
         }
         if (!kMask && !kLast) {
-            // steady state: tell the scheduler the order we want.  K operands leave LDS first;
-            // the exp / convert work of step i starts while they are in flight and continues
-            // under the score MFMAs of step i+1; the V operands are fetched under those MFMAs
-            // too; the threshold test of the new scores runs under the P.V MFMAs.
-            constexpr int kQK = 2 * kNCT * (D / 32), kPV = kNCT + kNCT * (D / 16);
-            __builtin_amdgcn_sched_group_barrier(0x100, 2 * (D / 32), 0);        // K: ds_read_b128
-            __builtin_amdgcn_sched_group_barrier(0x002, 6 * kNCT, 0);            // VALU
+            // steady state, first half: tell the scheduler the order we want.  The exp / convert
+            // work of step i runs under the score MFMAs of step i+1, and the V operands are
+            // fetched under them too.
+            constexpr int kQK = 2 * kNCT * (D / 32);
+            __builtin_amdgcn_sched_group_barrier(0x002, 4 * kNCT, 0);            // VALU
 #pragma unroll
             for (int r = 0; r < kQK; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               // 1 MFMA
                 __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);               // 2 VALU
                 if (r < D / 16) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // V: one ds_read_b128
             }
+        }
+        // K(i+2) and V(i+1) must have landed before anyone reads them: all but the copies of
+        // the last kRing-3 steps issued
+        __builtin_amdgcn_sched_barrier(0);             // nothing may move across the two halves
+        wait_vmcnt<(kRing - 3) * kStepLoads>();
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+
+        if (!kLast) load_k(i + 2);
+#pragma unroll
+        for (int c = 0; c < kNCT; ++c)
+            lacc[c] = E::mfma32(ones, pb[c], lacc[c]);
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+#pragma unroll
+            for (int c = 0; c < kNCT; ++c)
+                o[c][dt] = E::mfma32(av[dt], pb[c], o[c][dt]);
+        }
+        if (!kMask && !kLast) {
+            // second half: the threshold test of the new scores and the K fetches run under the
+            // P.V MFMAs
+            constexpr int kPV = kNCT + kNCT * (D / 16);
 #pragma unroll
             for (int r = 0; r < kPV; ++r) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);
+                if (r >= 2 && r < 2 + 2 * (D / 32)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // K: one ds_read_b128
             }
         }
         if (!kLast) raise_max(xn);
-        // K(i+2) and V(i+1) must have landed before the next iteration reads them: all but the
-        // copies of the last kRing-3 steps issued
-        wait_vmcnt<(kRing - 3) * kStepLoads>();
-        __syncthreads();
     };
     float xb[kNCT][8];
     int32_t i = step_begin;
