@@ -214,6 +214,16 @@ int cs_run_layers(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end
  * byte counters. */
 int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Host-only view of the decode path's launch plan, for tests: the work items of `batch` in
+ * launch order, one word each -- sequence (bits 0-15), piece (16-23), pieces of that sequence
+ * (24-31) -- as they would travel in the kernel arguments; sequence s with n keys in k pieces
+ * has pieces of ceil(n/k) keys rounded up to a page.  Writes min(items, capacity) words and
+ * returns the number of items; returns -1000000 - items when the list is too long for the
+ * kernel arguments (then a planning kernel builds it on the device, in sequence order).
+ * *split_tokens (optional) receives the target keys per item.  No device work. */
+int32_t cs_debug_decode_items(const cs_batch* batch, int32_t num_kv_heads, int32_t head_dim,
+                              uint32_t* items, int32_t capacity, int32_t* split_tokens);
+
 /* Tuning knob for measurements: force the decode path's tokens per split (multiple of 16,
  * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */
 void cs_set_decode_split_tokens(int32_t tokens);

@@ -99,6 +99,8 @@ def lib():
                                     ctypes.POINTER(ctypes.c_int32), vp]
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
+        L.cs_debug_decode_items.restype = ctypes.c_int32
+        L.cs_debug_decode_items.argtypes = [BP, i32, i32, ctypes.POINTER(ctypes.c_uint32), i32, ctypes.POINTER(ctypes.c_int32)]
         L.cs_status_string.restype, L.cs_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
         L.cs_last_hip_error.restype, L.cs_last_hip_error.argtypes = ctypes.c_char_p, []
         _lib = L
@@ -109,7 +111,7 @@ EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
     "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
-    "cs_kv_ckpt_load", "cs_run_layers", "cs_debug_copy",
+    "cs_kv_ckpt_load", "cs_run_layers", "cs_debug_copy", "cs_debug_decode_items",
     "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
 ]
 
@@ -278,6 +280,19 @@ def cs_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
     nbytes = src.numel() * src.element_size()
     assert dst.numel() * dst.element_size() >= nbytes
     _check(lib().cs_debug_copy(_ptr(dst), _ptr(src), nbytes, _stream(stream)), "cs_debug_copy")
+
+
+def cs_debug_decode_items(batch: "Batch", Hkv: int, D: int, capacity: int = 1024):
+    """(items as (seq, piece, pieces) tuples or None when the list does not fit the kernel
+    arguments, number of items, target keys per item) -- host only."""
+    buf = (ctypes.c_uint32 * capacity)()
+    split = ctypes.c_int32(0)
+    n = lib().cs_debug_decode_items(ctypes.byref(batch.c), Hkv, D, buf, capacity, ctypes.byref(split))
+    if n <= -1000000:
+        return None, -1000000 - n, split.value
+    if n < 0:
+        raise CsError(n, "cs_debug_decode_items")
+    return [(w & 0xffff, (w >> 16) & 0xff, w >> 24) for w in buf[:min(n, capacity)]], n, split.value
 
 
 def cs_set_decode_split_tokens(tokens: int):

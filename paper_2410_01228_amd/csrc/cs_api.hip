@@ -343,6 +343,17 @@ int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {
     return launch_plain_copy(dst, src, bytes, (hipStream_t)stream);
 }
 
+int32_t cs_debug_decode_items(const cs_batch* batch, int32_t Hkv, int32_t D, uint32_t* items, int32_t capacity,
+                              int32_t* split_tokens) {
+    if (!shape_supported(Hkv, D) || validate_batch(nullptr, batch) != CS_OK || capacity < 0 || (capacity > 0 && !items))
+        return CS_ERR_INVALID_ARG;
+    const DecodePlan p = plan_decode(batch, Hkv, D);
+    if (split_tokens) *split_tokens = p.split_tokens;
+    if (!p.in_args) return -1000000 - p.total_items;       // the planning kernel would build the list
+    for (int32_t i = 0; i < p.total_items && i < capacity; ++i) items[i] = p.arg_items.e[i];
+    return p.total_items;
+}
+
 void cs_set_decode_split_tokens(int32_t tokens) {
     if (tokens < 0) tokens = 0;
     g_forced_split.store((tokens + 15) / 16 * 16);

@@ -126,6 +126,62 @@ def test_attention_shape_and_workspace_checks():
     assert more >= need > none_cut == 0
 
 
+def _plan(ctx, ql, Hkv, D, max_blocks=1 << 16):
+    """Host-only launch plan of the decode path as (seq, piece, pieces) tuples."""
+    lib = cs.lib()
+    b, keep = _batch(ctx, ql, max_blocks=max_blocks)
+    buf = (ctypes.c_uint32 * 1024)()
+    split = ctypes.c_int32(0)
+    n = lib.cs_debug_decode_items(ctypes.byref(b), Hkv, D, buf, 1024, ctypes.byref(split))
+    items = None if n < 0 else [(w & 0xffff, (w >> 16) & 0xff, w >> 24) for w in buf[:n]]
+    return items, n, split.value
+
+
+def test_decode_plan_lists_every_piece_once_longest_first():
+    import random
+    rnd = random.Random(7)
+    ctx = [rnd.randint(0, 40000) for _ in range(90)]
+    ql = [1] * 90
+    for s in (3, 17, 50):
+        ql[s] = rnd.choice([0, 5, 300])                     # not decode sequences: never listed
+    items, n, split = _plan(ctx, ql, 8, 128)
+    assert items is not None and n == len(items) and split % 16 == 0 and split >= 256
+    decode = [s for s in range(90) if ql[s] == 1]
+    by_seq = {}
+    for pos, (s, piece, k) in enumerate(items):
+        by_seq.setdefault(s, []).append((pos, piece, k))
+    assert sorted(by_seq) == decode
+    length = []
+    for s, lst in by_seq.items():
+        k = lst[0][2]
+        assert [p for _, p, _ in lst] == list(range(k)) and all(kk == k for _, _, kk in lst)     # each piece once
+        assert [pos for pos, _, _ in lst] == list(range(lst[0][0], lst[0][0] + k))              # adjacent
+        nkeys = ctx[s] + 1
+        assert k == max(1, (nkeys + split // 2) // split)                                       # round(n / split)
+        piece_keys = nkeys if k == 1 else (-(-nkeys // k) + 15) // 16 * 16
+        assert k * piece_keys >= nkeys                                                          # the pieces cover the keys
+        length.append((lst[0][0], piece_keys))
+    length.sort()
+    assert all(a[1] >= b[1] for a, b in zip(length, length[1:]))                                # longest first
+
+
+def test_decode_plan_falls_back_to_the_planning_kernel_beyond_the_argument_block():
+    ctx = [100] * 880
+    items, n, _ = _plan(ctx, [1] * 880, 2, 64)
+    assert n == 880 and [s for s, _, _ in items] == list(range(880))       # equal lengths: stable order
+    items, n, _ = _plan(ctx + [100], [1] * 881, 2, 64)
+    assert items is None and n == -1000000 - 881
+    lib = cs.lib()
+    try:
+        lib.cs_set_decode_split_tokens(256)
+        items, n, split = _plan([70000, 10], [1, 1], 2, 64)                # round(70001/256) = 273 pieces: a word holds 255
+        assert items is None and split == 256
+        items, n, split = _plan([60000, 10], [1, 1], 2, 64)
+        assert n == 234 + 1 and items[-1] == (1, 0, 1) and items[0][2] == 234   # round(60001/256) = 234
+    finally:
+        lib.cs_set_decode_split_tokens(0)
+
+
 def test_debug_copy_argument_checks():
     lib = cs.lib()
     assert lib.cs_debug_copy(0x1000, 0x2000, 24, None) == cs.CS_ERR_INVALID_ARG          # not a multiple of 16
