@@ -64,7 +64,10 @@ __device__ __forceinline__ void lds_dma16(const void* src, void* dst_wave_base) 
 // the lanes in mask_a fetch from base_a + off, the others from base_b + off (off = this
 // lane's byte offset inside a page's K or V block).  Scalar bases and a per-lane 32-bit
 // offset keep all address arithmetic out of the vector ALU; EXEC is narrowed to each lane
-// set in turn and restored.  Must be called with all 64 lanes active.
+// set in turn and restored.  Must be called with all 64 lanes active.  s_not_b64 writes SCC,
+// hence the clobber: without it the compiler may keep the carry of a 64-bit address addition
+// alive across this block (s_add_u32 before it, s_addc_u32 after it), and the address that
+// comes out is 4 GiB off.
 __device__ __forceinline__ void lds_dma16_two_pages(const void* base_a, const void* base_b, uint32_t off,
                                                     uint64_t mask_a, void* dst_wave_base) {
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_base;
@@ -74,7 +77,7 @@ __device__ __forceinline__ void lds_dma16_two_pages(const void* base_a, const vo
                  "s_not_b64 exec, exec\n\t"
                  "global_load_lds_dwordx4 %1, %3\n\t"
                  "s_mov_b64 exec, -1"
-                 :: "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0");
+                 :: "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0", "scc");
 }
 
 // max(a, b, c) in one instruction.  fmaxf() makes the compiler canonicalise every operand
