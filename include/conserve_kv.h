@@ -209,6 +209,13 @@ int cs_run_layers(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end
                   int32_t num_q_heads, float softmax_scale, void* workspace, size_t workspace_bytes,
                   const cs_safepoint* safepoint, int32_t* preempted_before_layer, void* stream);
 
+/* The same loop for fp16 data (see cs_paged_attention_mixed_f16). */
+int cs_run_layers_f16(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end, const cs_batch* batch,
+                      const void* q, const void* k_new, const void* v_new, void* out,
+                      int64_t q_layer_stride, int64_t kv_layer_stride,
+                      int32_t num_q_heads, float softmax_scale, void* workspace, size_t workspace_bytes,
+                      const cs_safepoint* safepoint, int32_t* preempted_before_layer, void* stream);
+
 /* Plain device-to-device copy kernel of `bytes` (multiple of 16, both pointers 16-byte
  * aligned): the measured copy ceiling of the device and the calibration point for hardware
  * byte counters. */

@@ -93,8 +93,9 @@ def lib():
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
         for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp, vp]
+        L.cs_run_layers_f16.restype = ctypes.c_int
         L.cs_run_layers.restype = ctypes.c_int
-        L.cs_run_layers.argtypes = [PP, i32, i32, BP, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, i32,
+        L.cs_run_layers_f16.argtypes = L.cs_run_layers.argtypes = [PP, i32, i32, BP, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, i32,
                                     ctypes.c_float, vp, sz, ctypes.POINTER(cs_safepoint),
                                     ctypes.POINTER(ctypes.c_int32), vp]
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
@@ -111,7 +112,7 @@ EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
     "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
-    "cs_kv_ckpt_load", "cs_run_layers", "cs_debug_copy", "cs_debug_decode_items",
+    "cs_kv_ckpt_load", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items",
     "cs_set_decode_split_tokens", "cs_status_string", "cs_last_hip_error",
 ]
 
@@ -263,12 +264,14 @@ def cs_kv_ckpt_load(pool: Pool, layer_begin: int, layer_end: int, page_ids: torc
 
 def cs_run_layers(pool: Pool, layer_begin: int, layer_end: int, batch: Batch, q: torch.Tensor,
                   k_new: torch.Tensor, v_new: torch.Tensor, out: torch.Tensor, Hq: int, softmax_scale: float,
-                  workspace: Optional[torch.Tensor], safepoint: Optional[cs_safepoint] = None, stream=None) -> int:
+                  workspace: Optional[torch.Tensor], safepoint: Optional[cs_safepoint] = None, stream=None,
+                  f16: bool = False) -> int:
     """q, out: [layers, T, Hq, D]; k_new, v_new: [layers, T, Hkv, D].  Returns the first layer
-    that ran online-only, or -1."""
+    that ran online-only, or -1.  f16: the data is fp16 (cs_run_layers_f16)."""
     wb = 0 if workspace is None else workspace.numel() * workspace.element_size()
     first = ctypes.c_int32(-1)
-    _check(lib().cs_run_layers(ctypes.byref(pool.c), layer_begin, layer_end, ctypes.byref(batch.c), _ptr(q),
+    fn = lib().cs_run_layers_f16 if f16 else lib().cs_run_layers
+    _check(fn(ctypes.byref(pool.c), layer_begin, layer_end, ctypes.byref(batch.c), _ptr(q),
                                _ptr(k_new), _ptr(v_new), _ptr(out), q.stride(0), k_new.stride(0), Hq,
                                softmax_scale, _ptr(workspace), wb,
                                ctypes.byref(safepoint) if safepoint is not None else None,

@@ -291,11 +291,11 @@ int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_
     return launch_page_copy(*pool, l0, l1, ids, n, staging, false, (hipStream_t)stream);
 }
 
-int cs_run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch* batch,
-                  const void* q, const void* k_new, const void* v_new, void* out,
-                  int64_t q_stride, int64_t kv_stride, int32_t Hq, float scale,
-                  void* workspace, size_t workspace_bytes, const cs_safepoint* sp,
-                  int32_t* preempted_before_layer, void* stream) {
+static int run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch* batch,
+                      const void* q, const void* k_new, const void* v_new, void* out,
+                      int64_t q_stride, int64_t kv_stride, int32_t Hq, float scale,
+                      void* workspace, size_t workspace_bytes, const cs_safepoint* sp,
+                      int32_t* preempted_before_layer, void* stream, bool f16) {
     if (preempted_before_layer) *preempted_before_layer = -1;
     int rc = validate_pool(pool);
     if (rc) return rc;
@@ -330,10 +330,28 @@ int cs_run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch
         uint16_t* ol = (uint16_t*)out + i * q_stride;
         rc = cs_kv_append(pool, l, &cur, kl, vl, stream);
         if (rc) return rc;
-        rc = cs_paged_attention_mixed(pool, l, &cur, ql, ol, Hq, scale, workspace, workspace_bytes, stream);
+        rc = attention_mixed(pool, l, &cur, ql, ol, Hq, scale, workspace, workspace_bytes, stream, f16);
         if (rc) return rc;
     }
     return CS_OK;
+}
+
+int cs_run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch* batch,
+                  const void* q, const void* k_new, const void* v_new, void* out,
+                  int64_t q_stride, int64_t kv_stride, int32_t Hq, float scale,
+                  void* workspace, size_t workspace_bytes, const cs_safepoint* sp,
+                  int32_t* preempted_before_layer, void* stream) {
+    return run_layers(pool, l0, l1, batch, q, k_new, v_new, out, q_stride, kv_stride, Hq, scale, workspace,
+                      workspace_bytes, sp, preempted_before_layer, stream, false);
+}
+
+int cs_run_layers_f16(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch* batch,
+                      const void* q, const void* k_new, const void* v_new, void* out,
+                      int64_t q_stride, int64_t kv_stride, int32_t Hq, float scale,
+                      void* workspace, size_t workspace_bytes, const cs_safepoint* sp,
+                      int32_t* preempted_before_layer, void* stream) {
+    return run_layers(pool, l0, l1, batch, q, k_new, v_new, out, q_stride, kv_stride, Hq, scale, workspace,
+                      workspace_bytes, sp, preempted_before_layer, stream, true);
 }
 
 int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream) {

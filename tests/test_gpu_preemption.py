@@ -15,12 +15,12 @@ pytestmark = pytest.mark.gpu
 L = 8
 
 
-def setup():
+def setup(dtype=torch.bfloat16):
     b = synth.config_qwen7b_mixed(shrink=16)
     sh = b.shape
-    steps = [Step(b, 20 + l, layer=0) for l in range(L)]            # independent data per layer
+    steps = [Step(b, 20 + l, layer=0, dtype=dtype) for l in range(L)]   # independent data per layer
     pools = np.stack([st.prior_pool()[0] for st in steps])           # [L, P, 2, Hkv, 16D]
-    pool = cs.Pool(from_bits(pools, "cuda"), L, b.num_pages, sh.Hkv, sh.D)
+    pool = cs.Pool(from_bits(pools, "cuda", dtype), L, b.num_pages, sh.Hkv, sh.D)
     bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
     q = torch.stack([st.q for st in steps]).cuda()
     k = torch.stack([st.k_new for st in steps]).cuda()
@@ -31,13 +31,14 @@ def setup():
 
 def run(pool, bb, q, k, v, ws, sh, sp):
     out = torch.full_like(q, float("nan"))
-    first = cs.cs_run_layers(pool, 0, L, bb, q, k, v, out, sh.Hq, sh.scale, ws, sp)
+    first = cs.cs_run_layers(pool, 0, L, bb, q, k, v, out, sh.Hq, sh.scale, ws, sp, f16=q.dtype == torch.float16)
     torch.cuda.synchronize()
     return out, first
 
 
-def test_no_preemption_runs_every_layer_on_the_full_batch():
-    b, sh, steps, pool, bb, q, k, v, ws = setup()
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+def test_no_preemption_runs_every_layer_on_the_full_batch(dtype):
+    b, sh, steps, pool, bb, q, k, v, ws = setup(dtype)
     flag = ctypes.c_int32(0)
     sp = cs.cs_safepoint(ctypes.addressof(flag), cs.POLL_FN(0), None, 4, b.extra["n_online"], 0)
     out, first = run(pool, bb, q, k, v, ws, sh, sp)
