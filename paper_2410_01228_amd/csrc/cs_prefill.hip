@@ -49,17 +49,12 @@ __device__ __forceinline__ void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 15) | (7 << 4) | (15 << 8) | ((N >> 4) << 14));
 }
 
-// One LDS-DMA load: every lane's 16 bytes at `src` go to LDS at `dst_wave_base` + lane*16
-// (dst_wave_base is wave-uniform and travels in M0).  Written as inline assembly so that the
-// compiler's wait-count pass does not see it: it cannot tell which ring slot a later LDS
-// read touches and would drain the whole copy queue (vmcnt(0)) before every read.  The waits
-// are placed by hand with wait_vmcnt<>() instead.
-__device__ __forceinline__ void lds_dma16(const void* src, void* dst_wave_base) {
-    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_base;
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :: "s"(lds_addr), "v"(src) : "memory", "m0");
-}
-
+// LDS-DMA (global_load_lds_dwordx4): every active lane's 16 bytes go from global memory
+// straight to LDS at base + lane*16, where the wave-uniform base travels in M0.  Written as
+// inline assembly so that the compiler's wait-count pass does not see the loads: it cannot
+// tell which ring slot a later LDS read touches and would drain the whole copy queue
+// (vmcnt(0)) before every read.  The waits are placed by hand with wait_vmcnt<>() instead.
+//
 // Two LDS-DMA loads for one run of 64 LDS units whose lanes read from two different pages:
 // the lanes in mask_a fetch from base_a + off, the others from base_b + off (off = this
 // lane's byte offset inside a page's K or V block).  Scalar bases and a per-lane 32-bit
