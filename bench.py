@@ -51,7 +51,7 @@ class Leg:
 
     def __init__(self, name, fn, bound, work, unit_count=None):
         self.name, self.fn, self.bound, self.work = name, fn, bound, work
-        self.us = None
+        self.us = self.us_median = self.us_min = None
 
     def roofline(self, traffic=None):
         peak = HBM_PEAK if self.bound == "hbm" else MFMA_BF16_PEAK
@@ -163,7 +163,10 @@ def time_legs(legs, steps, warmup):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     for i, leg in enumerate(legs):
-        leg.us = sum(ev[k][i].elapsed_time(ev[k][i + 1]) for k in range(steps)) / steps * 1e3
+        per_call = sorted(ev[k][i].elapsed_time(ev[k][i + 1]) * 1e3 for k in range(steps))
+        leg.us = sum(per_call) / steps
+        leg.us_median = per_call[steps // 2]
+        leg.us_min = per_call[0]
     return wall / steps
 
 
@@ -211,6 +214,36 @@ def cpu_baseline(b, min_seconds=10.0, max_seconds=30.0):
     return {"value": round(tokens / secs, 1), "unit": "tokens/s", "cores": threads, "kind": "oracle",
             "sample": "%d of %d sequences (%d tokens a sweep) of the same workload, fp64 logical attention, "
                       "%d sweeps, %.1f s" % (len(pick), len(order), sum(d[4] for d in data), sweeps, secs)}
+
+
+def cpu_copy_baseline(b, layers=2, max_pages=256, min_seconds=3.0):
+    """The oracle's checkpoint gather and restore (plain bit copies over its own pool format) on a
+    bounded sample of the workload's dirty pages, in GB/s read+write."""
+    import numpy as np
+    from oracle import kv_layout
+    sh = b.shape
+    ids = np.asarray(b.extra["dirty_pages"][:max_pages], dtype=np.int64)
+    uniq = {int(p): i for i, p in enumerate(sorted(set(int(p) for p in ids)))}
+    pool = np.random.default_rng(5).integers(0, 2 ** 16, size=(layers, len(uniq), 2, sh.Hkv, 16 * sh.D), dtype=np.uint16)
+    local = [uniq[int(p)] for p in ids]
+    nbytes = 2 * layers * len(local) * kv_layout.page_elems(sh.Hkv, sh.D) * 2
+    out = {}
+    for name, fn in (("gather", lambda st: kv_layout.ref_gather(pool, 0, layers, local)),
+                     ("restore", lambda st: kv_layout.ref_restore(pool, 0, layers, sorted(set(local)), st))):
+        st = kv_layout.ref_gather(pool, 0, layers, sorted(set(local))) if name == "restore" else None
+        if name == "restore":
+            nb = 2 * layers * len(set(local)) * kv_layout.page_elems(sh.Hkv, sh.D) * 2
+        else:
+            nb = nbytes
+        secs, reps = 0.0, 0
+        while secs < min_seconds and reps < 1000:
+            t0 = time.perf_counter()
+            fn(st)
+            secs += time.perf_counter() - t0
+            reps += 1
+        out[name] = round(nb * reps / secs / 1e9, 2)
+    return {"gather_GBps": out["gather"], "restore_GBps": out["restore"], "cores": 1, "kind": "oracle",
+            "sample": "%d of %d dirty pages x %d of %d layers, read+write bytes" % (len(local), len(b.extra["dirty_pages"]), layers, sh.L)}
 
 
 def checkpoint_pipeline(info, layers=8, reps=5):
@@ -554,7 +587,8 @@ def main():
                    "page_size": 16, "layers_per_step": 1,
                    "step": "+".join(l.name for l in legs)},
         "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=KERNEL_OF.get((args.workload, dom.name), dom.name)),
-        "legs": {l.name: {"us": round(l.us, 2), "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
+        "legs": {l.name: {"us": round(l.us, 2), "us_median": round(l.us_median, 2), "us_min": round(l.us_min, 2),
+                          "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }
     if args.append_sweep:
         del info["keep"][:]
@@ -572,6 +606,8 @@ def main():
         result["ckpt_pipeline"] = checkpoint_pipeline(info)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(b)
+        if args.workload == "qwen14b_ckpt":
+            result["cpu_baseline_copies"] = cpu_copy_baseline(b)
     print(json.dumps(result), flush=True)
 
 
