@@ -292,7 +292,20 @@ def checkpoint_pipeline(info, layers=8, reps=5):
     l0, l1 = timed(side, lambda: cs.cs_kv_ckpt_load(pool, 0, layers, fresh, stage, host, stream=side), reps)
     torch.cuda.synchronize()
     load_alone = l0.elapsed_time(l1) / reps * 1e3
+    # the paper's own example (Sec. 4.4): one whole 2048-token chunk = 128 pages of every layer
+    L_all = staging.shape[0]
+    chunk_pages = min(128, n)
+    chunk_ids = dirty[:chunk_pages].contiguous()
+    chunk_stage = staging.view(-1)[:L_all * chunk_pages * staging.shape[2]].view(L_all, chunk_pages, staging.shape[2])
+    chunk_host = torch.empty((L_all, chunk_pages, staging.shape[2]), dtype=torch.bfloat16).pin_memory()
+    cs.cs_kv_ckpt_save(pool, 0, L_all, chunk_ids, chunk_stage, chunk_host, stream=side)
+    c0, c1 = timed(side, lambda: cs.cs_kv_ckpt_save(pool, 0, L_all, chunk_ids, chunk_stage, chunk_host, stream=side), reps)
+    torch.cuda.synchronize()
+    chunk_ms = c0.elapsed_time(c1) / reps
+    chunk_bytes = chunk_host.numel() * 2
     r = {"layers": layers, "pages": n, "bytes": nbytes,
+         "chunk_2048_tokens": {"layers": L_all, "pages": chunk_pages, "bytes": chunk_bytes, "save_ms": round(chunk_ms, 2),
+                               "GBps": round(chunk_bytes / chunk_ms / 1e6, 1)},
          "save_us": round(save_alone, 1), "save_GBps": round(nbytes / save_alone / 1e3, 1),
          "load_us": round(load_alone, 1), "load_GBps": round(nbytes / load_alone / 1e3, 1),
          "save_us_during_attention": round(save_busy, 1), "save_GBps_during_attention": round(nbytes / save_busy / 1e3, 1),
@@ -301,6 +314,8 @@ def checkpoint_pipeline(info, layers=8, reps=5):
         "with attention running: save %.1f GB/s, attention %.1f -> %.1f us"
         % (layers, n, nbytes / 1e9, save_alone, r["save_GBps"], load_alone, r["load_GBps"],
            r["save_GBps_during_attention"], attn_alone, attn_busy))
+    log("  one 2048-token chunk of all %d layers (%d pages, %.0f MB): saved to the host in %.2f ms"
+        % (L_all, chunk_pages, chunk_bytes / 1e6, chunk_ms))
     return r
 
 
