@@ -242,6 +242,36 @@ def test_f16_key_range_split_and_shrunk_config():
     assert_close_f16(out, st.oracle_attention(), "f16 qwen7b/8")
 
 
+@pytest.mark.parametrize("seed", list(range(48)))
+def test_random_mixed_batches(seed):
+    """Seeded random shapes and batches: any group size up to 16, either head_dim, decode
+    tokens, chunks and idle sequences in any order, contexts on and off page boundaries, with
+    the automatic and with a forced decode split."""
+    import random
+    rnd = random.Random(1000 + seed)
+    D = rnd.choice([64, 128])
+    Hkv = rnd.choice([1, 2, 3, 4, 8])
+    G = rnd.choice([1, 2, 4, 5, 7, 8, 16])
+    sh = synth.Shape(Hkv * G, Hkv, D)
+    S = rnd.randint(1, 10)
+    ctx, ql = [], []
+    for _ in range(S):
+        kind = rnd.choice(["decode", "decode", "chunk", "chunk", "idle"])
+        c = rnd.choice([0, 1, 15, 16, 17, 31, 32, rnd.randint(0, 700), rnd.randint(0, 2500)])
+        ctx.append(c)
+        ql.append(1 if kind == "decode" else 0 if kind == "idle" else rnd.choice([2, 16, 17, rnd.randint(2, 150)]))
+    if sum(ql) == 0:
+        ql[0] = 1
+    b = synth.make_batch(sh, ctx, ql, synth.generator(2000 + seed), spare=rnd.randint(0, 5))
+    split = rnd.choice([0, 0, 64, 256])
+    gain = rnd.choice([1.0, 1.0, 4.0])
+    dtype = rnd.choice([torch.bfloat16, torch.bfloat16, torch.float16])
+    out, st, _, _ = run_step(b, 2000 + seed, q_gain=gain, split=split, dtype=dtype)
+    active = [s for s in range(S) if ql[s] > 0]
+    assert_attention_close(out, st.oracle_attention(active),
+                           "random seed %d: %d/%d/%d ctx %s q %s split %d gain %g %s" % (seed, sh.Hq, Hkv, D, ctx, ql, split, gain, dtype))
+
+
 def test_page_permutation_leaves_output_bit_identical():
     sh = synth.Shape(8, 2, 128)
     ctx, ql = [100, 700, 31, 0, 260], [1, 1, 1, 48, 33]
