@@ -38,10 +38,13 @@ def logical_from_pool(pool_t, layer, bt_row, n, Hkv, D):
 
 
 def run_full(index, sample_seqs, rows_per_chunk=6):
-    b = synth.CONFIGS[index]()
+    return run_batch(synth.CONFIGS[index](), synth.BASE_SEED + index, sample_seqs, rows_per_chunk)
+
+
+def run_batch(b, seed, sample_seqs, rows_per_chunk=6):
     sh = b.shape
     gen = torch.Generator(device="cuda")
-    gen.manual_seed(synth.BASE_SEED + index)
+    gen.manual_seed(seed)
     L_alloc = 1                                     # attention uses one layer of the pool
     pool = cs.Pool.empty(L_alloc, b.num_pages, sh.Hkv, sh.D)
     fill(pool.tensor, gen)
@@ -107,6 +110,19 @@ def test_llama70b_long_full_size():
     b = synth.config_llama70b_long()
     order = np.argsort(b.ctx_lens[:128].numpy())
     run_full(3, [int(order[0]), int(order[-1]), 77, 128], rows_per_chunk=4)
+
+
+def test_very_long_contexts():
+    """Contexts far beyond the workloads': a decode over 150 001 keys (cut into more pieces than
+    an item word can say, so the planning kernel lists them), one over 70 002, and a chunk of
+    48 tokens on 90 000 (few tiles on a very long context: key ranges and their merge)."""
+    sh = synth.Shape(4, 2, 64)
+    b = synth.make_batch(sh, [150000, 70001, 90000], [1, 1, 48], synth.generator(90))
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    items, n_items, split = cs.cs_debug_decode_items(bb, sh.Hkv, sh.D)
+    assert items is None and n_items > 255                      # listed on the device
+    assert cs.cs_paged_attention_workspace_bytes(bb, sh.Hq, sh.Hkv, sh.D) > 0
+    run_batch(b, 90, [0, 1, 2], rows_per_chunk=5)
 
 
 def test_qwen14b_ckpt_full_size():
