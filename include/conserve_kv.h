@@ -74,7 +74,7 @@ typedef struct {
  * P; 1 for a decode token, >1 for a prefill chunk, 0 for an idle sequence).  New token i of
  * sequence s has absolute position ctx_lens[s] + i. */
 typedef struct {
-    int32_t        num_seqs;            /* S */
+    int32_t        num_seqs;            /* S, at most 65535 */
     int32_t        num_tokens;          /* T = cu_q_lens[S] */
     const int32_t* block_tables;        /* device [S][max_blocks_per_seq] page ids; entries
                                            past ceil((ctx+q)/16) are never read          */

@@ -114,8 +114,9 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     __shared__ u32x4 lds_k[kRing][kStepUnits];
     __shared__ u32x4 lds_v[kRing][kStepUnits];
 
-    const int32_t g = blockIdx.x;
-    const int32_t b = blockIdx.y;
+    // grid.x = slots * Hkv, kv head fastest; grid.y = key ranges
+    const int32_t b = blockIdx.x / Hkv;
+    const int32_t g = blockIdx.x - b * Hkv;
     // sequence owning slot b: the largest s with start(s) <= b
     int32_t lo = 0, hi = S;
     while (hi - lo > 1) {
@@ -137,9 +138,9 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
     const int32_t first_edge = (C + tb_min * 16 + 1) / kKeysPerStep;   // steps before it need no causal mask
     // key range of this workgroup: a tile whose keys need more than range_steps steps is cut
-    // into ranges handled by gridDim.z workgroups, each leaving a partial (max, sum, output)
+    // into ranges handled by gridDim.y workgroups, each leaving a partial (max, sum, output)
     const int32_t n_ranges = (n_steps + range_steps - 1) / range_steps;
-    const int32_t step_begin = blockIdx.z * range_steps;
+    const int32_t step_begin = blockIdx.y * range_steps;
     if (step_begin >= n_steps) return;
     const int32_t step_end = min(n_steps, step_begin + range_steps);
     const int32_t n_pages = min((n_seq_keys + kPage - 1) >> 4, max_blocks);
@@ -455,7 +456,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
         }
     } else {
         // partial of this key range: unnormalised output, running max and sum per query row
-        float* wg = part + (((int64_t)(b - base_slot) * Hkv + g) * gridDim.z + blockIdx.z) * (kTileCols * 16 * kPartRow);
+        float* wg = part + (((int64_t)(b - base_slot) * Hkv + g) * gridDim.y + blockIdx.y) * (kTileCols * 16 * kPartRow);
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
             float* row = wg + ((wave * kNCT + c) * 16 + (lane & 15)) * kPartRow;
@@ -466,7 +467,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     }
 }
 
-// Merge of the key-range partials of the tiles that were cut: grid = (Hkv, slots), 256
+// Merge of the key-range partials of the tiles that were cut: grid = Hkv * slots, 256
 // lanes, two lanes per query row (half of the features each).
 template <int D, class E>
 __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
@@ -475,7 +476,7 @@ __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     int32_t range_steps, int32_t max_ranges, int32_t base_slot, const float* __restrict__ part)
 {
     constexpr int kPartRow = D + 4;
-    const int32_t g = blockIdx.x, b = blockIdx.y + base_slot;
+    const int32_t g = blockIdx.x % Hkv, b = blockIdx.x / Hkv + base_slot;
     int32_t lo = 0, hi = S;
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
@@ -583,9 +584,9 @@ static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_bat
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     const float scale_log2e = scale * 1.4426950408889634f;
     const int64_t slots64 = prefill_slot_start(b.num_tokens, b.num_seqs, G);
-    if (slots64 > 65535) return CS_ERR_UNSUPPORTED;
+    if (slots64 * Hkv > 2147483647ll || plan.max_ranges > 65535) return CS_ERR_UNSUPPORTED;
     const uint32_t slots = (uint32_t)slots64;
-    dim3 grid((uint32_t)Hkv, slots, (uint32_t)plan.max_ranges);
+    dim3 grid((uint32_t)Hkv * slots, (uint32_t)plan.max_ranges);
     float* part = (float*)workspace;
     if (D == 128)
         hipLaunchKernelGGL((prefill_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
@@ -598,7 +599,7 @@ static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_bat
                            b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
                            plan.range_steps, plan.base_slot, part);
     if (plan.max_ranges > 1) {
-        dim3 mgrid((uint32_t)Hkv, (uint32_t)plan.num_slots);
+        dim3 mgrid((uint32_t)Hkv * (uint32_t)plan.num_slots);
         if (D == 128)
             hipLaunchKernelGGL((prefill_merge_kernel<128, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
                                b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,

@@ -272,6 +272,21 @@ def test_random_mixed_batches(seed):
                            "random seed %d: %d/%d/%d ctx %s q %s split %d gain %g %s" % (seed, sh.Hq, Hkv, D, ctx, ql, split, gain, dtype))
 
 
+def test_prefill_many_short_chunks():
+    """More workgroup slots than one grid dimension holds (60 000 sequences: two-token chunks and
+    decode tokens interleaved): the slot index rides in grid.x together with the kv head."""
+    sh = synth.Shape(2, 1, 64)
+    S = 60000
+    ql = [2 if s % 3 else 1 for s in range(S)]
+    ctx = [s % 5 for s in range(S)]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(36))
+    out, st, _, _ = run_step(b, 36, check_append=False)
+    sample = list(range(0, S, 997)) + [S - 1, S - 2]
+    ref = st.oracle_attention(sample)
+    assert_attention_close(out, ref, "60000 sequences")
+    assert torch.isfinite(out.float()).all()
+
+
 def test_page_permutation_leaves_output_bit_identical():
     sh = synth.Shape(8, 2, 128)
     ctx, ql = [100, 700, 31, 0, 260], [1, 1, 1, 48, 33]
