@@ -543,6 +543,9 @@ def main():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="element type of the pool and the queries (f16: the fp16 attention entry point)")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
+    ap.add_argument("--separate-launches", action="store_true",
+                    help="run the prefill tiles and the decode work items of a mixed batch as two kernels in a row "
+                         "instead of one fused grid")
     ap.add_argument("--append-sweep", action="store_true", help="also time cs_kv_append over growing token counts")
     ap.add_argument("--fit-latency-model", action="store_true",
                     help="also run the (P, C) timing grid and fit the paper's latency model to this path")
@@ -560,6 +563,7 @@ def main():
     cs.lib()                                   # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
     cs.cs_set_decode_split_tokens(args.split_tokens)
+    cs.cs_set_mixed_fusion(not args.separate_launches)
     if args.calibration_copy_gib > 0:
         n = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
         src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)

@@ -235,6 +235,11 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t num_kv_heads, int32
  * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */
 void cs_set_decode_split_tokens(int32_t tokens);
 
+/* Tuning knob for measurements and tests: 1 (default) lets a call that holds both prefill
+ * chunks and decode tokens run them as one fused launch when its plan allows; 0 always
+ * launches the prefill kernel and the decode kernel one after the other.  Process-wide. */
+void cs_set_mixed_fusion(int32_t on);
+
 const char* cs_status_string(int status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */
 const char* cs_last_hip_error(void);

@@ -10,6 +10,7 @@ namespace cs {
 
 static thread_local char g_hip_error[256] = "";
 static std::atomic<int32_t> g_forced_split{0};
+static std::atomic<int32_t> g_fuse_mixed{1};
 
 int hip_failed(hipError_t e, const char* what) {
     snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
@@ -195,6 +196,12 @@ static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
+    if (plan.num_prefill > 0 && plan.num_decode > 0 && plan.in_args && pplan.max_ranges == 1 && g_fuse_mixed.load()) {
+        // both kinds of work in one grid
+        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, st, f16);
+        if (rc) return rc;
+        return launch_decode(*pool, layer, *batch, plan, q, out, Hq, softmax_scale, workspace, st, f16, true);
+    }
     if (plan.num_prefill > 0) {
         rc = launch_prefill(*pool, layer, *batch, pplan, q, out, Hq, softmax_scale, (char*)workspace + decode_bytes, st, f16);
         if (rc) return rc;
@@ -370,6 +377,10 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t Hkv, int32_t D, uin
     if (!p.in_args) return -1000000 - p.total_items;       // the planning kernel would build the list
     for (int32_t i = 0; i < p.total_items && i < capacity; ++i) items[i] = p.arg_items.e[i];
     return p.total_items;
+}
+
+void cs_set_mixed_fusion(int32_t on) {
+    g_fuse_mixed.store(on ? 1 : 0);
 }
 
 void cs_set_decode_split_tokens(int32_t tokens) {

@@ -72,8 +72,11 @@ int launch_token_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer
                       const int32_t* token_slots, int32_t n, void* staging, bool to_staging, hipStream_t st);
 int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);
 // f16: the pool, q and out hold IEEE half instead of bf16.
+// merge_only: the items' work has been done already (by the fused kernel below); only the
+// partials of the cut sequences remain to be merged.  Valid when plan.in_args.
 int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& plan,
-                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16);
+                  const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16,
+                  bool merge_only = false);
 // Key-range split of the prefill path (pure function of the host lengths).
 struct PrefillPlan {
     int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
@@ -85,5 +88,13 @@ struct PrefillPlan {
 PrefillPlan plan_prefill(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
 int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
                    const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16);
+// One launch for a batch that holds both chunks and decode tokens: the prefill workgroups
+// first, the decode items (longest first) behind them, so that decode work fills the slots the
+// uneven prefill tiles leave empty instead of waiting for the last of them.  Needs the item
+// list in the kernel arguments (dplan.in_args) and uncut prefill tiles (pplan.max_ranges == 1);
+// the caller merges the cut decode sequences afterwards (launch_decode with merge_only).
+int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
+                 const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
+                 void* decode_workspace_base, hipStream_t st, bool f16);
 
 }  // namespace cs

@@ -1,0 +1,81 @@
+// Fused kernel for a mixed batch (paper Sec. 4.2: online decode tokens and offline prefill
+// chunks share an iteration).  The prefill workgroups and the decode work items are one grid:
+// the prefill tiles, bound by the matrix cores and of uneven length, come first; the decode
+// items, bound by HBM and sorted longest first, follow and move into every slot a finished or
+// missing prefill tile leaves free -- two kernels in a row would leave those slots idle until
+// the longest tile is done.  Both kinds of workgroup have 4 wavefronts and share one LDS
+// allocation (a union of the two layouts), so two of them fit a CU in any combination.
+#include "cs_prefill_impl.h"
+#include "cs_decode_impl.h"
+
+namespace cs {
+
+static_assert(kPrefillThreads == kDecodeThreads, "one block size for both kinds of workgroup");
+
+template <int D>
+union MixedLds {
+    PrefillLds<D> prefill;
+    DecodeLds<D> decode;
+};
+
+template <int D, class E>
+__global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
+    const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t G, int32_t S,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
+    int32_t range_steps, uint32_t num_prefill_wgs, const ItemsInArgs items,
+    float* __restrict__ part_o, float* __restrict__ part_ml)
+{
+    __shared__ MixedLds<D> lds;
+    if (blockIdx.x < num_prefill_wgs) {
+        const int32_t b = blockIdx.x / Hkv;
+        const int32_t g = blockIdx.x - b * Hkv;
+        prefill_tile<D, E>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
+                           ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, 0, nullptr, g, b, 0, 1);
+    } else {
+        const uint32_t w = blockIdx.x - num_prefill_wgs;
+        const int32_t item = w / Hkv, g = w - item * Hkv;
+        decode_item<D, ItemsInArgs, E>(lds.decode, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks,
+                                       items, ctx_lens, cu_q_lens, q, out, scale_log2e, part_o, part_ml, item, g);
+    }
+}
+
+template <class E>
+static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
+                           const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
+                           void* decode_ws, hipStream_t st)
+{
+    const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
+    const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
+    const float scale_log2e = scale * 1.4426950408889634f;
+    const int64_t slots = prefill_slot_start(b.num_tokens, b.num_seqs, G);
+    const int64_t n_prefill = slots * Hkv, n_decode = (int64_t)dplan.total_items * Hkv;
+    if (n_prefill + n_decode > 2147483647ll) return CS_ERR_UNSUPPORTED;
+    const DecodeWorkspace w = decode_workspace(dplan, b.num_seqs, Hq, D);
+    float* part_ml = (float*)((char*)decode_ws + w.part_ml);
+    float* part_o = (float*)((char*)decode_ws + w.part_o);
+    dim3 grid((uint32_t)(n_prefill + n_decode));
+    if (D == 128)
+        hipLaunchKernelGGL((mixed_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
+                           pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
+                           b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,
+                           (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
+    else
+        hipLaunchKernelGGL((mixed_kernel<64, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
+                           pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
+                           b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,
+                           (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
+    return check_launch("mixed kernel");
+}
+
+int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
+                 const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
+                 void* decode_ws, hipStream_t st, bool f16)
+{
+    return f16 ? launch_mixed_as<F16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, st)
+               : launch_mixed_as<Bf16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, st);
+}
+
+}  // namespace cs

@@ -3,8 +3,8 @@
 The LDS-DMA helper of the prefill kernel narrows EXEC with s_not_b64, which also writes SCC.
 If the asm statement did not declare that, the compiler could keep the carry of a 64-bit
 address addition alive across the block (s_add_u32 before it, s_addc_u32 after it); the
-address then comes out 4 GiB off and the copy faults.  This test compiles the kernel to
-assembly and looks for any SCC reader that follows an inline-asm block without an SCC
+address then comes out 4 GiB off and the copy faults.  This test compiles every file whose kernels
+contain the helper to assembly and looks for any SCC reader that follows an inline-asm block without an SCC
 writer in between.  (The toolchain cross-compiles; no GPU is needed.)"""
 import os
 import re
@@ -14,7 +14,9 @@ import subprocess
 import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-SRC = os.path.join(ROOT, "paper_2410_01228_amd", "csrc", "cs_prefill.hip")
+CSRC = os.path.join(ROOT, "paper_2410_01228_amd", "csrc")
+ASM_HOME = os.path.join(CSRC, "cs_prefill_impl.h")            # where the inline assembly is written
+USERS = ["cs_prefill.hip", "cs_mixed.hip"]                     # the files whose kernels contain it
 
 SCC_READER = re.compile(r"^(s_cbranch_scc[01]|s_addc_u32|s_subb_u32|s_cselect_b(32|64)|s_cmov_b(32|64))\b")
 # scalar instructions that leave SCC alone; every other s_* instruction is taken to write it
@@ -73,15 +75,17 @@ def test_scanner_sees_a_planted_hazard():
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
-def test_no_scc_value_lives_across_the_dma_asm(tmp_path):
+@pytest.mark.parametrize("src", USERS)
+def test_no_scc_value_lives_across_the_dma_asm(tmp_path, src):
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    out = tmp_path / "cs_prefill.s"
+    out = tmp_path / (src + ".s")
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-I" + os.path.join(ROOT, "include"),
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", str(out), SRC]
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-S", "--cuda-device-only", "-o", str(out),
+           os.path.join(CSRC, src)]
     subprocess.run(cmd, check=True, stdout=subprocess.DEVNULL, stderr=subprocess.DEVNULL)
     text = out.read_text()
     assert text.count("global_load_lds_dwordx4") > 50, "the DMA blocks are gone from the kernel?"
     hazards = scc_reads_after_asm(text)
     assert hazards == [], "SCC read after an inline-asm block that rewrote it: %r" % hazards[:5]
     # and the statement says so itself
-    assert '"scc"' in open(SRC).read()
+    assert '"scc"' in open(ASM_HOME).read()

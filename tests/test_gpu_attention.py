@@ -10,7 +10,7 @@ from helpers import Step, assert_attention_close, bits, from_bits
 pytestmark = pytest.mark.gpu
 
 
-def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16):
+def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16, fuse=True):
     """append + attention through the C ABI; returns (gpu_out, Step, device pool, cs.Batch)."""
     st = Step(batch, seed, q_gain=q_gain, dtype=dtype)
     sh = batch.shape
@@ -23,6 +23,7 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bf
         torch.cuda.synchronize()
         np.testing.assert_array_equal(bits(pool.tensor), st.oracle_append(cpu_pool))
     cs.cs_set_decode_split_tokens(split)
+    cs.cs_set_mixed_fusion(fuse)
     try:
         ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
         out = torch.full((batch.T, sh.Hq, sh.D), float("nan"), dtype=dtype, device="cuda")
@@ -30,6 +31,7 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bf
         torch.cuda.synchronize()
     finally:
         cs.cs_set_decode_split_tokens(0)
+        cs.cs_set_mixed_fusion(True)
     return out, st, pool, bb
 
 
@@ -270,6 +272,24 @@ def test_random_mixed_batches(seed):
     active = [s for s in range(S) if ql[s] > 0]
     assert_attention_close(out, st.oracle_attention(active),
                            "random seed %d: %d/%d/%d ctx %s q %s split %d gain %g %s" % (seed, sh.Hq, Hkv, D, ctx, ql, split, gain, dtype))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,split,dtype", [(8, 2, 128, 0, torch.bfloat16), (28, 4, 128, 64, torch.bfloat16),
+                                                   (16, 1, 64, 32, torch.bfloat16), (8, 2, 128, 64, torch.float16)])
+def test_fused_and_separate_launches_agree(Hq, Hkv, D, split, dtype):
+    """A batch with decode tokens and chunks runs as one fused grid; with the fusion switched off
+    the same work items run as two kernels in a row.  Same arithmetic in the same order: the
+    outputs are bit-identical, and both meet the oracle."""
+    sh = synth.Shape(Hq, Hkv, D)
+    ctx = [700, 33, 0, 1500, 260, 15, 2047, 90, 5, 311]
+    ql = [1, 100, 17, 1, 1, 48, 1, 0, 1, 2]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(77), spare=3)
+    o1, st, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=True)
+    o2, _, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=False)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    active = [s for s in range(len(ql)) if ql[s] > 0]
+    check = assert_attention_close if dtype == torch.bfloat16 else assert_close_f16
+    check(o1, st.oracle_attention(active), "fused %d/%d/%d split %d" % (Hq, Hkv, D, split))
 
 
 def test_prefill_many_short_chunks():
