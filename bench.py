@@ -27,6 +27,10 @@ WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b
 # the kernel behind the call a roofline line is quoted for
 KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16> (the call's only kernel here)",
              ("qwen14b_ckpt", "ckpt_gather"): "cs::page_copy_kernel<true>",
+             ("qwen7b_mixed", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
+             ("llama70b_long", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
+             ("qwen14b_ckpt", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
+             ("tiny", "paged_attention_mixed"): "cs::mixed_kernel<64, cs::Bf16> (prefill tiles and decode work items in one grid)",
              ("qwen7b_mixed", "prefill_only"): "cs::prefill_kernel<128, cs::Bf16>",
              ("llama70b_long", "prefill_only"): "cs::prefill_kernel<128, cs::Bf16>"}
 
@@ -521,14 +525,17 @@ def append_sweep():
     return rows
 
 
-def read_traffic(name):
-    """HBM bytes per launch of the dominant kernel from the committed counter summary, if any."""
+def read_traffic(name, kernel):
+    """HBM bytes per launch of `kernel` (as the profiler prints its name) from the committed
+    counter summary of the workload, if it has a row for it."""
     p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
     if not os.path.exists(p):
         return None
+    in_table = False
     for line in open(p):
-        if line.startswith("traffic_bytes_per_launch:"):
-            return float(line.split(":")[1])
+        in_table = in_table or line.startswith("## HBM traffic")
+        if in_table and line.startswith(kernel + " "):
+            return float(line.split()[-1])
     return None
 
 
@@ -594,6 +601,11 @@ def main():
         dom = detail[1]
     else:
         dom = by_name["paged_attention_mixed"]
+    dom_kernel = KERNEL_OF.get((args.workload, dom.name), dom.name)
+    if args.dtype == "f16":
+        dom_kernel = dom_kernel.replace("cs::Bf16", "cs::F16")
+    if args.separate_launches and "mixed_kernel" in dom_kernel:
+        dom_kernel = dom.name
     result = {
         "metric": "mixed-batch paged-attn tokens/s per layer",
         "value": round(info["T"] / (att_us * 1e-6), 1),
@@ -605,7 +617,7 @@ def main():
         "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
                    "page_size": 16, "layers_per_step": 1,
                    "step": "+".join(l.name for l in legs)},
-        "roofline": dict(dom.roofline(read_traffic(args.workload)), kernel=KERNEL_OF.get((args.workload, dom.name), dom.name)),
+        "roofline": dict(dom.roofline(read_traffic(args.workload, dom_kernel.split(" (")[0])), kernel=dom_kernel),
         "legs": {l.name: {"us": round(l.us, 2), "us_median": round(l.us_median, 2), "us_min": round(l.us_min, 2),
                           "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }
