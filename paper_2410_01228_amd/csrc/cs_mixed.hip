@@ -32,7 +32,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     if (blockIdx.x < num_prefill_wgs) {
         const int32_t b = blockIdx.x / Hkv;
         const int32_t g = blockIdx.x - b * Hkv;
-        prefill_tile<D, E>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
+        prefill_tile<D, E, false>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
                            ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, 0, nullptr, g, b, 0, 1);
     } else {
         const uint32_t w = blockIdx.x - num_prefill_wgs;

@@ -17,7 +17,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     __shared__ PrefillLds<D> lds;
     const int32_t b = blockIdx.x / Hkv;
     const int32_t g = blockIdx.x - b * Hkv;
-    prefill_tile<D, E>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
+    prefill_tile<D, E, true>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
                        q, out, scale_log2e, range_steps, base_slot, part, g, b, blockIdx.y, gridDim.y);
 }
 

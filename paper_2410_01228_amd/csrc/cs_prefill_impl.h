@@ -107,8 +107,10 @@ struct PrefillLds {
 
 // The work of one prefill workgroup: the tile in slot b, kv head g, key range `range` of
 // `n_ranges_grid` (a tile whose keys need more than range_steps steps is cut into ranges, each
-// leaving a partial).  `lds` is the workgroup's own.
-template <int D, class E>
+// leaving a partial).  `lds` is the workgroup's own.  kPhasePriority: the wavefront alternates
+// its issue priority between the halves of an iteration (for a grid of tiles only; beside
+// decode workgroups it gains nothing and the whole call comes out slower).
+template <int D, class E, bool kPhasePriority>
 __device__ __forceinline__ void prefill_tile(
     PrefillLds<D>& lds,
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -357,6 +359,11 @@ __device__ __forceinline__ void prefill_tile(
         constexpr bool kLast = decltype(last)::value;
         // step i+kRing-1 goes into the slot step i-1 left (its last reader finished before the
         // barrier inside iteration i-1)
+        // First half at low, second half at high issue priority.  The two wavefronts that share
+        // a SIMD (one of each resident workgroup) then settle one half apart: the one in its P.V
+        // half gets the matrix pipe whenever it asks, the exp / convert work of the other fills
+        // the issue slots in between (measured: 7-9% on every shape).
+        if (kPhasePriority) __builtin_amdgcn_s_setprio(0);
         dma_step(i + kRing - 1, pg_next);
         pg_next = step_pages(i + kRing);               // consumed by the next iteration
 
@@ -406,6 +413,7 @@ __device__ __forceinline__ void prefill_tile(
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
 
+        if (kPhasePriority) __builtin_amdgcn_s_setprio(1);
         if (!kLast) load_k(i + 2);
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
@@ -444,6 +452,7 @@ __device__ __forceinline__ void prefill_tile(
             for (int j = 0; j < 8; ++j) x[c][j] = xb[c][j];
     }
     iteration(std::true_type{}, std::true_type{}, i, x, xb);
+    if (kPhasePriority) __builtin_amdgcn_s_setprio(0);
     wait_vmcnt<0>();                                   // no copy may outlive the workgroup's LDS
 
     // ---- store: lane holds 4 consecutive features of one query row per tile ----
