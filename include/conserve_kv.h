@@ -235,6 +235,11 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t num_kv_heads, int32
  * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */
 void cs_set_decode_split_tokens(int32_t tokens);
 
+/* Tuning knob for measurements and tests: pages (of 16 keys) a wavefront of the decode kernel
+ * keeps in flight beyond the one it is multiplying: 1 or 2; 0 = automatic (by item length and
+ * grid size).  Process-wide. */
+void cs_set_decode_pages_ahead(int32_t pages);
+
 /* Tuning knob for measurements and tests: 1 (default) lets a call that holds both prefill
  * chunks and decode tokens run them as one fused launch when its plan allows; 0 always
  * launches the prefill kernel and the decode kernel one after the other.  Process-wide. */

@@ -101,6 +101,7 @@ def lib():
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
+        L.cs_set_decode_pages_ahead.restype, L.cs_set_decode_pages_ahead.argtypes = None, [i32]
         L.cs_debug_decode_items.restype = ctypes.c_int32
         L.cs_debug_decode_items.argtypes = [BP, i32, i32, ctypes.POINTER(ctypes.c_uint32), i32, ctypes.POINTER(ctypes.c_int32)]
         L.cs_status_string.restype, L.cs_status_string.argtypes = ctypes.c_char_p, [ctypes.c_int]
@@ -114,7 +115,7 @@ EXPORTS = [
     "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items",
-    "cs_set_decode_split_tokens", "cs_set_mixed_fusion", "cs_status_string", "cs_last_hip_error",
+    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_status_string", "cs_last_hip_error",
 ]
 
 
@@ -297,6 +298,10 @@ def cs_debug_decode_items(batch: "Batch", Hkv: int, D: int, capacity: int = 1024
     if n < 0:
         raise CsError(n, "cs_debug_decode_items")
     return [(w & 0xffff, (w >> 16) & 0xff, w >> 24) for w in buf[:min(n, capacity)]], n, split.value
+
+
+def cs_set_decode_pages_ahead(pages: int):
+    lib().cs_set_decode_pages_ahead(int(pages))
 
 
 def cs_set_mixed_fusion(on: bool):

@@ -11,6 +11,7 @@ namespace cs {
 static thread_local char g_hip_error[256] = "";
 static std::atomic<int32_t> g_forced_split{0};
 static std::atomic<int32_t> g_fuse_mixed{1};
+static std::atomic<int32_t> g_forced_ahead{0};
 
 int hip_failed(hipError_t e, const char* what) {
     snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
@@ -68,6 +69,7 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         }
     }
     p.split_tokens = 256;
+    p.pages_ahead = 1;
     if (p.num_decode == 0) return p;
     int32_t split = g_forced_split.load();
     if (split <= 0) {
@@ -95,6 +97,16 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         p.total_items += k;
         if (k > 1) ++p.num_multi;
         if (k > max_k) max_k = k;
+    }
+    // Two pages ahead per wavefront need the registers of the third workgroup per CU.  Measured
+    // over 33 batch shapes: the deeper queue wins 2-6% once the launch is long enough for the
+    // steady state to dominate (from about 0.65 GB of K/V on, ~100 us), and loses 2-7% on
+    // smaller launches, where start-up and tail decide and every workgroup slot counts.
+    {
+        const int64_t kv_bytes = p.decode_keys * 2 * Hkv * head_dim * 2;
+        p.pages_ahead = kv_bytes >= 650000000ll ? 2 : 1;
+        const int32_t forced = g_forced_ahead.load();
+        if (forced == 1 || forced == 2) p.pages_ahead = forced;
     }
     // A list short enough for the argument block is written here, longest items first: the
     // workgroups of a launch start in index order, so the long ones get going at once and
@@ -377,6 +389,10 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t Hkv, int32_t D, uin
     if (!p.in_args) return -1000000 - p.total_items;       // the planning kernel would build the list
     for (int32_t i = 0; i < p.total_items && i < capacity; ++i) items[i] = p.arg_items.e[i];
     return p.total_items;
+}
+
+void cs_set_decode_pages_ahead(int32_t pages) {
+    g_forced_ahead.store(pages == 1 || pages == 2 ? pages : 0);
 }
 
 void cs_set_mixed_fusion(int32_t on) {

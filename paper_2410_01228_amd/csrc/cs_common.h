@@ -51,6 +51,7 @@ struct DecodePlan {
     int32_t total_items;       // sum over decode sequences of their split count
     int32_t num_multi;         // decode sequences cut into more than one item
     int64_t decode_keys;       // total keys read by decode sequences
+    int32_t pages_ahead;       // pages a wavefront of the decode kernel prefetches (1 or 2)
     bool    in_args;           // the item list below is valid and replaces the planning kernel
     ItemsInArgs arg_items;     // total_items words
     ItemsInArgs arg_multi;     // num_multi words

@@ -161,8 +161,10 @@ struct DecodeLds {
 // The work of one decode workgroup: item `item` (a sequence's key range), kv head g; 4
 // wavefronts.  Src says where the item list is: in memory, in the kernel arguments, or
 // nowhere (item x is sequence x, and the workgroup leaves at once if that sequence is not a
-// decode).
-template <int D, class Src, class E>
+// decode).  kAhead: pages a wavefront keeps in flight beyond the one it multiplies (1 or 2; a
+// page is 32 registers, so 2 costs the third workgroup per CU: it pays for long items on a
+// full grid, not for short ones on a small grid).
+template <int D, class Src, class E, int kAhead>
 __device__ __forceinline__ void decode_item(
     DecodeLds<D>& lds,
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -206,26 +208,53 @@ __device__ __forceinline__ void decode_item(
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) st.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // wave w streams pages page_begin + w, + w + 4, ...; the next page's loads are in
-    // flight while the current page is multiplied
-    PageRegs<D> cur, nxt;
-    int32_t pg = page_begin + wave;
-    int32_t id_cur = pg < page_end ? table[pg] : -1;
-    int32_t id_nxt = pg + kDecodeWaves < page_end ? table[pg + kDecodeWaves] : -1;
-    if (pg < page_end && id_cur >= 0 && id_cur < num_pages)
-        load_page<D>(cur, layer_base, page_stride, id_cur, g, Hkv, lane);
-    while (pg < page_end) {
-        const int32_t pg_n = pg + kDecodeWaves;
-        const bool have_n = pg_n < page_end;
-        const int32_t id_n2 = pg_n + kDecodeWaves < page_end ? table[pg_n + kDecodeWaves] : -1;
-        const bool ok_n = have_n && id_nxt >= 0 && id_nxt < num_pages;
-        if (ok_n) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
-        if (id_cur >= 0 && id_cur < num_pages)
-            process_page<D, E>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
-        cur = nxt;
-        id_cur = id_nxt;
-        id_nxt = id_n2;
-        pg = pg_n;
+    static_assert(kAhead == 1 || kAhead == 2, "one or two pages ahead");
+    if constexpr (kAhead == 1) {
+        // wave w streams pages page_begin + w, + w + 4, ...; the next page's loads are in
+        // flight while the current page is multiplied
+        PageRegs<D> cur, nxt;
+        int32_t pg = page_begin + wave;
+        int32_t id_cur = pg < page_end ? table[pg] : -1;
+        int32_t id_nxt = pg + kDecodeWaves < page_end ? table[pg + kDecodeWaves] : -1;
+        if (pg < page_end && id_cur >= 0 && id_cur < num_pages)
+            load_page<D>(cur, layer_base, page_stride, id_cur, g, Hkv, lane);
+        while (pg < page_end) {
+            const int32_t pg_n = pg + kDecodeWaves;
+            const bool have_n = pg_n < page_end;
+            const int32_t id_n2 = pg_n + kDecodeWaves < page_end ? table[pg_n + kDecodeWaves] : -1;
+            const bool ok_n = have_n && id_nxt >= 0 && id_nxt < num_pages;
+            if (ok_n) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
+            if (id_cur >= 0 && id_cur < num_pages)
+                process_page<D, E>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
+            cur = nxt;
+            id_cur = id_nxt;
+            id_nxt = id_n2;
+            pg = pg_n;
+        }
+    } else {
+        // wave w streams pages page_begin + w, + w + 4, ...; the loads of the next two pages are
+        // in flight while the current page is multiplied
+        PageRegs<D> b0, b1, b2;
+        int32_t pg = page_begin + wave;
+        auto id_at = [&](int32_t p) -> int32_t { return p < page_end ? table[p] : -1; };
+        auto ok = [&](int32_t id) { return id >= 0 && id < num_pages; };
+        int32_t id0 = id_at(pg), id1 = id_at(pg + kDecodeWaves), id2 = id_at(pg + 2 * kDecodeWaves);
+        if (ok(id0)) load_page<D>(b0, layer_base, page_stride, id0, g, Hkv, lane);
+        if (ok(id1)) load_page<D>(b1, layer_base, page_stride, id1, g, Hkv, lane);
+        auto stage = [&](PageRegs<D>& use, PageRegs<D>& fill) {
+            const int32_t id3 = id_at(pg + 3 * kDecodeWaves);
+            if (ok(id2)) load_page<D>(fill, layer_base, page_stride, id2, g, Hkv, lane);
+            if (ok(id0)) process_page<D, E>(st, use, qb, scale_log2e, pg << 4, n_keys, lane);
+            id0 = id1; id1 = id2; id2 = id3;
+            pg += kDecodeWaves;
+        };
+        while (pg < page_end) {
+            stage(b0, b2);
+            if (pg >= page_end) break;
+            stage(b1, b0);
+            if (pg >= page_end) break;
+            stage(b2, b1);
+        }
     }
     st.l += __shfl_xor(st.l, 16, 64);
     st.l += __shfl_xor(st.l, 32, 64);

@@ -4,7 +4,8 @@
 // items, bound by HBM and sorted longest first, follow and move into every slot a finished or
 // missing prefill tile leaves free -- two kernels in a row would leave those slots idle until
 // the longest tile is done.  Both kinds of workgroup have 4 wavefronts and share one LDS
-// allocation (a union of the two layouts), so two of them fit a CU in any combination.
+// allocation (a union of the two layouts), so two of them fit a CU in any combination; the
+// decode items take the deeper page prefetch, whose registers cost nothing here.
 #include "cs_prefill_impl.h"
 #include "cs_decode_impl.h"
 
@@ -37,7 +38,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     } else {
         const uint32_t w = blockIdx.x - num_prefill_wgs;
         const int32_t item = w / Hkv, g = w - item * Hkv;
-        decode_item<D, ItemsInArgs, E>(lds.decode, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks,
+        decode_item<D, ItemsInArgs, E, 2>(lds.decode, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks,
                                        items, ctx_lens, cu_q_lens, q, out, scale_log2e, part_o, part_ml, item, g);
     }
 }

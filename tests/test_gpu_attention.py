@@ -10,7 +10,7 @@ from helpers import Step, assert_attention_close, bits, from_bits
 pytestmark = pytest.mark.gpu
 
 
-def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16, fuse=True):
+def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16, fuse=True, ahead=0):
     """append + attention through the C ABI; returns (gpu_out, Step, device pool, cs.Batch)."""
     st = Step(batch, seed, q_gain=q_gain, dtype=dtype)
     sh = batch.shape
@@ -24,6 +24,7 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bf
         np.testing.assert_array_equal(bits(pool.tensor), st.oracle_append(cpu_pool))
     cs.cs_set_decode_split_tokens(split)
     cs.cs_set_mixed_fusion(fuse)
+    cs.cs_set_decode_pages_ahead(ahead)
     try:
         ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
         out = torch.full((batch.T, sh.Hq, sh.D), float("nan"), dtype=dtype, device="cuda")
@@ -32,6 +33,7 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bf
     finally:
         cs.cs_set_decode_split_tokens(0)
         cs.cs_set_mixed_fusion(True)
+        cs.cs_set_decode_pages_ahead(0)
     return out, st, pool, bb
 
 
@@ -75,6 +77,23 @@ def test_decode_item_list_sources(S, split):
     b = decode_batch(sh, ctxs, 41)
     out, st, _, _ = run_step(b, 41, split=split, check_append=False)
     assert_attention_close(out, st.oracle_attention(), "decode S=%d split=%d" % (S, split))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,split,dtype", [(4, 2, 64, 0, torch.bfloat16), (32, 8, 128, 64, torch.bfloat16),
+                                                   (28, 4, 128, 256, torch.bfloat16), (8, 2, 128, 32, torch.float16)])
+def test_decode_pages_ahead(Hq, Hkv, D, split, dtype):
+    """The decode kernel exists with one and with two pages in flight per wavefront (the host
+    picks by the size of the batch).  A wavefront multiplies its pages in the same order either
+    way, so the outputs are bit-identical; contexts chosen so that wavefronts get 0, 1, 2, 3
+    and many pages, with and without cutting."""
+    sh = synth.Shape(Hq, Hkv, D)
+    ctxs = [0, 15, 16, 31, 47, 63, 64, 100, 127, 128, 191, 200, 255, 300, 1000, 2047, 2500]
+    b = decode_batch(sh, ctxs, 52)
+    o1, st, _, _ = run_step(b, 52, split=split, dtype=dtype, ahead=1)
+    o2, _, _, _ = run_step(b, 52, split=split, dtype=dtype, ahead=2)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    check = assert_attention_close if dtype == torch.bfloat16 else assert_close_f16
+    check(o2, st.oracle_attention(), "two pages ahead %d/%d/%d split %d" % (Hq, Hkv, D, split))
 
 
 def test_decode_llama8b_shrunk():
