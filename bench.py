@@ -25,7 +25,7 @@ MFMA_BF16_PEAK = 2.5e15      # FLOP/s, dense bf16
 
 WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b_ckpt"]
 # the kernel behind the call a roofline line is quoted for
-KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16> (the call's only kernel here)",
+KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16, 2> (the call's only kernel here)",
              ("qwen14b_ckpt", "ckpt_gather"): "cs::page_copy_kernel<true>",
              ("qwen7b_mixed", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
              ("llama70b_long", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
