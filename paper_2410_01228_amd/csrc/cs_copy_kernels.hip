@@ -1,5 +1,6 @@
 // Copy kernels: KV append into pages, checkpoint gather / restore of whole pages, and a
 // plain copy used as the bandwidth ceiling.  All are HBM-bound streams of 16-byte lanes.
+#include <algorithm>
 #include "cs_common.h"
 
 namespace cs {
@@ -174,10 +175,7 @@ int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 // tokens touches at most q/16 + 2 pages), found by bisection.
 // ------------------------------------------------------------------------------------
 constexpr int kAppendThreads = 256;
-
-constexpr int kAppendPagesLog2 = 0;      // log2 of the pages one workgroup fills
-constexpr int kAppendPages = 1 << kAppendPagesLog2;
-constexpr int kAppendSlotShift = 4 + kAppendPagesLog2;
+constexpr int kAppendSlotShift = 4;
 
 __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -189,7 +187,8 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Groups of 8 page
     // slots are numbered head-major, so the workgroups of one page -- which together read
     // whole token rows and write one whole page -- all land on the same XCD.
-    const int32_t group = blockIdx.x / (8 * Hkv), in_group = blockIdx.x - group * (8 * Hkv);
+    const int32_t per = 8 * Hkv;
+    const int32_t group = blockIdx.x / per, in_group = blockIdx.x - group * per;
     const int32_t h = in_group >> 3;
     const int32_t slot_id = group * 8 + (in_group & 7);
     int32_t lo = 0, hi = S;                                       // largest s with start(s) <= slot_id
@@ -202,10 +201,13 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     const int32_t first = ctx_lens[s];                            // the step fills positions [first, last)
     const int32_t last = first + (cu_q_lens[s + 1] - t_seq);
     if (last - first == 1) return;                               // single tokens: append_token_kernel
-    const int32_t blk0 = (first >> 4) + kAppendPages * (slot_id - ((t_seq >> kAppendSlotShift) + 2 * s));
-    if ((blk0 << 4) >= last) return;
+    const int32_t blk = (first >> 4) + (slot_id - ((t_seq >> kAppendSlotShift) + 2 * s));
+    const int32_t p0 = blk << 4;                                  // first position of the page
+    if (p0 >= last || blk >= max_blocks) return;
+    const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
+    if (page < 0 || page >= num_pages) return;
     const int32_t block_elems = kPage * D;
-    const int64_t row = (int64_t)Hkv * D;                         // elements between consecutive tokens
+    const int32_t row = Hkv * D;                                  // elements between consecutive tokens
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (wave * 32 >= D) return;                                   // head_dim 64: two wavefronts suffice
 
@@ -218,47 +220,33 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     // Either way consecutive lanes store consecutive units: 1 KiB per store instruction.
     const int32_t tok = lane & 15, dblk = wave * 4 + (lane >> 4);
     const int32_t th = (lane >> 4) & 1, feat = wave * 32 + (lane >> 5) * 16 + (lane & 15);
-    uint16_t* kblk[kAppendPages];
-    bool k_ok[kAppendPages], v_full[kAppendPages], v_part[kAppendPages];
-    u32x4 kv[kAppendPages];
-    uint16_t e[kAppendPages][8];
-    const uint16_t* vsrc[kAppendPages];
-    int32_t vpos[kAppendPages];
+    // packed token index of page position p0 (may lie before the step's first token)
+    const int64_t tok_base = (int64_t)t_seq + (p0 - first);
+    const int32_t pos = p0 + tok;
+    const bool k_ok = pos >= first && pos < last;
+    const int32_t vpos = p0 + th * 8;                             // first position of the half
+    const bool v_full = vpos >= first && vpos + 8 <= last;
+    const uint16_t* ksrc = k_new + (tok_base + tok) * row + (int64_t)h * D + dblk * 8;
+    const uint16_t* vsrc = v_new + (tok_base + th * 8) * row + (int64_t)h * D + feat;
+    uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
+    uint16_t* dst = kblk + (int64_t)Hkv * block_elems + (wave * 64 + lane) * 8;
+    u32x4 kv;
+    uint16_t e[8];
+    if (k_ok) kv = __builtin_nontemporal_load((const u32x4*)ksrc);
+    if (v_full) {
 #pragma unroll
-    for (int p = 0; p < kAppendPages; ++p) {
-        const int32_t blk = blk0 + p, p0 = blk << 4;              // first position of the page
-        int32_t page = -1;
-        if (p0 < last && blk < max_blocks) page = block_tables[(int64_t)s * max_blocks + blk];
-        const bool ok = page >= 0 && page < num_pages;
-        kblk[p] = layer_base + (int64_t)(ok ? page : 0) * page_stride + (int64_t)h * block_elems;
-        // packed token index of page position p0 (may lie before the step's first token)
-        const int64_t tok_base = (int64_t)t_seq + (p0 - first);
-        const int32_t pos = p0 + tok;
-        k_ok[p] = ok && pos >= first && pos < last;
-        if (k_ok[p]) kv[p] = __builtin_nontemporal_load((const u32x4*)(k_new + ((tok_base + tok) * Hkv + h) * D + dblk * 8));
-        vpos[p] = p0 + th * 8;                                    // first position of the half
-        vsrc[p] = v_new + ((tok_base + th * 8) * Hkv + h) * D + feat;
-        v_full[p] = ok && vpos[p] >= first && vpos[p] + 8 <= last;
-        v_part[p] = ok && !v_full[p];
-        if (v_full[p]) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) e[p][j] = __builtin_nontemporal_load(vsrc[p] + j * row);
-        }
+        for (int j = 0; j < 8; ++j) e[j] = __builtin_nontemporal_load(vsrc + j * row);
     }
+    if (k_ok) __builtin_nontemporal_store(kv, (u32x4*)(kblk + (dblk * 16 + tok) * 8));
+    if (v_full) {
+        const u32x4 unit = { (uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
+                             (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16) };
+        __builtin_nontemporal_store(unit, (u32x4*)dst);
+    } else {
+        // a half the step fills only partly: element by element
 #pragma unroll
-    for (int p = 0; p < kAppendPages; ++p) {
-        if (k_ok[p]) __builtin_nontemporal_store(kv[p], (u32x4*)(kblk[p] + (dblk * 16 + tok) * 8));
-        uint16_t* dst = kblk[p] + (int64_t)Hkv * block_elems + (wave * 64 + lane) * 8;
-        if (v_full[p]) {
-            const u32x4 unit = { (uint32_t)e[p][0] | ((uint32_t)e[p][1] << 16), (uint32_t)e[p][2] | ((uint32_t)e[p][3] << 16),
-                                 (uint32_t)e[p][4] | ((uint32_t)e[p][5] << 16), (uint32_t)e[p][6] | ((uint32_t)e[p][7] << 16) };
-            __builtin_nontemporal_store(unit, (u32x4*)dst);
-        } else if (v_part[p]) {
-            // a half the step fills only partly: element by element
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (vpos[p] + j >= first && vpos[p] + j < last) dst[j] = vsrc[p][j * row];
-        }
+        for (int j = 0; j < 8; ++j)
+            if (vpos + j >= first && vpos + j < last) dst[j] = vsrc[j * row];
     }
 }
 
