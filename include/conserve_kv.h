@@ -8,7 +8,8 @@
  *   - returns a cs_status (0 = CS_OK, negative = error); all checks that need only host
  *     data are made before anything is enqueued, and a failed call enqueues nothing;
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
- *     calls never synchronise, never allocate or free, and keep no state between calls;
+ *     calls never synchronise, never allocate or free, and keep no state between calls
+ *     (the one exception is the host-side cs_page_map object at the end of this file);
  *   - every pointer is owned by the caller and must stay valid until the enqueued work has
  *     run.  "device" pointers are HIP device memory of the current device, "host" pointers
  *     are ordinary host memory read during the call only;
@@ -52,7 +53,8 @@ typedef enum {
     CS_ERR_UNSUPPORTED = -2,        /* page size, head_dim or head ratio not supported   */
     CS_ERR_WORKSPACE_TOO_SMALL = -3,
     CS_ERR_STAGING_TOO_SMALL = -4,
-    CS_ERR_HIP = -5                 /* a launch failed; see cs_last_hip_error()          */
+    CS_ERR_HIP = -5,                /* a launch failed; see cs_last_hip_error()          */
+    CS_ERR_NO_HOST_PAGES = -6       /* the host page store has no free run long enough   */
 } cs_status;
 
 #define CS_PAGE_SIZE 16
@@ -215,6 +217,71 @@ int cs_run_layers_f16(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer
                       int64_t q_layer_stride, int64_t kv_layer_stride,
                       int32_t num_q_heads, float softmax_scale, void* workspace, size_t workspace_bytes,
                       const cs_safepoint* safepoint, int32_t* preempted_before_layer, void* stream);
+
+/* ---- The page table's extra field (Sec. 5): which host page holds the checkpoint of a GPU
+ * page.  Host-side bookkeeping only; it is the one object of this library that keeps state
+ * (create allocates it with malloc, destroy frees it), and it is not thread-safe: one
+ * scheduler thread owns it.
+ *
+ * The host page store it indexes is caller-owned PINNED memory laid out
+ *     store[host page][layer][page bytes]
+ * so one host page is the contiguous checkpoint of one GPU page in all layers of the store,
+ * and a checkpoint round, which takes its host pages as ONE ascending run, is one contiguous
+ * device-to-host copy (Sec. 5: gather into a contiguous buffer, transfer once).
+ *
+ * Life of a page: cs_page_map_checkpoint gives every listed GPU page that has no host copy
+ * yet the next page of a fresh run (those pages are what cs_kv_ckpt_save_run then copies);
+ * cs_page_map_evict (preemption) forgets the GPU side and reports the host pages, which stay
+ * allocated; cs_page_map_bind (resume) ties them to the fresh GPU pages they were loaded
+ * into by cs_kv_ckpt_load_run; cs_page_map_drop frees host pages (request finished). ---- */
+typedef struct cs_page_map cs_page_map;
+
+typedef struct cs_host_store {
+    void*   base;            /* PINNED host memory: num_pages * num_layers * page bytes   */
+    int32_t num_layers;      /* layers a host page holds                                 */
+    int32_t num_pages;       /* host pages                                               */
+} cs_host_store;
+
+/* NULL if a count is not positive or memory is short. */
+cs_page_map* cs_page_map_create(int32_t num_gpu_pages, int32_t num_host_pages);
+void cs_page_map_destroy(cs_page_map* map);
+
+/* Host page of a GPU page, -1 if it has none (or the id is out of range). */
+int32_t cs_page_map_host_of(const cs_page_map* map, int32_t gpu_page);
+/* GPU page a host page is tied to; -1: allocated but evicted; -2: free or out of range. */
+int32_t cs_page_map_gpu_of(const cs_page_map* map, int32_t host_page);
+int32_t cs_page_map_free_host_pages(const cs_page_map* map);
+
+/* One checkpoint round over gpu_pages[0..n): the pages without a host copy (each once, in
+ * the order given) are written to dirty_out (room for n) and get the host pages
+ * *first_host, *first_host + 1, ...  Returns how many (0: everything was saved already),
+ * CS_ERR_NO_HOST_PAGES if no free run of that length exists, CS_ERR_INVALID_ARG for a page
+ * id out of range or a null pointer; on error the map is unchanged. */
+int32_t cs_page_map_checkpoint(cs_page_map* map, const int32_t* gpu_pages, int32_t n,
+                               int32_t* dirty_out, int32_t* first_host);
+
+/* Preemption: the GPU pages go back to the allocator.  host_out[i] (room for n) = the host
+ * page of gpu_pages[i], -1 if it never was checkpointed (its tokens must be recomputed). */
+int cs_page_map_evict(cs_page_map* map, const int32_t* gpu_pages, int32_t n, int32_t* host_out);
+
+/* Resume: host_pages[i] (allocated, evicted) now backs gpu_pages[i] (no host copy).  All or
+ * nothing: CS_ERR_INVALID_ARG leaves the map unchanged. */
+int cs_page_map_bind(cs_page_map* map, const int32_t* host_pages, const int32_t* gpu_pages, int32_t n);
+
+/* Free host pages, tied to a GPU page or not.  Freeing a free page is an error (all or
+ * nothing). */
+int cs_page_map_drop(cs_page_map* map, const int32_t* host_pages, int32_t n);
+
+/* cs_kv_ckpt_save / cs_kv_ckpt_load into and out of the host page store: the n pages go to /
+ * come from the host pages first_host_page .. + n.  The staging buffer is used page-major
+ * ([n][layers][page bytes]) so that the host side is one contiguous copy.
+ * layer_end - layer_begin must equal store->num_layers. */
+int cs_kv_ckpt_save_run(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                        const int32_t* page_ids, int32_t n, void* staging, size_t staging_bytes,
+                        const cs_host_store* store, int32_t first_host_page, void* stream);
+int cs_kv_ckpt_load_run(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
+                        const int32_t* page_ids, int32_t n, void* staging, size_t staging_bytes,
+                        const cs_host_store* store, int32_t first_host_page, void* stream);
 
 /* Plain device-to-device copy kernel of `bytes` (multiple of 16, both pointers 16-byte
  * aligned): the measured copy ceiling of the device and the calibration point for hardware

@@ -19,6 +19,7 @@ CS_ERR_UNSUPPORTED = -2
 CS_ERR_WORKSPACE_TOO_SMALL = -3
 CS_ERR_STAGING_TOO_SMALL = -4
 CS_ERR_HIP = -5
+CS_ERR_NO_HOST_PAGES = -6
 PAGE = 16
 
 
@@ -49,6 +50,10 @@ class cs_batch(ctypes.Structure):
 
 
 POLL_FN = ctypes.CFUNCTYPE(ctypes.c_int32, ctypes.c_void_p)
+
+
+class cs_host_store(ctypes.Structure):
+    _fields_ = [("base", ctypes.c_void_p), ("num_layers", ctypes.c_int32), ("num_pages", ctypes.c_int32)]
 
 
 class cs_safepoint(ctypes.Structure):
@@ -93,6 +98,18 @@ def lib():
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
         for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp, vp]
+        for f in (L.cs_kv_ckpt_save_run, L.cs_kv_ckpt_load_run):
+            f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, ctypes.POINTER(cs_host_store), i32, vp]
+        ip = ctypes.POINTER(ctypes.c_int32)
+        L.cs_page_map_create.restype, L.cs_page_map_create.argtypes = vp, [i32, i32]
+        L.cs_page_map_destroy.restype, L.cs_page_map_destroy.argtypes = None, [vp]
+        L.cs_page_map_host_of.restype, L.cs_page_map_host_of.argtypes = i32, [vp, i32]
+        L.cs_page_map_gpu_of.restype, L.cs_page_map_gpu_of.argtypes = i32, [vp, i32]
+        L.cs_page_map_free_host_pages.restype, L.cs_page_map_free_host_pages.argtypes = i32, [vp]
+        L.cs_page_map_checkpoint.restype, L.cs_page_map_checkpoint.argtypes = i32, [vp, ip, i32, ip, ip]
+        L.cs_page_map_evict.restype, L.cs_page_map_evict.argtypes = ctypes.c_int, [vp, ip, i32, ip]
+        L.cs_page_map_bind.restype, L.cs_page_map_bind.argtypes = ctypes.c_int, [vp, ip, ip, i32]
+        L.cs_page_map_drop.restype, L.cs_page_map_drop.argtypes = ctypes.c_int, [vp, ip, i32]
         L.cs_run_layers_f16.restype = ctypes.c_int
         L.cs_run_layers.restype = ctypes.c_int
         L.cs_run_layers_f16.argtypes = L.cs_run_layers.argtypes = [PP, i32, i32, BP, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, i32,
@@ -114,7 +131,9 @@ EXPORTS = [
     "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
     "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
-    "cs_kv_ckpt_load", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items",
+    "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
+    "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
+    "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items",
     "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_status_string", "cs_last_hip_error",
 ]
 
@@ -262,6 +281,99 @@ def cs_kv_ckpt_load(pool: Pool, layer_begin: int, layer_end: int, page_ids: torc
     _check(lib().cs_kv_ckpt_load(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids), page_ids.numel(),
                                  _ptr(staging), staging.numel() * staging.element_size(), _ptr(host_buf),
                                  _stream(stream)), "cs_kv_ckpt_load")
+
+
+class HostStore:
+    """A cs_host_store over a pinned CPU tensor [num_pages, num_layers, page_elems]."""
+
+    def __init__(self, tensor: torch.Tensor):
+        assert tensor.is_pinned() and tensor.is_contiguous() and tensor.dim() == 3
+        self.tensor = tensor
+        self.c = cs_host_store(_ptr(tensor), int(tensor.shape[1]), int(tensor.shape[0]))
+
+
+class PageMap:
+    """cs_page_map: which host page holds the checkpoint of a GPU page (host bookkeeping)."""
+
+    def __init__(self, num_gpu_pages: int, num_host_pages: int):
+        self._h = lib().cs_page_map_create(num_gpu_pages, num_host_pages)
+        if not self._h:
+            raise CsError(CS_ERR_INVALID_ARG, "cs_page_map_create")
+
+    def close(self):
+        if getattr(self, "_h", None) and _lib is not None:
+            _lib.cs_page_map_destroy(self._h)
+        self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _arr(xs):
+        return (ctypes.c_int32 * max(1, len(xs)))(*xs)
+
+    def host_of(self, gpu_page: int) -> int:
+        return int(lib().cs_page_map_host_of(self._h, gpu_page))
+
+    def gpu_of(self, host_page: int) -> int:
+        return int(lib().cs_page_map_gpu_of(self._h, host_page))
+
+    def free_host_pages(self) -> int:
+        return int(lib().cs_page_map_free_host_pages(self._h))
+
+    def checkpoint(self, gpu_pages):
+        """-> (pages that need saving, first host page of their run); raises CsError."""
+        gpu_pages = list(gpu_pages)
+        dirty = self._arr([0] * len(gpu_pages))
+        first = ctypes.c_int32(-1)
+        n = lib().cs_page_map_checkpoint(self._h, self._arr(gpu_pages), len(gpu_pages), dirty, ctypes.byref(first))
+        if n < 0:
+            raise CsError(n, "cs_page_map_checkpoint")
+        return [int(dirty[i]) for i in range(n)], int(first.value)
+
+    def evict(self, gpu_pages):
+        gpu_pages = list(gpu_pages)
+        out = self._arr([0] * len(gpu_pages))
+        _check(lib().cs_page_map_evict(self._h, self._arr(gpu_pages), len(gpu_pages), out), "cs_page_map_evict")
+        return [int(out[i]) for i in range(len(gpu_pages))]
+
+    def bind(self, host_pages, gpu_pages):
+        host_pages, gpu_pages = list(host_pages), list(gpu_pages)
+        assert len(host_pages) == len(gpu_pages)
+        _check(lib().cs_page_map_bind(self._h, self._arr(host_pages), self._arr(gpu_pages), len(host_pages)), "cs_page_map_bind")
+
+    def drop(self, host_pages):
+        host_pages = list(host_pages)
+        _check(lib().cs_page_map_drop(self._h, self._arr(host_pages), len(host_pages)), "cs_page_map_drop")
+
+
+def ascending_runs(pages):
+    """Split a list of host pages into maximal runs p, p+1, ...: [(start index, length)]."""
+    runs, i = [], 0
+    while i < len(pages):
+        j = i + 1
+        while j < len(pages) and pages[j] == pages[j - 1] + 1:
+            j += 1
+        runs.append((i, j - i))
+        i = j
+    return runs
+
+
+def cs_kv_ckpt_save_run(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,
+                        staging: torch.Tensor, store: HostStore, first_host_page: int, stream=None):
+    _check(lib().cs_kv_ckpt_save_run(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids), page_ids.numel(),
+                                     _ptr(staging), staging.numel() * staging.element_size(), ctypes.byref(store.c),
+                                     first_host_page, _stream(stream)), "cs_kv_ckpt_save_run")
+
+
+def cs_kv_ckpt_load_run(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,
+                        staging: torch.Tensor, store: HostStore, first_host_page: int, stream=None):
+    _check(lib().cs_kv_ckpt_load_run(ctypes.byref(pool.c), layer_begin, layer_end, _ptr(page_ids), page_ids.numel(),
+                                     _ptr(staging), staging.numel() * staging.element_size(), ctypes.byref(store.c),
+                                     first_host_page, _stream(stream)), "cs_kv_ckpt_load_run")
 
 
 def cs_run_layers(pool: Pool, layer_begin: int, layer_end: int, batch: Batch, q: torch.Tensor,

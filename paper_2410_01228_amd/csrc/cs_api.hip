@@ -310,6 +310,38 @@ int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_
     return launch_page_copy(*pool, l0, l1, ids, n, staging, false, (hipStream_t)stream);
 }
 
+static int run_common(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                      const void* staging, size_t staging_bytes, const cs_host_store* store, int32_t first) {
+    const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);
+    if (rc <= 0) return rc;
+    if (!store || !store->base || store->num_layers != l1 - l0 || store->num_pages <= 0) return CS_ERR_INVALID_ARG;
+    if (first < 0 || (int64_t)first + n > store->num_pages) return CS_ERR_INVALID_ARG;
+    return 1;   // proceed
+}
+
+int cs_kv_ckpt_save_run(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                        void* staging, size_t staging_bytes, const cs_host_store* store, int32_t first, void* stream) {
+    const int rc = run_common(pool, l0, l1, ids, n, staging, staging_bytes, store, first);
+    if (rc <= 0) return rc;
+    const int lrc = launch_page_copy(*pool, l0, l1, ids, n, staging, true, (hipStream_t)stream, true);
+    if (lrc) return lrc;
+    const size_t fat = (size_t)(l1 - l0) * cs_page_bytes(pool->num_kv_heads, pool->head_dim);   // one host page
+    const hipError_t e = hipMemcpyAsync((char*)store->base + (size_t)first * fat, staging, (size_t)n * fat,
+                                        hipMemcpyDeviceToHost, (hipStream_t)stream);
+    return e == hipSuccess ? CS_OK : hip_failed(e, "checkpoint device-to-host copy");
+}
+
+int cs_kv_ckpt_load_run(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_t* ids, int32_t n,
+                        void* staging, size_t staging_bytes, const cs_host_store* store, int32_t first, void* stream) {
+    const int rc = run_common(pool, l0, l1, ids, n, staging, staging_bytes, store, first);
+    if (rc <= 0) return rc;
+    const size_t fat = (size_t)(l1 - l0) * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const hipError_t e = hipMemcpyAsync(staging, (const char*)store->base + (size_t)first * fat, (size_t)n * fat,
+                                        hipMemcpyHostToDevice, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_failed(e, "checkpoint host-to-device copy");
+    return launch_page_copy(*pool, l0, l1, ids, n, staging, false, (hipStream_t)stream, true);
+}
+
 static int run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_batch* batch,
                       const void* q, const void* k_new, const void* v_new, void* out,
                       int64_t q_stride, int64_t kv_stride, int32_t Hq, float scale,
@@ -412,6 +444,7 @@ const char* cs_status_string(int status) {
         case CS_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
         case CS_ERR_STAGING_TOO_SMALL: return "staging buffer too small";
         case CS_ERR_HIP: return "HIP error";
+        case CS_ERR_NO_HOST_PAGES: return "no free run of host pages";
         default: return "unknown status";
     }
 }

@@ -68,7 +68,8 @@ DecodeWorkspace decode_workspace(const DecodePlan& p, int32_t num_seqs, int32_t 
 int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
                   const void* k_new, const void* v_new, hipStream_t st);
 int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_end,
-                     const int32_t* ids, int32_t n, void* staging, bool to_staging, hipStream_t st);
+                     const int32_t* ids, int32_t n, void* staging, bool to_staging, hipStream_t st,
+                     bool page_major = false);
 int launch_token_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_end,
                       const int32_t* token_slots, int32_t n, void* staging, bool to_staging, hipStream_t st);
 int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st);

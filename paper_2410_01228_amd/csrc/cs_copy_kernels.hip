@@ -21,8 +21,9 @@ constexpr int kChunkBytes = kCopyThreads * 16 * kCopyUnroll;
 template <bool kToStaging>
 __global__ __launch_bounds__(kCopyThreads) void page_copy_kernel(
     char* __restrict__ pool_base, int64_t layer_stride_b, int64_t page_stride_b,
-    int32_t num_pages, int32_t layer_begin, const int32_t* __restrict__ ids, int32_t n,
-    char* __restrict__ staging, int32_t page_bytes, int32_t chunks_per_page)
+    int32_t num_pages, int32_t layer_begin, const int32_t* __restrict__ ids,
+    char* __restrict__ staging, int64_t stg_layer_stride_b, int64_t stg_page_stride_b,
+    int32_t page_bytes, int32_t chunks_per_page)
 {
     // grid.x = n * chunks_per_page (page-major), grid.y = layers
     const int32_t i = blockIdx.x / chunks_per_page;
@@ -31,7 +32,7 @@ __global__ __launch_bounds__(kCopyThreads) void page_copy_kernel(
     const int32_t id = ids[i];
     if (id < 0 || id >= num_pages) return;                       // never touch a bad page id
     char* p = pool_base + (int64_t)(layer_begin + l) * layer_stride_b + (int64_t)id * page_stride_b;
-    char* s = staging + ((int64_t)l * n + i) * (int64_t)page_bytes;
+    char* s = staging + l * stg_layer_stride_b + i * stg_page_stride_b;
     const char* src = kToStaging ? p : s;
     char* dst = kToStaging ? s : p;
     const int32_t off0 = c * kChunkBytes + threadIdx.x * 16;
@@ -49,21 +50,25 @@ __global__ __launch_bounds__(kCopyThreads) void page_copy_kernel(
 }
 
 int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_end,
-                     const int32_t* ids, int32_t n, void* staging, bool to_staging, hipStream_t st)
+                     const int32_t* ids, int32_t n, void* staging, bool to_staging, hipStream_t st,
+                     bool page_major)
 {
     const int32_t layers = layer_end - layer_begin;
     if (n == 0 || layers == 0) return CS_OK;
     const int32_t page_bytes = (int32_t)cs_page_bytes(pool.num_kv_heads, pool.head_dim);
     const int32_t cpp = (page_bytes + kChunkBytes - 1) / kChunkBytes;
     dim3 grid((uint32_t)n * cpp, (uint32_t)layers);
+    // staging[layer][page] (the default) or staging[page][layer] (one page's layers together)
+    const int64_t stg_layer = page_major ? (int64_t)page_bytes : (int64_t)n * page_bytes;
+    const int64_t stg_page = page_major ? (int64_t)layers * page_bytes : (int64_t)page_bytes;
     if (to_staging)
         hipLaunchKernelGGL(page_copy_kernel<true>, grid, dim3(kCopyThreads), 0, st,
                            (char*)pool.base, pool.layer_stride * 2, pool.page_stride * 2, pool.num_pages,
-                           layer_begin, ids, n, (char*)staging, page_bytes, cpp);
+                           layer_begin, ids, (char*)staging, stg_layer, stg_page, page_bytes, cpp);
     else
         hipLaunchKernelGGL(page_copy_kernel<false>, grid, dim3(kCopyThreads), 0, st,
                            (char*)pool.base, pool.layer_stride * 2, pool.page_stride * 2, pool.num_pages,
-                           layer_begin, ids, n, (char*)staging, page_bytes, cpp);
+                           layer_begin, ids, (char*)staging, stg_layer, stg_page, page_bytes, cpp);
     return check_launch("page_copy_kernel");
 }
 
