@@ -302,6 +302,11 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t num_kv_heads, int32
  * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */
 void cs_set_decode_split_tokens(int32_t tokens);
 
+/* Host-only view of one more launch decision, for tests: the pages a wavefront of the decode
+ * kernel will keep in flight for this batch (1 or 2; see cs_set_decode_pages_ahead), or
+ * CS_ERR_INVALID_ARG. */
+int32_t cs_debug_decode_pages_ahead(const cs_batch* batch, int32_t num_kv_heads, int32_t head_dim);
+
 /* Tuning knob for measurements and tests: pages (of 16 keys) a wavefront of the decode kernel
  * keeps in flight beyond the one it is multiplying: 1 or 2; 0 = automatic (by item length and
  * grid size).  Process-wide. */

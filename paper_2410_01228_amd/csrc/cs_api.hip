@@ -423,6 +423,11 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t Hkv, int32_t D, uin
     return p.total_items;
 }
 
+int32_t cs_debug_decode_pages_ahead(const cs_batch* batch, int32_t Hkv, int32_t D) {
+    if (!shape_supported(Hkv, D) || validate_batch(nullptr, batch) != CS_OK) return CS_ERR_INVALID_ARG;
+    return plan_decode(batch, Hkv, D).pages_ahead;
+}
+
 void cs_set_decode_pages_ahead(int32_t pages) {
     g_forced_ahead.store(pages == 1 || pages == 2 ? pages : 0);
 }

@@ -182,6 +182,37 @@ def test_decode_plan_falls_back_to_the_planning_kernel_beyond_the_argument_block
         lib.cs_set_decode_split_tokens(0)
 
 
+def test_decode_prefetch_depth_follows_the_launch_volume():
+    """Two pages in flight per wavefront from about 0.65 GB of K/V per launch on, one below;
+    the knob overrides either way."""
+    lib = cs.lib()
+
+    def ahead(ctx, Hkv, D):
+        b, keep = _batch(ctx, [1] * len(ctx), max_blocks=1 << 16)
+        return lib.cs_debug_decode_pages_ahead(ctypes.byref(b), Hkv, D)
+
+    # 256 sequences x 2304 keys x 8 heads x 128 x 4 bytes = 2.4 GB
+    assert ahead([2303] * 256, 8, 128) == 2
+    # 64 x 4600 keys x 4 heads: 0.6 GB
+    assert ahead([4599] * 64, 4, 128) == 1
+    # either side of the threshold: keys * 2 * Hkv * D * 2 bytes against 650e6
+    keys_at = -(-650000000 // (2 * 8 * 128 * 2))            # the first key count at or over it
+    assert ahead([keys_at - 1], 8, 128) == 2                # ctx + 1 keys = keys_at
+    assert ahead([keys_at - 2], 8, 128) == 1
+    try:
+        lib.cs_set_decode_pages_ahead(1)
+        assert ahead([2303] * 256, 8, 128) == 1
+        lib.cs_set_decode_pages_ahead(2)
+        assert ahead([10], 8, 128) == 2
+        lib.cs_set_decode_pages_ahead(7)                    # not a depth: back to automatic
+        assert ahead([10], 8, 128) == 1
+    finally:
+        lib.cs_set_decode_pages_ahead(0)
+    b, keep = _batch([5, 5], [3, 4], max_blocks=16)
+    assert lib.cs_debug_decode_pages_ahead(ctypes.byref(b), 8, 128) == 1      # no decode sequence
+    assert lib.cs_debug_decode_pages_ahead(ctypes.byref(b), 8, 100) == cs.CS_ERR_INVALID_ARG
+
+
 def test_debug_copy_argument_checks():
     lib = cs.lib()
     assert lib.cs_debug_copy(0x1000, 0x2000, 24, None) == cs.CS_ERR_INVALID_ARG          # not a multiple of 16
