@@ -267,7 +267,8 @@ def test_f16_key_range_split_and_shrunk_config():
 def test_random_mixed_batches(seed):
     """Seeded random shapes and batches: any group size up to 16, either head_dim, decode
     tokens, chunks and idle sequences in any order, contexts on and off page boundaries, with
-    the automatic and with a forced decode split."""
+    the automatic and with a forced decode split, fused and separate launches, either decode
+    prefetch depth."""
     import random
     rnd = random.Random(1000 + seed)
     D = rnd.choice([64, 128])
@@ -287,7 +288,9 @@ def test_random_mixed_batches(seed):
     split = rnd.choice([0, 0, 64, 256])
     gain = rnd.choice([1.0, 1.0, 4.0])
     dtype = rnd.choice([torch.bfloat16, torch.bfloat16, torch.float16])
-    out, st, _, _ = run_step(b, 2000 + seed, q_gain=gain, split=split, dtype=dtype)
+    fuse = rnd.choice([True, True, False])                 # one fused grid, or two kernels in a row
+    ahead = rnd.choice([0, 1, 2])                           # decode prefetch depth: automatic, one, two pages
+    out, st, _, _ = run_step(b, 2000 + seed, q_gain=gain, split=split, dtype=dtype, fuse=fuse, ahead=ahead)
     active = [s for s in range(S) if ql[s] > 0]
     assert_attention_close(out, st.oracle_attention(active),
                            "random seed %d: %d/%d/%d ctx %s q %s split %d gain %g %s" % (seed, sh.Hq, Hkv, D, ctx, ql, split, gain, dtype))
