@@ -1,5 +1,6 @@
 // Kernels, launch plan and launcher of the prefill-chunk path (the workgroup's work itself is
 // in cs_prefill_impl.h, shared with the fused mixed-batch kernel).
+#include <cmath>
 #include "cs_prefill_impl.h"
 
 namespace cs {
@@ -107,18 +108,49 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     p.max_ranges = 1;
     if (tiles == 0) return p;
     const int64_t wgs = tiles * Hkv;
-    const int64_t avg = total_steps / tiles;
-    // Cut key ranges only when the tiles alone would leave CUs without any workgroup (a small
-    // chunk on a long context: few tiles, each walking thousands of keys).  Measured: once
-    // every CU has a workgroup, uneven tiles cost less than the partials of a split would --
-    // the long tiles speed up as the short ones retire.  When cutting, aim at about four
+    // Tiles that would leave CUs without any workgroup (a small chunk on a long context: few
+    // tiles, each walking thousands of keys) are cut along the keys: aim at about four
     // workgroups per CU with ranges of at least 32 steps (1024 keys), at most 8 per tile.
-    (void)avg;
     if (wgs < 256) {
         int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 1023) / 1024);
         rs = std::max<int64_t>(rs, (max_steps + 7) / 8);
         if (rs < max_steps) {
             p.range_steps = (int32_t)rs;
+            p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
+        }
+    } else if (wgs <= 1024) {
+        // Between one and four workgroups per CU the grid runs as one or two rounds over the 512
+        // workgroup slots, and a round that is not full costs almost as much as a full one.
+        // Cutting every tile into r key ranges multiplies the workgroups and divides their
+        // length: pick the r whose rounds come out fullest.  The cost model is fitted to
+        // measurements (it reproduces them within a few percent), in steps of a workgroup that
+        // shares its CU: a workgroup with the CU to itself runs a step in 0.76 of that; while all
+        // workgroups are resident the longest tile decides, beyond that the average tile and a
+        // round count halfway between W/512 and its ceiling (tiles end at different times, so
+        // rounds blur); every workgroup pays about 8 steps of start-up and store; the partials
+        // cost a launch plus their bytes written and read back at 5 TB/s.
+        const double avg_steps = (double)total_steps / (double)tiles;
+        auto cost = [&](int r) -> double {
+            const double W = (double)wgs * r;
+            double c;
+            if (W <= 256) c = 0.76 * ((double)max_steps / r + 8);
+            else if (W <= 512) c = (0.76 + (W - 256) / 256 * 0.24) * ((double)max_steps / r + 8);
+            else c = 0.5 * (W / 512 + std::ceil(W / 512)) * (avg_steps / r + 8);
+            if (r > 1) {
+                const double part_bytes = W * kTileCols * 16 * (D + 4) * 4.0;
+                c += (10.0 + 2.0 * part_bytes / 5.0e6) / 0.87;     // microseconds -> steps
+            }
+            return c;
+        };
+        int best = 1;
+        double best_cost = cost(1);
+        for (int r = 2; r <= 8; ++r) {
+            if (max_steps / r < 64) break;
+            const double c = cost(r);
+            if (c < best_cost) { best = r; best_cost = c; }
+        }
+        if (best > 1 && best_cost <= 0.92 * cost(1)) {
+            p.range_steps = (max_steps + best - 1) / best;
             p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
         }
     }

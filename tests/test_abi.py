@@ -213,6 +213,32 @@ def test_decode_prefetch_depth_follows_the_launch_volume():
     assert lib.cs_debug_decode_pages_ahead(ctypes.byref(b), 8, 100) == cs.CS_ERR_INVALID_ARG
 
 
+def test_prefill_key_range_plan_follows_the_rounds():
+    """Workspace bytes show the prefill plan: partial results exist only when tiles are cut into
+    key ranges.  Few tiles on a long context are cut; a grid of exactly one workgroup per CU
+    is cut in two on a long context and left alone on a short one; two workgroups per CU
+    (a full round) are never cut; 640 workgroups are cut only when the tiles are long."""
+    lib = cs.lib()
+
+    def ranges(Hq, Hkv, P, C):
+        b, keep = _batch([C], [P], max_blocks=1 << 16)
+        by = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), Hq, Hkv, 128)
+        slots = (P * (Hq // Hkv) + 127) // 128 + 1
+        return by / (slots * Hkv * 8 * 16 * 132 * 4)
+
+    assert ranges(32, 8, 128, 32768) > 4                 # 32 tile workgroups
+    assert 1.9 < ranges(32, 8, 1024, 32768) < 2.1        # 256
+    assert 1.9 < ranges(32, 8, 1024, 4096) < 2.1
+    assert ranges(32, 8, 1024, 2048) == 0                # ranges would be shorter than 64 steps
+    assert ranges(28, 4, 1280, 32768) >= 3               # 280: three or more ranges fill the rounds
+    assert ranges(28, 4, 1280, 4096) == 0
+    assert ranges(32, 8, 2048, 32768) == 0               # 512: one full round
+    assert ranges(28, 4, 2048, 65536) == 0               # 448
+    assert 3.9 < ranges(32, 8, 2560, 32768) < 4.1        # 640 -> 2560 = five rounds
+    assert ranges(32, 8, 2560, 4096) == 0
+    assert ranges(32, 8, 4608, 65536) == 0               # beyond 1024: rounds blur, never cut
+
+
 def test_debug_copy_argument_checks():
     lib = cs.lib()
     assert lib.cs_debug_copy(0x1000, 0x2000, 24, None) == cs.CS_ERR_INVALID_ARG          # not a multiple of 16

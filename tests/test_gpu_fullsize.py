@@ -125,6 +125,25 @@ def test_very_long_contexts():
     run_batch(b, 90, [0, 1, 2], rows_per_chunk=5)
 
 
+@pytest.mark.parametrize("Hq,Hkv,ctx,ql", [
+    (32, 8, [8192], [1024]),                 # 256 tile workgroups: cut in two, one full round of pairs
+    (28, 4, [16384], [1280]),                # 280: cut in three, two rounds
+    (32, 8, [12000, 17000], [1280, 1280]),   # 640 over two sequences of different length
+    (64, 8, [33000], [1536]),                # 768: cut in two
+])
+def test_chunks_between_one_and_four_workgroups_per_cu_are_cut_into_key_ranges(Hq, Hkv, ctx, ql):
+    """A grid of 256..1024 tile workgroups runs as one or two rounds over the workgroup slots;
+    on long contexts the host cuts the tiles into key ranges so that the rounds come out full.
+    Full-size parity of exactly those plans (the plan must really cut), plus two decode
+    sequences riding along."""
+    sh = synth.Shape(Hq, Hkv, 128)
+    b = synth.make_batch(sh, [700, 3000] + ctx, [1, 1] + ql, synth.generator(91))
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    only_chunks = cs.Batch(b.block_tables[2:], b.ctx_lens[2:], b.cu_q_lens[2:] - 2)
+    assert cs.cs_paged_attention_workspace_bytes(only_chunks, sh.Hq, sh.Hkv, sh.D) > 0    # partials: the tiles are cut
+    run_batch(b, 91, list(range(len(ctx) + 2)), rows_per_chunk=4)
+
+
 def test_qwen14b_ckpt_full_size():
     """Workload 4 at its stated page counts on a subset of layers: gather all dirty pages of 3
     of the 48 layers (the kernels index layers independently), restore into the spare pages,
