@@ -485,13 +485,17 @@ def fit_latency_model(reps=8):
         torch.cuda.synchronize()
         samples.append((batch, e0.elapsed_time(e1) / reps * 1e-3))
     m, rel = fit(samples)
+    import numpy as np
+    big = np.array([t >= 150e-6 for _, t in samples])           # batches long enough to matter to an SLO
     r = {"shape": "32/8/128", "samples": len(samples), "k_token_s": m.k_p, "k2_attention_s": m.k2,
          "k4_memory_s": m.k4, "k5_constant_s": m.k5,
          "mean_rel_err": round(float(rel.mean()), 4), "max_rel_err": round(float(rel.max()), 4),
+         "mean_rel_err_150us_up": round(float(rel[big].mean()), 4), "max_rel_err_150us_up": round(float(rel[big].max()), 4),
          "can_schedule_2048_tokens_ctx0_vs_ctx32768_at_1ms": [
              m.can_schedule([(1, 4096)] * 64, 2048, 0, 1e-3), m.can_schedule([(1, 4096)] * 64, 2048, 32768, 1e-3)]}
     log("  latency model over %d batches: k_token %.3e s, k2 %.3e s/pair, k4 %.3e s/token, k5 %.3e s; "
-        "relative error mean %.1f%% max %.1f%%" % (len(samples), m.k_p, m.k2, m.k4, m.k5, 100 * rel.mean(), 100 * rel.max()))
+        "relative error mean %.1f%% max %.1f%% (batches of 150 us and more: mean %.1f%% max %.1f%%)"
+        % (len(samples), m.k_p, m.k2, m.k4, m.k5, 100 * rel.mean(), 100 * rel.max(), 100 * rel[big].mean(), 100 * rel[big].max()))
     for (batch, t), e in zip(samples, rel):
         log("    %-34s %9.1f us  err %5.1f%%" % ("%d req, P=%d, C<=%d" % (len(batch), sum(p for p, _ in batch), max(c for _, c in batch)), t * 1e6, 100 * e))
     return r

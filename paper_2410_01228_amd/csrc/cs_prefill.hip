@@ -108,21 +108,18 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     p.max_ranges = 1;
     if (tiles == 0) return p;
     const int64_t wgs = tiles * Hkv;
-    // Tiles that would leave CUs without any workgroup (a small chunk on a long context: few
-    // tiles, each walking thousands of keys) are cut along the keys: aim at about four
-    // workgroups per CU with ranges of at least 32 steps (1024 keys), at most 8 per tile.
-    if (wgs < 256) {
-        int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 1023) / 1024);
-        rs = std::max<int64_t>(rs, (max_steps + 7) / 8);
+    if (wgs <= 192 && max_steps < 128) {
+        // few and short tiles: about four workgroups per CU, ranges of at least 32 steps
+        const int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 1023) / 1024);
         if (rs < max_steps) {
             p.range_steps = (int32_t)rs;
             p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
         }
     } else if (wgs <= 1024) {
-        // Between one and four workgroups per CU the grid runs as one or two rounds over the 512
-        // workgroup slots, and a round that is not full costs almost as much as a full one.
-        // Cutting every tile into r key ranges multiplies the workgroups and divides their
-        // length: pick the r whose rounds come out fullest.  The cost model is fitted to
+        // Up to four workgroups per CU the grid runs as one or two rounds over the 512 workgroup
+        // slots (or leaves CUs empty), and a round that is not full costs almost as much as a
+        // full one.  Cutting every tile into r key ranges multiplies the workgroups and divides
+        // their length: pick the r whose rounds come out fullest.  The cost model is fitted to
         // measurements (it reproduces them within a few percent), in steps of a workgroup that
         // shares its CU: a workgroup with the CU to itself runs a step in 0.76 of that; while all
         // workgroups are resident the longest tile decides, beyond that the average tile and a
@@ -144,8 +141,8 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
         };
         int best = 1;
         double best_cost = cost(1);
-        for (int r = 2; r <= 8; ++r) {
-            if (max_steps / r < 64) break;
+        for (int r = 2; r <= 16; ++r) {
+            if (max_steps / r < 32) break;
             const double c = cost(r);
             if (c < best_cost) { best = r; best_cost = c; }
         }
