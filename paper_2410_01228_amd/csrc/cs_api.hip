@@ -208,9 +208,12 @@ static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
-    if (plan.num_prefill > 0 && plan.num_decode > 0 && plan.in_args && pplan.max_ranges == 1 && g_fuse_mixed.load()) {
-        // both kinds of work in one grid
-        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, st, f16);
+    if (plan.num_prefill > 0 && plan.num_decode > 0 && plan.in_args && g_fuse_mixed.load()) {
+        // both kinds of work in one grid, then the merges of whatever was cut
+        void* prefill_ws = (char*)workspace + decode_bytes;
+        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, prefill_ws, st, f16);
+        if (rc) return rc;
+        rc = launch_prefill_merge(*pool, *batch, pplan, out, Hq, prefill_ws, st, f16);
         if (rc) return rc;
         return launch_decode(*pool, layer, *batch, plan, q, out, Hq, softmax_scale, workspace, st, f16, true);
     }

@@ -90,13 +90,17 @@ struct PrefillPlan {
 PrefillPlan plan_prefill(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
 int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
                    const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16);
+// The merge of the key-range partials alone (what launch_prefill ends with when tiles are cut).
+int launch_prefill_merge(const cs_kv_pool& pool, const cs_batch& b, const PrefillPlan& plan, void* out, int32_t Hq,
+                         void* workspace, hipStream_t st, bool f16);
 // One launch for a batch that holds both chunks and decode tokens: the prefill workgroups
 // first, the decode items (longest first) behind them, so that decode work fills the slots the
 // uneven prefill tiles leave empty instead of waiting for the last of them.  Needs the item
-// list in the kernel arguments (dplan.in_args) and uncut prefill tiles (pplan.max_ranges == 1);
-// the caller merges the cut decode sequences afterwards (launch_decode with merge_only).
+// list in the kernel arguments (dplan.in_args).  Tiles cut into key ranges bring one workgroup
+// per range; the caller merges their partials (launch_prefill_merge) and the cut decode
+// sequences (launch_decode with merge_only) afterwards.
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                 void* decode_workspace_base, hipStream_t st, bool f16);
+                 void* decode_workspace_base, void* prefill_workspace, hipStream_t st, bool f16);
 
 }  // namespace cs

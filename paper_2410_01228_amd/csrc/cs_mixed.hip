@@ -26,15 +26,19 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
-    int32_t range_steps, uint32_t num_prefill_wgs, const ItemsInArgs items,
+    int32_t range_steps, int32_t base_slot, int32_t max_ranges, float* __restrict__ prefill_part,
+    uint32_t wgs_per_range, uint32_t num_prefill_wgs, const ItemsInArgs items,
     float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     __shared__ MixedLds<D> lds;
     if (blockIdx.x < num_prefill_wgs) {
-        const int32_t b = blockIdx.x / Hkv;
-        const int32_t g = blockIdx.x - b * Hkv;
+        // range-major, like the prefill kernel's own grid: all tiles of key range 0, then range 1, ...
+        const uint32_t range = blockIdx.x / wgs_per_range, rem = blockIdx.x - range * wgs_per_range;
+        const int32_t b = rem / Hkv;
+        const int32_t g = rem - b * Hkv;
         prefill_tile<D, E, false>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
-                           ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, 0, nullptr, g, b, 0, 1);
+                           ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, base_slot, prefill_part, g, b,
+                           (int32_t)range, max_ranges);
     } else {
         const uint32_t w = blockIdx.x - num_prefill_wgs;
         const int32_t item = w / Hkv, g = w - item * Hkv;
@@ -46,13 +50,14 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
 template <class E>
 static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                            const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                           void* decode_ws, hipStream_t st)
+                           void* decode_ws, void* prefill_ws, hipStream_t st)
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     const float scale_log2e = scale * 1.4426950408889634f;
     const int64_t slots = prefill_slot_start(b.num_tokens, b.num_seqs, G);
-    const int64_t n_prefill = slots * Hkv, n_decode = (int64_t)dplan.total_items * Hkv;
+    const int64_t per_range = slots * Hkv;
+    const int64_t n_prefill = per_range * pplan.max_ranges, n_decode = (int64_t)dplan.total_items * Hkv;
     if (n_prefill + n_decode > 2147483647ll) return CS_ERR_UNSUPPORTED;
     const DecodeWorkspace w = decode_workspace(dplan, b.num_seqs, Hq, D);
     float* part_ml = (float*)((char*)decode_ws + w.part_ml);
@@ -62,21 +67,23 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
         hipLaunchKernelGGL((mixed_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
                            b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,
+                           pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,
                            (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
     else
         hipLaunchKernelGGL((mixed_kernel<64, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
                            b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,
+                           pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,
                            (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
     return check_launch("mixed kernel");
 }
 
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                 void* decode_ws, hipStream_t st, bool f16)
+                 void* decode_ws, void* prefill_ws, hipStream_t st, bool f16)
 {
-    return f16 ? launch_mixed_as<F16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, st)
-               : launch_mixed_as<Bf16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, st);
+    return f16 ? launch_mixed_as<F16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st)
+               : launch_mixed_as<Bf16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st);
 }
 
 }  // namespace cs

@@ -160,6 +160,23 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
 }
 
 template <class E>
+static void launch_merge_as(const cs_kv_pool& pool, const cs_batch& b, const PrefillPlan& plan, void* out, int32_t Hq,
+                            void* workspace, hipStream_t st)
+{
+    const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
+    const float* part = (const float*)workspace;
+    dim3 mgrid((uint32_t)Hkv * (uint32_t)plan.num_slots);
+    if (D == 128)
+        hipLaunchKernelGGL((prefill_merge_kernel<128, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
+                           b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
+                           plan.base_slot, part);
+    else
+        hipLaunchKernelGGL((prefill_merge_kernel<64, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
+                           b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
+                           plan.base_slot, part);
+}
+
+template <class E>
 static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
                              const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st)
 {
@@ -181,18 +198,17 @@ static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_bat
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
                            b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
                            plan.range_steps, plan.base_slot, part);
-    if (plan.max_ranges > 1) {
-        dim3 mgrid((uint32_t)Hkv * (uint32_t)plan.num_slots);
-        if (D == 128)
-            hipLaunchKernelGGL((prefill_merge_kernel<128, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
-                               b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
-                               plan.base_slot, part);
-        else
-            hipLaunchKernelGGL((prefill_merge_kernel<64, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
-                               b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
-                               plan.base_slot, part);
-    }
+    if (plan.max_ranges > 1) launch_merge_as<E>(pool, b, plan, out, Hq, workspace, st);
     return check_launch("prefill kernels");
+}
+
+int launch_prefill_merge(const cs_kv_pool& pool, const cs_batch& b, const PrefillPlan& plan, void* out, int32_t Hq,
+                         void* workspace, hipStream_t st, bool f16)
+{
+    if (plan.max_ranges <= 1) return CS_OK;
+    if (f16) launch_merge_as<F16>(pool, b, plan, out, Hq, workspace, st);
+    else launch_merge_as<Bf16>(pool, b, plan, out, Hq, workspace, st);
+    return check_launch("prefill merge kernel");
 }
 
 int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const PrefillPlan& plan,
