@@ -130,6 +130,7 @@ def test_very_long_contexts():
     (28, 4, [16384], [1280]),                # 280: cut in three, two rounds
     (32, 8, [12000, 17000], [1280, 1280]),   # 640 over two sequences of different length
     (64, 8, [33000], [1536]),                # 768: cut in two
+    (32, 8, [100, 30000, 500, 60000], [512] * 4),   # 512 of very unequal length: only the long tiles are cut
 ])
 def test_chunks_between_one_and_four_workgroups_per_cu_are_cut_into_key_ranges(Hq, Hkv, ctx, ql):
     """A grid of 256..1024 tile workgroups runs as one or two rounds over the workgroup slots;
