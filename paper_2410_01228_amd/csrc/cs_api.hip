@@ -81,7 +81,11 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         const int32_t cap = head_dim >= 128 ? 4096 : 8192;
         const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
         const int64_t need = uniform ? 512 : 1024;
-        for (split = cap; split > 256; split /= 2) {
+        // no sequence is cut into more than about 16 pieces: beyond that the partials, their merge
+        // and the start-up of ever shorter items cost more than the fuller grid gains
+        int32_t floor_split = 256;
+        while (floor_split < cap && (int64_t)floor_split * 16 < max_keys) floor_split *= 2;
+        for (split = cap; split > floor_split; split /= 2) {
             int64_t items = 0;
             for (int32_t s = 0; s < b->num_seqs; ++s)
                 if (b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s] == 1)
