@@ -582,7 +582,7 @@ def main():
     cs.lib()                                   # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
     cs.cs_set_decode_split_tokens(args.split_tokens)
-    cs.cs_set_mixed_fusion(not args.separate_launches)
+    cs.cs_set_mixed_fusion(0 if args.separate_launches else 1)
     if args.calibration_copy_gib > 0:
         n = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
         src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)

@@ -417,8 +417,9 @@ def cs_set_decode_pages_ahead(pages: int):
     lib().cs_set_decode_pages_ahead(int(pages))
 
 
-def cs_set_mixed_fusion(on: bool):
-    lib().cs_set_mixed_fusion(1 if on else 0)
+def cs_set_mixed_fusion(mode):
+    """True / 1: fuse when it pays (default); 2: fuse whenever the plan allows; False / 0: never."""
+    lib().cs_set_mixed_fusion(int(mode))
 
 
 def cs_set_decode_split_tokens(tokens: int):

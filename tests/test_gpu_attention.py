@@ -10,7 +10,7 @@ from helpers import Step, assert_attention_close, bits, from_bits
 pytestmark = pytest.mark.gpu
 
 
-def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16, fuse=True, ahead=0):
+def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bfloat16, fuse=1, ahead=0):
     """append + attention through the C ABI; returns (gpu_out, Step, device pool, cs.Batch)."""
     st = Step(batch, seed, q_gain=q_gain, dtype=dtype)
     sh = batch.shape
@@ -32,7 +32,7 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bf
         torch.cuda.synchronize()
     finally:
         cs.cs_set_decode_split_tokens(0)
-        cs.cs_set_mixed_fusion(True)
+        cs.cs_set_mixed_fusion(1)
         cs.cs_set_decode_pages_ahead(0)
     return out, st, pool, bb
 
@@ -288,7 +288,7 @@ def test_random_mixed_batches(seed):
     split = rnd.choice([0, 0, 64, 256])
     gain = rnd.choice([1.0, 1.0, 4.0])
     dtype = rnd.choice([torch.bfloat16, torch.bfloat16, torch.float16])
-    fuse = rnd.choice([True, True, False])                 # one fused grid, or two kernels in a row
+    fuse = rnd.choice([2, 1, 0])                           # one fused grid always / when it pays / two kernels in a row
     ahead = rnd.choice([0, 1, 2])                           # decode prefetch depth: automatic, one, two pages
     out, st, _, _ = run_step(b, 2000 + seed, q_gain=gain, split=split, dtype=dtype, fuse=fuse, ahead=ahead)
     active = [s for s in range(S) if ql[s] > 0]
@@ -306,8 +306,8 @@ def test_fused_and_separate_launches_agree(Hq, Hkv, D, split, dtype):
     ctx = [700, 33, 0, 1500, 260, 15, 2047, 90, 5, 311]
     ql = [1, 100, 17, 1, 1, 48, 1, 0, 1, 2]
     b = synth.make_batch(sh, ctx, ql, synth.generator(77), spare=3)
-    o1, st, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=True)
-    o2, _, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=False)
+    o1, st, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=2)
+    o2, _, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=0)
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
     active = [s for s in range(len(ql)) if ql[s] > 0]
     check = assert_attention_close if dtype == torch.bfloat16 else assert_close_f16
