@@ -313,8 +313,8 @@ int32_t cs_debug_decode_pages_ahead(const cs_batch* batch, int32_t num_kv_heads,
 void cs_set_decode_pages_ahead(int32_t pages);
 
 /* Tuning knob for measurements and tests: 1 (default) lets a call that holds both prefill
- * chunks and decode tokens run them as one fused launch when its plan allows and neither side
- * is a sliver of the other; 2 fuses whenever the plan allows; 0 always launches the prefill
+ * chunks and decode tokens run them as one fused launch when its plan allows and the chunks are
+ * not a sliver beside the decode work; 2 fuses whenever the plan allows; 0 always launches the prefill
  * kernel and the decode kernel one after the other.  Process-wide. */
 void cs_set_mixed_fusion(int32_t mode);
 

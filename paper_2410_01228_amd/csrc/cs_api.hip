@@ -212,15 +212,16 @@ static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
-    // One grid pays when both kinds of work are there in earnest.  With a sliver of decode work
-    // beside long chunks the prefill kernel alone is faster (its wavefronts alternate their issue
-    // priority, which the fused grid does not), with a sliver of prefill beside a long decode the
-    // two kernels in a row are as fast: fuse when the decode side's ideal time (bytes at 6 TB/s)
-    // is between 0.08 and 10 times the prefill side's (flops at 1 PFLOP/s).  Measured over 60
-    // mixes of three model shapes: up to 18% for the fused grid inside that band, 3-7% against
-    // it outside.
+    // One grid for both kinds of work, unless the prefill side is a sliver: with a small chunk
+    // beside a long decode (ideal decode time, bytes at 6 TB/s, over ten times the ideal prefill
+    // time, flops at 1 PFLOP/s) two kernels in a row are as fast or a little faster.  Where the
+    // decode side is the smaller one (under 0.3 of the prefill time) the tiles of the fused grid
+    // alternate their issue priority as the prefill kernel's do; beside a decode load of equal
+    // weight that costs more than it gains.  Measured over 110 mixes of three model shapes: the
+    // fused grid is 1-18% faster than two kernels wherever this rule takes it.
     bool fuse = plan.num_prefill > 0 && plan.num_decode > 0 && plan.in_args && g_fuse_mixed.load() != 0;
-    if (fuse && g_fuse_mixed.load() == 1) {
+    bool prio = false;
+    if (fuse) {
         double pairs = 0;
         for (int32_t s = 0; s < batch->num_seqs; ++s) {
             const double ql = batch->h_cu_q_lens[s + 1] - batch->h_cu_q_lens[s];
@@ -228,12 +229,13 @@ static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch
         }
         const double t_prefill = 4.0 * Hq * pool->head_dim * pairs / 1.0e15;
         const double t_decode = (double)plan.decode_keys * 2 * pool->num_kv_heads * pool->head_dim * 2 / 6.0e12;
-        fuse = t_decode >= 0.08 * t_prefill && t_decode <= 10.0 * t_prefill;
+        prio = t_decode < 0.3 * t_prefill;
+        if (g_fuse_mixed.load() == 1) fuse = t_decode <= 10.0 * t_prefill;
     }
     if (fuse) {
         // both kinds of work in one grid, then the merges of whatever was cut
         void* prefill_ws = (char*)workspace + decode_bytes;
-        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, prefill_ws, st, f16);
+        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, prefill_ws, st, f16, prio);
         if (rc) return rc;
         rc = launch_prefill_merge(*pool, *batch, pplan, out, Hq, prefill_ws, st, f16);
         if (rc) return rc;

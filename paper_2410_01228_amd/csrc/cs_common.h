@@ -101,6 +101,7 @@ int launch_prefill_merge(const cs_kv_pool& pool, const cs_batch& b, const Prefil
 // sequences (launch_decode with merge_only) afterwards.
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                 void* decode_workspace_base, void* prefill_workspace, hipStream_t st, bool f16);
+                 void* decode_workspace_base, void* prefill_workspace, hipStream_t st, bool f16,
+                 bool phase_priority);
 
 }  // namespace cs

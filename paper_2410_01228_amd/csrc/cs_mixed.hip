@@ -5,7 +5,8 @@
 // missing prefill tile leaves free -- two kernels in a row would leave those slots idle until
 // the longest tile is done.  Both kinds of workgroup have 4 wavefronts and share one LDS
 // allocation (a union of the two layouts), so two of them fit a CU in any combination; the
-// decode items take the deeper page prefetch, whose registers cost nothing here.
+// decode items take the deeper page prefetch, whose registers cost nothing here.  kPhasePriority
+// (see prefill_tile) is set by the host when the decode side is the small one.
 #include "cs_prefill_impl.h"
 #include "cs_decode_impl.h"
 
@@ -19,7 +20,7 @@ union MixedLds {
     DecodeLds<D> decode;
 };
 
-template <int D, class E>
+template <int D, class E, bool kPhasePriority>
 __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G, int32_t S,
@@ -36,7 +37,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
         const uint32_t range = blockIdx.x / wgs_per_range, rem = blockIdx.x - range * wgs_per_range;
         const int32_t b = rem / Hkv;
         const int32_t g = rem - b * Hkv;
-        prefill_tile<D, E, false>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
+        prefill_tile<D, E, kPhasePriority>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
                            ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, base_slot, prefill_part, g, b,
                            (int32_t)range, max_ranges);
     } else {
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
 template <class E>
 static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                            const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                           void* decode_ws, void* prefill_ws, hipStream_t st)
+                           void* decode_ws, void* prefill_ws, hipStream_t st, bool prio)
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
@@ -63,27 +64,24 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
     float* part_ml = (float*)((char*)decode_ws + w.part_ml);
     float* part_o = (float*)((char*)decode_ws + w.part_o);
     dim3 grid((uint32_t)(n_prefill + n_decode));
-    if (D == 128)
-        hipLaunchKernelGGL((mixed_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
-                           pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
-                           b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,
-                           pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,
-                           (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
-    else
-        hipLaunchKernelGGL((mixed_kernel<64, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
-                           pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
-                           b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,
-                           pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,
-                           (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
+#define CS_LAUNCH_MIXED(DD, PRIO)                                                                            \
+    hipLaunchKernelGGL((mixed_kernel<DD, E, PRIO>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride, \
+                       pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,    \
+                       b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,         \
+                       pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,              \
+                       (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
+    if (D == 128) { if (prio) { CS_LAUNCH_MIXED(128, true) } else { CS_LAUNCH_MIXED(128, false) } }
+    else          { if (prio) { CS_LAUNCH_MIXED(64, true) } else { CS_LAUNCH_MIXED(64, false) } }
+#undef CS_LAUNCH_MIXED
     return check_launch("mixed kernel");
 }
 
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                 void* decode_ws, void* prefill_ws, hipStream_t st, bool f16)
+                 void* decode_ws, void* prefill_ws, hipStream_t st, bool f16, bool prio)
 {
-    return f16 ? launch_mixed_as<F16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st)
-               : launch_mixed_as<Bf16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st);
+    return f16 ? launch_mixed_as<F16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st, prio)
+               : launch_mixed_as<Bf16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st, prio);
 }
 
 }  // namespace cs

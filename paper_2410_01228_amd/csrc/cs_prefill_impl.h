@@ -108,8 +108,8 @@ struct PrefillLds {
 // The work of one prefill workgroup: the tile in slot b, kv head g, key range `range` of
 // `n_ranges_grid` (a tile whose keys need more than range_steps steps is cut into ranges, each
 // leaving a partial).  `lds` is the workgroup's own.  kPhasePriority: the wavefront alternates
-// its issue priority between the halves of an iteration (for a grid of tiles only; beside
-// decode workgroups it gains nothing and the whole call comes out slower).
+// its issue priority between the halves of an iteration (for grids whose other wavefronts are
+// mostly tiles too; beside a decode load of equal weight it costs more than it gains).
 template <int D, class E, bool kPhasePriority>
 __device__ __forceinline__ void prefill_tile(
     PrefillLds<D>& lds,
