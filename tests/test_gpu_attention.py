@@ -314,6 +314,22 @@ def test_fused_and_separate_launches_agree(Hq, Hkv, D, split, dtype):
     check(o1, st.oracle_attention(active), "fused %d/%d/%d split %d" % (Hq, Hkv, D, split))
 
 
+@pytest.mark.parametrize("Hq,Hkv,D,dtype", [(8, 2, 128, torch.bfloat16), (28, 4, 128, torch.bfloat16), (4, 2, 64, torch.float16)])
+def test_fused_grid_with_a_sliver_of_decode_work(Hq, Hkv, D, dtype):
+    """Prefill-heavy mix: the host takes the fused kernel whose tiles alternate their issue
+    priority (decode side under 0.3 of the prefill side's ideal time).  Priorities change no
+    arithmetic: bit-identical to the separate launches, and both meet the oracle."""
+    sh = synth.Shape(Hq, Hkv, D)
+    ctx = [40, 900, 0, 17, 2000]
+    ql = [1, 300, 130, 1, 260]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(78), spare=2)
+    o1, st, _, _ = run_step(b, 78, dtype=dtype, fuse=1)
+    o2, _, _, _ = run_step(b, 78, dtype=dtype, fuse=0)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    check = assert_attention_close if dtype == torch.bfloat16 else assert_close_f16
+    check(o1, st.oracle_attention(), "prefill-heavy fused %d/%d/%d" % (Hq, Hkv, D))
+
+
 def test_prefill_many_short_chunks():
     """More workgroup slots than one grid dimension holds (60 000 sequences: two-token chunks and
     decode tokens interleaved): the slot index rides in grid.x together with the kv head."""
