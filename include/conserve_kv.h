@@ -98,8 +98,11 @@ size_t cs_page_bytes(int32_t num_kv_heads, int32_t head_dim);
 int cs_kv_append(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
                  const void* k_new, const void* v_new, void* stream);
 
-/* Workspace the attention call needs for this batch (split partials of the decode path).
- * Depends only on the host arrays of `batch` and the shape.  Returns 0 on bad arguments. */
+/* Workspace the attention call needs for this batch: the fp32 partial results of decode
+ * sequences cut into work items and of prefill tiles cut into key ranges (the launch plan is
+ * made here from the host arrays of `batch` and the shape, and again, identically, in the
+ * attention call).  Zero for many batches; a few MB to a few hundred MB when chunks of up to a
+ * few thousand tokens are cut to fill the chip.  Returns 0 on bad arguments. */
 size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t num_q_heads,
                                           int32_t num_kv_heads, int32_t head_dim);
 
