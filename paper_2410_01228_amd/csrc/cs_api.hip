@@ -76,11 +76,11 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         // Few, long work items stream best: each pays its start-up latencies once, and when no
         // sequence is cut the plan and merge kernels are not launched at all.  Start from items
         // of about 2 MiB of K/V per kv head and halve only until the grid has enough workgroups:
-        // four per CU, or two per CU when the sequences are of nearly equal length (then the
+        // three per CU, or two per CU when the sequences are of nearly equal length (then the
         // items are too, and nothing straggles).
         const int32_t cap = head_dim >= 128 ? 4096 : 8192;
         const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
-        const int64_t need = uniform ? 512 : 1024;
+        const int64_t need = uniform ? 512 : 768;
         // no sequence is cut into more than about 16 pieces: beyond that the partials, their merge
         // and the start-up of ever shorter items cost more than the fuller grid gains
         int32_t floor_split = 256;
