@@ -154,6 +154,38 @@ def test_chunks_between_one_and_four_workgroups_per_cu_are_cut_into_key_ranges(H
     run_batch(b, 91, list(range(len(ctx) + 2)), rows_per_chunk=4)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_batches_at_model_shapes(seed):
+    """Seeded random mixes at the four model shapes and at sizes where the launch planning
+    matters (chunks of up to 2048 tokens on contexts of up to 40 000 keys, decodes of up to
+    20 000): whatever the host decides -- work items, prefetch depth, key ranges, fused grid or
+    not -- sampled rows must meet the oracle and the appended pages be exact."""
+    import random
+    rnd = random.Random(9000 + seed)
+    Hq, Hkv = rnd.choice([(32, 8), (28, 4), (64, 8), (40, 8)])
+    sh = synth.Shape(Hq, Hkv, 128)
+    n_dec = rnd.choice([0, 0, 3, 17, 70])
+    n_ch = rnd.choice([1, 1, 2, 4, 7])
+    ctx = [rnd.choice([rnd.randint(0, 3000), rnd.randint(0, 20000)]) for _ in range(n_dec)]
+    ql = [1] * n_dec
+    for _ in range(n_ch):
+        ctx.append(rnd.choice([0, rnd.randint(0, 4000), rnd.randint(0, 40000)]))
+        ql.append(rnd.choice([rnd.randint(2, 400), rnd.randint(200, 1500), rnd.choice([256, 512, 1024, 1280, 2048])]))
+    order = list(range(len(ctx)))
+    rnd.shuffle(order)
+    ctx, ql = [ctx[i] for i in order], [ql[i] for i in order]
+    mode, ahead = rnd.choice([1, 1, 2, 0]), rnd.choice([0, 0, 1, 2])
+    cs.cs_set_mixed_fusion(mode)
+    cs.cs_set_decode_pages_ahead(ahead)
+    try:
+        b = synth.make_batch(sh, ctx, ql, synth.generator(9500 + seed))
+        sample = list(range(len(ctx))) if len(ctx) <= 8 else rnd.sample(range(len(ctx)), 8)
+        run_batch(b, 9500 + seed, sample, rows_per_chunk=3)
+    finally:
+        cs.cs_set_mixed_fusion(1)
+        cs.cs_set_decode_pages_ahead(0)
+
+
 def test_qwen14b_ckpt_full_size():
     """Workload 4 at its stated page counts on a subset of layers: gather all dirty pages of 3
     of the 48 layers (the kernels index layers independently), restore into the spare pages,
