@@ -119,6 +119,8 @@ def lib():
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
         L.cs_set_decode_pages_ahead.restype, L.cs_set_decode_pages_ahead.argtypes = None, [i32]
+        L.cs_debug_prefill_order.restype = ctypes.c_int32
+        L.cs_debug_prefill_order.argtypes = [BP, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32]
         L.cs_debug_decode_pages_ahead.restype, L.cs_debug_decode_pages_ahead.argtypes = ctypes.c_int32, [BP, i32, i32]
         L.cs_debug_decode_items.restype = ctypes.c_int32
         L.cs_debug_decode_items.argtypes = [BP, i32, i32, ctypes.POINTER(ctypes.c_uint32), i32, ctypes.POINTER(ctypes.c_int32)]
@@ -134,7 +136,7 @@ EXPORTS = [
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
-    "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead",
+    "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
     "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_status_string", "cs_last_hip_error",
 ]
 

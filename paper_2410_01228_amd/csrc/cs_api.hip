@@ -455,6 +455,16 @@ int32_t cs_debug_decode_pages_ahead(const cs_batch* batch, int32_t Hkv, int32_t 
     return plan_decode(batch, Hkv, D).pages_ahead;
 }
 
+int32_t cs_debug_prefill_order(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D, int32_t* slots, int32_t capacity) {
+    if (attention_shape_ok(Hq, Hkv, D) != CS_OK || validate_batch(nullptr, batch) != CS_OK || capacity < 0 ||
+        (capacity > 0 && !slots))
+        return CS_ERR_INVALID_ARG;
+    if (batch->num_seqs == 0) return 0;
+    const PrefillPlan p = plan_prefill(batch, Hq, Hkv, D);
+    for (int32_t i = 0; i < p.n_ordered && i < capacity; ++i) slots[i] = p.order.slot[i];
+    return p.n_ordered;
+}
+
 void cs_set_decode_pages_ahead(int32_t pages) {
     g_forced_ahead.store(pages == 1 || pages == 2 ? pages : 0);
 }

@@ -80,7 +80,12 @@ int launch_decode(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, cons
                   const void* q, void* out, int32_t Hq, float scale, void* workspace, hipStream_t st, bool f16,
                   bool merge_only = false);
 // Key-range split of the prefill path (pure function of the host lengths).
+// Slot each grid position takes when the host reorders the tiles (see plan_prefill).
+constexpr int kMaxSlotOrder = 512;
+struct SlotOrder { uint16_t slot[kMaxSlotOrder]; };
 struct PrefillPlan {
+    int32_t n_ordered;         // > 0: the grid has n_ordered slot positions, position p takes slot order.slot[p]
+    SlotOrder order;
     int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
     int32_t max_ranges;        // grid depth: ranges of the longest tile
     int32_t base_slot;         // first workgroup slot that can belong to a prefill sequence

@@ -239,6 +239,44 @@ def test_prefill_key_range_plan_follows_the_rounds():
     assert ranges(32, 8, 4608, 65536) == 0               # beyond 1024: rounds blur, never cut
 
 
+def test_prefill_tile_order_gives_the_longest_tiles_a_cu_of_their_own():
+    """Four 320-token chunks of very different context at the Qwen-14B shape: 52 tiles per kv
+    head on 32 first-round positions.  The order must be a permutation of the tiles, the 12
+    positions that keep a CU to themselves must hold the 12 longest, and each shared CU a long
+    tile (first round) and a short one (second round) -- the longest of the rest with the
+    shortest."""
+    lib = cs.lib()
+    Hq, Hkv, G = 40, 8, 5
+    ctx, ql = [2048, 1000, 3000, 500], [320] * 4
+    b, keep = _batch(ctx, ql, max_blocks=1 << 12)
+    buf = (ctypes.c_int32 * 512)()
+    n = lib.cs_debug_prefill_order(ctypes.byref(b), Hq, Hkv, 128, buf, 512)
+    order = list(buf[:n])
+    # the tiles and their lengths, as the kernel numbers them: slot start of sequence s is (cu*G/128 + s) ...
+    steps = {}
+    cu = 0
+    for s, (c, q) in enumerate(zip(ctx, ql)):
+        start = (cu + 16 * s) * G // 128 + s
+        n_ct = (q + 15) // 16 * G
+        for j, ct0 in enumerate(range(0, n_ct, 8)):
+            tb_max = (min(ct0 + 8, n_ct) - 1) // G
+            steps[start + j] = (c + min(q, (tb_max + 1) * 16) + 31) // 32
+        cu += q
+    assert n == len(steps) == 52 and sorted(order) == sorted(steps)
+    first_round = 256 // Hkv
+    n_pair = n - first_round
+    assert n_pair == 20
+    solo = [steps[t] for t in order[n_pair:first_round]]
+    rest = sorted((steps[t] for t in order[:n_pair] + order[first_round:]), reverse=True)
+    assert min(solo) >= rest[0]
+    for k in range(n_pair):
+        assert steps[order[k]] == rest[k] and steps[order[first_round + k]] == rest[2 * n_pair - 1 - k]
+    # natural order where the rule does not apply: a full round, tiles cut into ranges, one per CU or fewer
+    for ctx2, ql2 in (([2048] * 4, [512] * 4), ([30000], [1024]), ([100], [256])):
+        b2, keep2 = _batch(ctx2, ql2, max_blocks=1 << 12)
+        assert lib.cs_debug_prefill_order(ctypes.byref(b2), 32, 8, 128, buf, 512) == 0
+
+
 def test_debug_copy_argument_checks():
     lib = cs.lib()
     assert lib.cs_debug_copy(0x1000, 0x2000, 24, None) == cs.CS_ERR_INVALID_ARG          # not a multiple of 16

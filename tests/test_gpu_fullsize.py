@@ -154,6 +154,25 @@ def test_chunks_between_one_and_four_workgroups_per_cu_are_cut_into_key_ranges(H
     run_batch(b, 91, list(range(len(ctx) + 2)), rows_per_chunk=4)
 
 
+@pytest.mark.parametrize("Hq,Hkv,ctx,ql", [
+    (40, 8, [2048, 1000, 3000, 500], [320] * 4),      # 416 tile workgroups of four lengths
+    (32, 8, [6000], [1536]),                          # 384: one chunk, causal lengths
+    (28, 4, [200, 800, 1400, 2000], [448] * 4),       # 392, four kv heads
+])
+def test_prefill_grids_dealt_to_cus_by_tile_length(Hq, Hkv, ctx, ql):
+    """Between one and two tile workgroups per CU the host permutes the tiles over the grid
+    positions (longest alone on a CU, the rest paired long with short).  The plan must really
+    be a permutation, and every chunk must still meet the oracle."""
+    sh = synth.Shape(Hq, Hkv, 128)
+    b = synth.make_batch(sh, ctx, ql, synth.generator(93))
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    import ctypes
+    buf = (ctypes.c_int32 * 512)()
+    n = cs.lib().cs_debug_prefill_order(ctypes.byref(bb.c), sh.Hq, sh.Hkv, sh.D, buf, 512)
+    assert 256 // Hkv < n < 512 // Hkv and len(set(buf[:n])) == n
+    run_batch(b, 93, list(range(len(ctx))), rows_per_chunk=6)
+
+
 @pytest.mark.parametrize("seed", range(16))
 def test_random_batches_at_model_shapes(seed):
     """Seeded random mixes at the four model shapes and at sizes where the launch planning
