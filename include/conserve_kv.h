@@ -305,14 +305,15 @@ int32_t cs_debug_decode_items(const cs_batch* batch, int32_t num_kv_heads, int32
  * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */
 void cs_set_decode_split_tokens(int32_t tokens);
 
-/* Host-only view of the prefill path's tile order, for tests.  When the uncut tiles of a batch
- * are all resident at once with more than one but fewer than two workgroups per CU, the host
- * deals them to grid positions so that the longest tiles get a CU to themselves and the others
- * share one long with short (the dispatcher gives the first 256 workgroups a CU each and
- * workgroup i + 256 the CU of workgroup i).  Writes the tile slot of every slot position
+/* Host-only view of the prefill path's tile order, for tests.  The host deals uncut tiles to
+ * grid positions for the dispatcher (which gives the first 256 workgroups a CU each and
+ * workgroup i + 256 the CU of workgroup i): between one and two workgroups per CU the longest
+ * tiles get a CU to themselves and the others share one long with short; with more tiles than
+ * workgroup slots the longest go first.  Writes the tile slot of every slot position
  * (min(n, capacity) entries; a slot is 8 column tiles of 16 query rows of one kv head group,
- * numbered as the prefill kernel numbers them) and returns n, 0 when the order is the natural
- * one, CS_ERR_INVALID_ARG on bad arguments.  No device work. */
+ * numbered as the prefill kernel numbers them) and returns n; 0 when the order is the natural
+ * one or (beyond 512 tiles) simply reversed; CS_ERR_INVALID_ARG on bad arguments.  No device
+ * work. */
 int32_t cs_debug_prefill_order(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
                                int32_t* slots, int32_t capacity);
 

@@ -86,6 +86,7 @@ struct SlotOrder { uint16_t slot[kMaxSlotOrder]; };
 struct PrefillPlan {
     int32_t n_ordered;         // > 0: the grid has n_ordered slot positions, position p takes slot order.slot[p]
     SlotOrder order;
+    bool    backwards;         // where no table is used: grid position p takes slot (slots - 1 - p)
     int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
     int32_t max_ranges;        // grid depth: ranges of the longest tile
     int32_t base_slot;         // first workgroup slot that can belong to a prefill sequence

@@ -28,15 +28,16 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
     int32_t range_steps, int32_t base_slot, int32_t max_ranges, float* __restrict__ prefill_part,
-    uint32_t wgs_per_range, uint32_t num_prefill_wgs, const ItemsInArgs items,
+    uint32_t wgs_per_range, uint32_t num_prefill_wgs, int32_t backwards, const ItemsInArgs items,
     float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     __shared__ MixedLds<D> lds;
     if (blockIdx.x < num_prefill_wgs) {
         // range-major, like the prefill kernel's own grid: all tiles of key range 0, then range 1, ...
         const uint32_t range = blockIdx.x / wgs_per_range, rem = blockIdx.x - range * wgs_per_range;
-        const int32_t b = rem / Hkv;
-        const int32_t g = rem - b * Hkv;
+        const int32_t pos = rem / Hkv;
+        const int32_t g = rem - pos * Hkv;
+        const int32_t b = backwards ? (int32_t)(wgs_per_range / Hkv) - 1 - pos : pos;   // longest tiles first
         prefill_tile<D, E, kPhasePriority>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
                            ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, base_slot, prefill_part, g, b,
                            (int32_t)range, max_ranges);
@@ -69,7 +70,7 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
                        pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,    \
                        b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,         \
                        pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,              \
-                       (uint32_t)n_prefill, dplan.arg_items, part_o, part_ml);
+                       (uint32_t)n_prefill, (int32_t)pplan.backwards, dplan.arg_items, part_o, part_ml);
     if (D == 128) { if (prio) { CS_LAUNCH_MIXED(128, true) } else { CS_LAUNCH_MIXED(128, false) } }
     else          { if (prio) { CS_LAUNCH_MIXED(64, true) } else { CS_LAUNCH_MIXED(64, false) } }
 #undef CS_LAUNCH_MIXED

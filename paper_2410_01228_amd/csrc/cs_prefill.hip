@@ -13,12 +13,13 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
-    int32_t range_steps, int32_t base_slot, float* __restrict__ part, int32_t n_ordered, const SlotOrder order)
+    int32_t range_steps, int32_t base_slot, float* __restrict__ part, int32_t n_ordered, const SlotOrder order,
+    int32_t backwards)
 {
     __shared__ PrefillLds<D> lds;
     const int32_t pos = blockIdx.x / Hkv;
     const int32_t g = blockIdx.x - pos * Hkv;
-    const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos] : pos;
+    const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos] : backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos;
     prefill_tile<D, E, true>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
                        q, out, scale_log2e, range_steps, base_slot, part, g, b, blockIdx.y, gridDim.y);
 }
@@ -157,23 +158,36 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
             p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
         }
     }
-    // Uncut tiles that are all resident at once, more than one per CU but fewer than two: the
-    // dispatcher deals workgroup i to XCD i % 8 and gives the first 256 a CU each, so workgroup
-    // i + 256 shares the CU of workgroup i and workgroups W-256 .. 255 keep theirs alone
-    // (observed with a probe that records where each workgroup runs).  The call lasts as long as
-    // the slowest CU: give the longest tiles the CUs of their own and pair the rest long with short.
+    // Uncut tiles in an order that suits the dispatcher, which deals workgroup i to XCD i % 8,
+    // gives the first 256 a CU each and puts workgroup i + 256 beside workgroup i (observed with
+    // a probe that records where each workgroup runs).  While everything is resident (up to 512
+    // workgroups) the call lasts as long as the slowest CU: the longest tiles get the CUs of their
+    // own (positions W-256 .. 255) and the rest are paired long with short.  With more tiles than
+    // slots the longest go first and the short ones fill the end; the natural order is the
+    // opposite (a chunk's later tiles see more keys).  The order travels as a table in the kernel
+    // arguments; a batch with more tiles than the table holds is simply walked backwards.
     const int32_t first_round = 256 / Hkv;                       // slot positions of the first 256 workgroups
     bool slots_fit = true;                                       // a table entry is 16 bits
     for (int32_t k = 0; k < n_listed; ++k) slots_fit = slots_fit && tile_list[k].slot < 65536;
-    if (p.max_ranges == 1 && 256 % Hkv == 0 && tiles == n_listed && slots_fit && tiles > first_round && tiles < 2 * first_round) {
-        std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
-        const int32_t n_pair = (int32_t)tiles - first_round, n_solo = first_round - n_pair;
-        for (int32_t k = 0; k < n_solo; ++k) p.order.slot[n_pair + k] = (uint16_t)tile_list[k].slot;
-        for (int32_t k = 0; k < n_pair; ++k) {
-            p.order.slot[k] = (uint16_t)tile_list[n_solo + k].slot;                                   // long
-            p.order.slot[first_round + k] = (uint16_t)tile_list[n_solo + 2 * n_pair - 1 - k].slot;    // short
+    if (p.max_ranges == 1 && wgs > 256) {
+        const bool listed = tiles == n_listed && slots_fit;
+        if (listed && wgs <= 512 && 256 % Hkv == 0) {
+            std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
+            const int32_t n_pair = (int32_t)tiles - first_round, n_solo = first_round - n_pair;
+            for (int32_t k = 0; k < n_solo; ++k) p.order.slot[n_pair + k] = (uint16_t)tile_list[k].slot;
+            for (int32_t k = 0; k < n_pair; ++k) {
+                p.order.slot[k] = (uint16_t)tile_list[n_solo + k].slot;                                   // long
+                p.order.slot[first_round + k] = (uint16_t)tile_list[n_solo + 2 * n_pair - 1 - k].slot;    // short
+            }
+            p.n_ordered = (int32_t)tiles;
+        } else if (wgs > 512) {
+            if (listed) {
+                std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
+                for (int32_t k = 0; k < n_listed; ++k) p.order.slot[k] = (uint16_t)tile_list[k].slot;
+                p.n_ordered = (int32_t)tiles;
+            }
+            p.backwards = true;
         }
-        p.n_ordered = (int32_t)tiles;
     }
     if (p.max_ranges > 1) {
         p.base_slot = (int32_t)prefill_slot_start(b->h_cu_q_lens[first], first, G);
@@ -216,12 +230,12 @@ static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_bat
         hipLaunchKernelGGL((prefill_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
                            b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
-                           plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order);
+                           plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order, (int32_t)plan.backwards);
     else
         hipLaunchKernelGGL((prefill_kernel<64, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
                            pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
                            b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
-                           plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order);
+                           plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order, (int32_t)plan.backwards);
     if (plan.max_ranges > 1) launch_merge_as<E>(pool, b, plan, out, Hq, workspace, st);
     return check_launch("prefill kernels");
 }

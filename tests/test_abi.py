@@ -271,8 +271,12 @@ def test_prefill_tile_order_gives_the_longest_tiles_a_cu_of_their_own():
     assert min(solo) >= rest[0]
     for k in range(n_pair):
         assert steps[order[k]] == rest[k] and steps[order[first_round + k]] == rest[2 * n_pair - 1 - k]
-    # natural order where the rule does not apply: a full round, tiles cut into ranges, one per CU or fewer
-    for ctx2, ql2 in (([2048] * 4, [512] * 4), ([30000], [1024]), ([100], [256])):
+    # more tiles than workgroup slots: longest first
+    b3, keep3 = _batch([0], [4096], max_blocks=1 << 12)
+    n3 = lib.cs_debug_prefill_order(ctypes.byref(b3), 32, 8, 128, buf, 512)
+    assert n3 == 128 and list(buf[:n3]) == list(range(127, -1, -1))       # one causal chunk: its tiles backwards
+    # natural order where no rule applies: tiles cut into key ranges, one workgroup per CU or fewer
+    for ctx2, ql2 in (([30000], [1024]), ([100], [256])):
         b2, keep2 = _batch(ctx2, ql2, max_blocks=1 << 12)
         assert lib.cs_debug_prefill_order(ctypes.byref(b2), 32, 8, 128, buf, 512) == 0
 

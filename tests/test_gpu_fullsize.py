@@ -154,23 +154,30 @@ def test_chunks_between_one_and_four_workgroups_per_cu_are_cut_into_key_ranges(H
     run_batch(b, 91, list(range(len(ctx) + 2)), rows_per_chunk=4)
 
 
-@pytest.mark.parametrize("Hq,Hkv,ctx,ql", [
-    (40, 8, [2048, 1000, 3000, 500], [320] * 4),      # 416 tile workgroups of four lengths
-    (32, 8, [6000], [1536]),                          # 384: one chunk, causal lengths
-    (28, 4, [200, 800, 1400, 2000], [448] * 4),       # 392, four kv heads
+@pytest.mark.parametrize("Hq,Hkv,ctx,ql,n_dec", [
+    (40, 8, [2048, 1000, 3000, 500], [320] * 4, 0),   # 416 tile workgroups of four lengths: solo + pairs
+    (32, 8, [6000], [1536], 0),                       # 384: one chunk, causal lengths
+    (28, 4, [200, 800, 1400, 2000], [448] * 4, 0),    # 392, four kv heads
+    (32, 8, [0], [4096], 0),                          # 1024: more tiles than slots, longest first
+    (32, 8, [0, 3000], [3072, 1024], 9),              # 1024 beside nine decodes: the fused grid walks the tiles backwards
 ])
-def test_prefill_grids_dealt_to_cus_by_tile_length(Hq, Hkv, ctx, ql):
-    """Between one and two tile workgroups per CU the host permutes the tiles over the grid
-    positions (longest alone on a CU, the rest paired long with short).  The plan must really
-    be a permutation, and every chunk must still meet the oracle."""
+def test_prefill_grids_dealt_to_cus_by_tile_length(Hq, Hkv, ctx, ql, n_dec):
+    """The host orders uncut tiles for the dispatcher: between one and two tile workgroups per
+    CU the longest get a CU of their own and the rest are paired long with short; with more tiles
+    than workgroup slots the longest go first.  The plan must really be a permutation of the
+    tiles, and every chunk must still meet the oracle."""
     sh = synth.Shape(Hq, Hkv, 128)
-    b = synth.make_batch(sh, ctx, ql, synth.generator(93))
-    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    b = synth.make_batch(sh, [900] * n_dec + ctx, [1] * n_dec + ql, synth.generator(93))
+    only_chunks = cs.Batch(b.block_tables[n_dec:], b.ctx_lens[n_dec:], b.cu_q_lens[n_dec:] - n_dec)
     import ctypes
     buf = (ctypes.c_int32 * 512)()
-    n = cs.lib().cs_debug_prefill_order(ctypes.byref(bb.c), sh.Hq, sh.Hkv, sh.D, buf, 512)
-    assert 256 // Hkv < n < 512 // Hkv and len(set(buf[:n])) == n
-    run_batch(b, 93, list(range(len(ctx))), rows_per_chunk=6)
+    n = cs.lib().cs_debug_prefill_order(ctypes.byref(only_chunks.c), sh.Hq, sh.Hkv, sh.D, buf, 512)
+    assert n > 256 // Hkv and len(set(buf[:n])) == n
+    cs.cs_set_mixed_fusion(2)
+    try:
+        run_batch(b, 93, list(range(n_dec + len(ctx))), rows_per_chunk=6)
+    finally:
+        cs.cs_set_mixed_fusion(1)
 
 
 @pytest.mark.parametrize("seed", range(16))
