@@ -24,15 +24,18 @@ HBM_PEAK = 8.0e12            # B/s, MI355X HBM3E
 MFMA_BF16_PEAK = 2.5e15      # FLOP/s, dense bf16
 
 WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b_ckpt"]
-# the kernel behind the call a roofline line is quoted for
-KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): "cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16, 2> (the call's only kernel here)",
-             ("qwen14b_ckpt", "ckpt_gather"): "cs::page_copy_kernel<true>",
-             ("qwen7b_mixed", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
-             ("llama70b_long", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
-             ("qwen14b_ckpt", "paged_attention_mixed"): "cs::mixed_kernel<128, cs::Bf16> (prefill tiles and decode work items in one grid)",
-             ("tiny", "paged_attention_mixed"): "cs::mixed_kernel<64, cs::Bf16> (prefill tiles and decode work items in one grid)",
-             ("qwen7b_mixed", "prefill_only"): "cs::prefill_kernel<128, cs::Bf16>",
-             ("llama70b_long", "prefill_only"): "cs::prefill_kernel<128, cs::Bf16>"}
+# the kernel behind the call a roofline line is quoted for: the start of its name as the profiler
+# prints it (the remaining template arguments -- prefetch depth, issue priorities, page size --
+# follow from the launch plan) and a note
+_ONE_GRID = "prefill tiles and decode work items in one grid"
+KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): ("cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16,", "the call's only kernel here"),
+             ("qwen14b_ckpt", "ckpt_gather"): ("cs::page_copy_kernel<true>", ""),
+             ("qwen7b_mixed", "paged_attention_mixed"): ("cs::mixed_kernel<128, cs::Bf16,", _ONE_GRID),
+             ("llama70b_long", "paged_attention_mixed"): ("cs::mixed_kernel<128, cs::Bf16,", _ONE_GRID),
+             ("qwen14b_ckpt", "paged_attention_mixed"): ("cs::mixed_kernel<128, cs::Bf16,", _ONE_GRID),
+             ("tiny", "paged_attention_mixed"): ("cs::mixed_kernel<64, cs::Bf16,", _ONE_GRID),
+             ("qwen7b_mixed", "prefill_only"): ("cs::prefill_kernel<128, cs::Bf16,", ""),
+             ("llama70b_long", "prefill_only"): ("cs::prefill_kernel<128, cs::Bf16,", "")}
 
 
 def log(*a):
@@ -75,16 +78,17 @@ def attention_work(b, seqs=None):
         c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
         if ql == 1:
             n = c + 1
-            dec_bytes += n * 2 * sh.Hkv * sh.D * 2 + 2 * sh.Hq * sh.D * 2 + 4 * ((n + 15) // 16)
+            dec_bytes += n * 2 * sh.Hkv * sh.D * 2 + 2 * sh.Hq * sh.D * 2 + 4 * ((n + sh.page_size - 1) // sh.page_size)
         elif ql > 1:
             pre_flops += 4 * sh.Hq * sh.D * (ql * c + ql * (ql + 1) // 2)
             pre_bytes += (c + ql) * 2 * sh.Hkv * sh.D * 2 + 2 * ql * sh.Hq * sh.D * 2
     return dec_bytes, pre_flops, pre_bytes
 
 
-def build(name, f16=False):
+def build(name, f16=False, page_size=16):
     """Allocate and fill the workload on the GPU; returns (batch, legs, dominant leg name, info).
-    f16: the pool and the queries hold IEEE half and the fp16 attention entry point is timed."""
+    f16: the pool and the queries hold IEEE half and the fp16 attention entry point is timed.
+    page_size: tokens per page of the pool (8: the three model-shaped attention workloads only)."""
     import torch
     from paper_2410_01228_amd import binding as cs
     from paper_2410_01228_amd import synth
@@ -92,11 +96,11 @@ def build(name, f16=False):
     attend = cs.cs_paged_attention_mixed_f16 if f16 else cs.cs_paged_attention_mixed
 
     idx = WORKLOADS.index(name)
-    b = synth.CONFIGS[idx]()
+    b = synth.CONFIGS[idx]() if page_size == 16 else synth.CONFIGS[idx](page_size=page_size)
     sh = b.shape
     gen = torch.Generator(device="cuda")
     gen.manual_seed(synth.BASE_SEED + idx)
-    pool = cs.Pool.empty(sh.L, b.num_pages, sh.Hkv, sh.D)
+    pool = cs.Pool.empty(sh.L, b.num_pages, sh.Hkv, sh.D, page_size=sh.page_size)
     fill_randn_bf16(pool.tensor.view(-1), gen, edt)
     bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
     T = b.T
@@ -538,17 +542,20 @@ def append_sweep():
 
 
 def read_traffic(name, kernel):
-    """HBM bytes per launch of `kernel` (as the profiler prints its name) from the committed
-    counter summary of the workload, if it has a row for it."""
+    """(full kernel name, HBM bytes per launch) of the kernel whose name, as the profiler prints
+    it, starts with `kernel`, from the committed counter summary of the workload; of several
+    such rows the one with the most launches.  (None, None) if there is no such row."""
     p = os.path.join(ROOT, "profiles", "%s_hbm_traffic.txt" % name)
     if not os.path.exists(p):
-        return None
-    in_table = False
+        return None, None
+    in_table, best = False, (None, None, -1)
     for line in open(p):
         in_table = in_table or line.startswith("## HBM traffic")
-        if in_table and line.startswith(kernel + " "):
-            return float(line.split()[-1])
-    return None
+        if in_table and line.startswith(kernel):
+            f = line.split()                      # name ..., launches, FETCH, WRITE, HBM bytes
+            if int(f[-4]) > best[2]:
+                best = (line[:line.rfind(">") + 1] if ">" in line else f[0], float(f[-1]), int(f[-4]))
+    return best[0], best[1]
 
 
 def main():
@@ -559,6 +566,8 @@ def main():
     ap.add_argument("--workload", default="llama8b_decode", choices=WORKLOADS)
     ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--page-size", type=int, default=16, choices=[16, 8],
+                    help="tokens per page of the pool (16: the paper's; 8: the smaller variant)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="element type of the pool and the queries (f16: the fp16 attention entry point)")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
@@ -592,7 +601,9 @@ def main():
         torch.cuda.synchronize()
         log("calibration: plain_copy_kernel moved %d bytes (read) + %d bytes (written) per launch" % (n, n))
         del src, dst
-    b, legs, detail, info = build(args.workload, f16=args.dtype == "f16")
+    if args.page_size != 16 and args.workload not in ("llama8b_decode", "qwen7b_mixed", "llama70b_long"):
+        sys.exit("bench.py: --page-size 8 is for the workloads llama8b_decode, qwen7b_mixed and llama70b_long")
+    b, legs, detail, info = build(args.workload, f16=args.dtype == "f16", page_size=args.page_size)
     log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
         % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))
     sec_per_step = time_legs(legs, args.steps, args.warmup)
@@ -613,11 +624,17 @@ def main():
         dom = detail[1]
     else:
         dom = by_name["paged_attention_mixed"]
-    dom_kernel = KERNEL_OF.get((args.workload, dom.name), dom.name)
-    if args.dtype == "f16":
-        dom_kernel = dom_kernel.replace("cs::Bf16", "cs::F16")
-    if args.separate_launches and "mixed_kernel" in dom_kernel:
-        dom_kernel = dom.name
+    dom_prefix, dom_note = KERNEL_OF.get((args.workload, dom.name), (None, ""))
+    if dom_prefix and args.dtype == "f16":
+        dom_prefix = dom_prefix.replace("cs::Bf16", "cs::F16")
+    if args.separate_launches and dom_prefix and "mixed_kernel" in dom_prefix:
+        dom_prefix = None
+    if args.page_size != 16:
+        dom_prefix = None                          # the committed counter summaries are of 16-token pages
+    dom_full, dom_traffic = read_traffic(args.workload, dom_prefix) if dom_prefix else (None, None)
+    dom_kernel = dom_full or (dom_prefix + " ...>" if dom_prefix and dom_prefix.endswith(",") else dom_prefix) or dom.name
+    if dom_note:
+        dom_kernel += " (%s)" % dom_note
     result = {
         "metric": "mixed-batch paged-attn tokens/s per layer",
         "value": round(info["T"] / (att_us * 1e-6), 1),
@@ -627,9 +644,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
-                   "page_size": 16, "layers_per_step": 1,
+                   "page_size": args.page_size, "layers_per_step": 1,
                    "step": "+".join(l.name for l in legs)},
-        "roofline": dict(dom.roofline(read_traffic(args.workload, dom_kernel.split(" (")[0])), kernel=dom_kernel),
+        "roofline": dict(dom.roofline(dom_traffic), kernel=dom_kernel),
         "legs": {l.name: {"us": round(l.us, 2), "us_median": round(l.us_median, 2), "us_min": round(l.us_min, 2),
                           "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
     }

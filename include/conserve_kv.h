@@ -13,8 +13,9 @@
  *   - every pointer is owned by the caller and must stay valid until the enqueued work has
  *     run.  "device" pointers are HIP device memory of the current device, "host" pointers
  *     are ordinary host memory read during the call only;
- *   - 16-bit data (bf16; fp16 through cs_paged_attention_mixed_f16), 16 tokens per page (the paper's page granularity, Sec. 5),
- *     head_dim 64 or 128, num_q_heads / num_kv_heads <= 16;
+ *   - 16-bit data (bf16; fp16 through cs_paged_attention_mixed_f16), 16 tokens per page (the
+ *     paper's page granularity, Sec. 5) or 8 (cs_kv_pool.page_size), head_dim 64 or 128,
+ *     num_q_heads / num_kv_heads <= 16;
  *   - each call works on ONE decoder layer (attention, append) or a layer range (gather,
  *     restore), so that a scheduler can stop between layers (layer-wise preemption,
  *     Sec. 4.3): sequences are expected online-first, and passing a smaller num_seqs /
@@ -36,6 +37,14 @@
  * A 16-byte unit of K is 8 features of one token, a 16-byte unit of V is one feature of 8
  * tokens: these are the operand registers the gfx950 matrix instructions take for Q.K^T and
  * P.V, so wavefronts read blocks with fully coalesced loads and no shuffles.
+ *
+ * Pages of 8 tokens (page_size 8; a finer unit for the per-token management of Sec. 4.4)
+ * use the same format with 8 in place of 16 tokens and one token group in place of two:
+ *     pool[layer][page][kv][kv_head][8 * head_dim],  t = 0..7
+ *     K:  ((d / 8) * 8 + t) * 8 + d % 8                  [D/8][8 tokens][8 features]
+ *     V:  ((d / 16) * 16 + d % 16) * 8 + t               [D/16][16][8 tokens]
+ * Wherever a comment below says 16 tokens or "/16", read page_size.  The attention kernels
+ * then take two (decode) or four (prefill) pages per step instead of one or two.
  */
 #ifndef CONSERVE_KV_H
 #define CONSERVE_KV_H
@@ -64,7 +73,7 @@ typedef struct {
     void*   base;                   /* device                                            */
     int32_t num_layers;
     int32_t num_pages;
-    int32_t page_size;              /* must be 16                                        */
+    int32_t page_size;              /* 16 or 8                                           */
     int32_t num_kv_heads;
     int32_t head_dim;               /* 64 or 128                                         */
     int64_t layer_stride;           /* >= num_pages * page_stride                        */
@@ -87,8 +96,10 @@ typedef struct {
     const int32_t* h_cu_q_lens;         /* host copy of cu_q_lens                        */
 } cs_batch;
 
-/* Bytes of one (layer, page): K and V of every kv head.  0 if the shape is unsupported. */
+/* Bytes of one (layer, page) of 16 tokens: K and V of every kv head.  0 if the shape is
+ * unsupported.  cs_pool_page_bytes: the same for the page size of `pool`. */
 size_t cs_page_bytes(int32_t num_kv_heads, int32_t head_dim);
+size_t cs_pool_page_bytes(const cs_kv_pool* pool);
 
 /* KV append (the cache is append-only, Sec. 1 and 4.4; pages of 16 tokens, Sec. 5).
  * For every new token t = cu_q_lens[s] + i: copy k_new[t][h][:] and v_new[t][h][:] into
@@ -134,7 +145,7 @@ int cs_paged_attention_mixed_f16(const cs_kv_pool* pool, int32_t layer, const cs
  * buffer and transferred once; Sec. 4.4: only newly filled pages are checkpointed).
  *     staging[l - layer_begin][i][0 .. page_elems) = pool[l][page_ids[i]][...]
  * for layer_begin <= l < layer_end, 0 <= i < n.  page_ids: device [n]; duplicates allowed.
- * staging: device, (layer_end-layer_begin) * n * cs_page_bytes() bytes, 16-byte aligned.
+ * staging: device, (layer_end-layer_begin) * n * cs_pool_page_bytes() bytes, 16-byte aligned.
  * n == 0 is a no-op. */
 int cs_kv_ckpt_gather(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end,
                       const int32_t* page_ids, int32_t n,
@@ -148,7 +159,7 @@ int cs_kv_ckpt_restore(const cs_kv_pool* pool, int32_t layer_begin, int32_t laye
 
 /* Token-granular checkpoint (Sec. 4.4: the KV state is managed per token, and after each
  * generation step only the newly generated tokens are checkpointed).  token_slots[i] =
- * page * 16 + slot names one cached token;
+ * page * page_size + slot names one cached token;
  *     staging[l - layer_begin][i][0][h][:] = its K row of kv head h,  [...][1][h][:] = its V row
  * (plain rows of head_dim bf16, the layout of k_new / v_new; nothing of the page format is
  * left in the buffer).  token_slots: device [n]; a slot outside the pool is skipped.

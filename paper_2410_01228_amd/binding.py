@@ -89,6 +89,7 @@ def lib():
         vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
         PP, BP = ctypes.POINTER(cs_kv_pool), ctypes.POINTER(cs_batch)
         L.cs_page_bytes.restype, L.cs_page_bytes.argtypes = sz, [i32, i32]
+        L.cs_pool_page_bytes.restype, L.cs_pool_page_bytes.argtypes = sz, [PP]
         L.cs_kv_append.restype, L.cs_kv_append.argtypes = ctypes.c_int, [PP, i32, BP, vp, vp, vp]
         L.cs_paged_attention_workspace_bytes.restype = sz
         L.cs_paged_attention_workspace_bytes.argtypes = [BP, i32, i32, i32]
@@ -131,7 +132,7 @@ def lib():
 
 
 EXPORTS = [
-    "cs_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
+    "cs_page_bytes", "cs_pool_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
     "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
@@ -154,22 +155,23 @@ def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
 
 
 class Pool:
-    """A cs_kv_pool over a torch tensor [L, P, 2, Hkv, 16*D] bf16 (or any tensor of that
-    many elements); keeps the tensor alive."""
+    """A cs_kv_pool over a torch tensor [L, P, 2, Hkv, page_size*D] bf16 (or any tensor of
+    that many elements); keeps the tensor alive."""
 
     def __init__(self, tensor: torch.Tensor, L: int, P: int, Hkv: int, D: int,
-                 layer_stride: Optional[int] = None, page_stride: Optional[int] = None):
+                 layer_stride: Optional[int] = None, page_stride: Optional[int] = None, page_size: int = PAGE):
         self.tensor = tensor
-        self.page_elems = 2 * Hkv * PAGE * D
+        self.page_size = page_size
+        self.page_elems = 2 * Hkv * page_size * D
         ps = self.page_elems if page_stride is None else page_stride
         ls = P * ps if layer_stride is None else layer_stride
-        self.c = cs_kv_pool(_ptr(tensor), L, P, PAGE, Hkv, D, ls, ps)
+        self.c = cs_kv_pool(_ptr(tensor), L, P, page_size, Hkv, D, ls, ps)
         self.L, self.P, self.Hkv, self.D = L, P, Hkv, D
 
     @classmethod
-    def empty(cls, L, P, Hkv, D, device="cuda"):
-        t = torch.empty((L, P, 2, Hkv, PAGE * D), dtype=torch.bfloat16, device=device)
-        return cls(t, L, P, Hkv, D)
+    def empty(cls, L, P, Hkv, D, device="cuda", page_size: int = PAGE):
+        t = torch.empty((L, P, 2, Hkv, page_size * D), dtype=torch.bfloat16, device=device)
+        return cls(t, L, P, Hkv, D, page_size=page_size)
 
 
 class Batch:
@@ -213,6 +215,10 @@ def _check(rc, where):
 
 def cs_page_bytes(Hkv: int, D: int) -> int:
     return int(lib().cs_page_bytes(Hkv, D))
+
+
+def cs_pool_page_bytes(pool: "Pool") -> int:
+    return int(lib().cs_pool_page_bytes(ctypes.byref(pool.c)))
 
 
 def cs_kv_append(pool: Pool, layer: int, batch: Batch, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):

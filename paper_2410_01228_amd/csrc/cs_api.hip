@@ -26,8 +26,8 @@ int validate_pool(const cs_kv_pool* p) {
     if (!p || !p->base) return CS_ERR_INVALID_ARG;
     if (p->num_layers <= 0 || p->num_pages <= 0 || p->num_kv_heads <= 0 || p->head_dim <= 0)
         return CS_ERR_INVALID_ARG;
-    if (p->page_size != kPage || !shape_supported(p->num_kv_heads, p->head_dim)) return CS_ERR_UNSUPPORTED;
-    const int64_t page_elems = 2ll * p->num_kv_heads * kPage * p->head_dim;
+    if (!page_size_supported(p->page_size) || !shape_supported(p->num_kv_heads, p->head_dim)) return CS_ERR_UNSUPPORTED;
+    const int64_t page_elems = 2ll * p->num_kv_heads * p->page_size * p->head_dim;
     if (p->page_stride < page_elems || (p->page_stride & 7) != 0) return CS_ERR_INVALID_ARG;
     if (p->layer_stride < (int64_t)p->num_pages * p->page_stride || (p->layer_stride & 7) != 0)
         return CS_ERR_INVALID_ARG;
@@ -36,7 +36,7 @@ int validate_pool(const cs_kv_pool* p) {
 }
 
 int validate_batch(const cs_kv_pool* pool, const cs_batch* b) {
-    (void)pool;
+    const int32_t page_size = pool ? pool->page_size : kPage;
     if (!b) return CS_ERR_INVALID_ARG;
     if (b->num_seqs < 0 || b->num_tokens < 0 || b->num_seqs > 65535) return CS_ERR_INVALID_ARG;
     if (b->num_seqs == 0) return b->num_tokens == 0 ? CS_OK : CS_ERR_INVALID_ARG;
@@ -48,7 +48,7 @@ int validate_batch(const cs_kv_pool* pool, const cs_batch* b) {
         const int64_t ql = (int64_t)b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
         const int64_t c = b->h_ctx_lens[s];
         if (ql < 0 || c < 0) return CS_ERR_INVALID_ARG;
-        if (c + ql > (int64_t)b->max_blocks_per_seq * kPage) return CS_ERR_INVALID_ARG;
+        if (c + ql > (int64_t)b->max_blocks_per_seq * page_size) return CS_ERR_INVALID_ARG;
     }
     return CS_OK;
 }
@@ -165,6 +165,11 @@ size_t cs_page_bytes(int32_t Hkv, int32_t D) {
     return (size_t)2 * Hkv * kPage * D * 2;
 }
 
+size_t cs_pool_page_bytes(const cs_kv_pool* pool) {
+    if (!pool || !page_size_supported(pool->page_size) || !shape_supported(pool->num_kv_heads, pool->head_dim)) return 0;
+    return pool_page_bytes(*pool);
+}
+
 int cs_kv_append(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
                  const void* k_new, const void* v_new, void* stream) {
     int rc = validate_pool(pool);
@@ -267,7 +272,7 @@ static int ckpt_common(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int
     if (l0 < 0 || l1 < l0 || l1 > pool->num_layers || n < 0) return CS_ERR_INVALID_ARG;
     if (n == 0 || l1 == l0) return CS_OK;
     if (!ids || !staging || ((uintptr_t)staging & 15)) return CS_ERR_INVALID_ARG;
-    const size_t need = (size_t)(l1 - l0) * n * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const size_t need = (size_t)(l1 - l0) * n * pool_page_bytes(*pool);
     if (staging_bytes < need) return CS_ERR_STAGING_TOO_SMALL;
     if ((int64_t)n * 4 > 2147483647ll || l1 - l0 > 65535) return CS_ERR_INVALID_ARG;
     return 1;   // proceed
@@ -321,7 +326,7 @@ int cs_kv_ckpt_save(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_
     if (!host_buf) return CS_ERR_INVALID_ARG;
     const int lrc = launch_page_copy(*pool, l0, l1, ids, n, staging, true, (hipStream_t)stream);
     if (lrc) return lrc;
-    const size_t bytes = (size_t)(l1 - l0) * n * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const size_t bytes = (size_t)(l1 - l0) * n * pool_page_bytes(*pool);
     const hipError_t e = hipMemcpyAsync(host_buf, staging, bytes, hipMemcpyDeviceToHost, (hipStream_t)stream);
     return e == hipSuccess ? CS_OK : hip_failed(e, "checkpoint device-to-host copy");
 }
@@ -331,7 +336,7 @@ int cs_kv_ckpt_load(const cs_kv_pool* pool, int32_t l0, int32_t l1, const int32_
     const int rc = ckpt_common(pool, l0, l1, ids, n, staging, staging_bytes);
     if (rc <= 0) return rc;
     if (!host_buf) return CS_ERR_INVALID_ARG;
-    const size_t bytes = (size_t)(l1 - l0) * n * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const size_t bytes = (size_t)(l1 - l0) * n * pool_page_bytes(*pool);
     const hipError_t e = hipMemcpyAsync(staging, host_buf, bytes, hipMemcpyHostToDevice, (hipStream_t)stream);
     if (e != hipSuccess) return hip_failed(e, "checkpoint host-to-device copy");
     return launch_page_copy(*pool, l0, l1, ids, n, staging, false, (hipStream_t)stream);
@@ -352,7 +357,7 @@ int cs_kv_ckpt_save_run(const cs_kv_pool* pool, int32_t l0, int32_t l1, const in
     if (rc <= 0) return rc;
     const int lrc = launch_page_copy(*pool, l0, l1, ids, n, staging, true, (hipStream_t)stream, true);
     if (lrc) return lrc;
-    const size_t fat = (size_t)(l1 - l0) * cs_page_bytes(pool->num_kv_heads, pool->head_dim);   // one host page
+    const size_t fat = (size_t)(l1 - l0) * pool_page_bytes(*pool);   // one host page
     const hipError_t e = hipMemcpyAsync((char*)store->base + (size_t)first * fat, staging, (size_t)n * fat,
                                         hipMemcpyDeviceToHost, (hipStream_t)stream);
     return e == hipSuccess ? CS_OK : hip_failed(e, "checkpoint device-to-host copy");
@@ -362,7 +367,7 @@ int cs_kv_ckpt_load_run(const cs_kv_pool* pool, int32_t l0, int32_t l1, const in
                         void* staging, size_t staging_bytes, const cs_host_store* store, int32_t first, void* stream) {
     const int rc = run_common(pool, l0, l1, ids, n, staging, staging_bytes, store, first);
     if (rc <= 0) return rc;
-    const size_t fat = (size_t)(l1 - l0) * cs_page_bytes(pool->num_kv_heads, pool->head_dim);
+    const size_t fat = (size_t)(l1 - l0) * pool_page_bytes(*pool);
     const hipError_t e = hipMemcpyAsync(staging, (const char*)store->base + (size_t)first * fat, (size_t)n * fat,
                                         hipMemcpyHostToDevice, (hipStream_t)stream);
     if (e != hipSuccess) return hip_failed(e, "checkpoint host-to-device copy");

@@ -7,7 +7,11 @@
 
 namespace cs {
 
-constexpr int kPage = CS_PAGE_SIZE;          // tokens per page
+constexpr int kPage = CS_PAGE_SIZE;          // keys per step of the decode path; also the default page size
+// Pages hold 16 tokens (the paper's granularity, Sec. 5) or 8; the attention kernels are
+// instantiated for each and walk the keys 16 (decode) or 32 (prefill) at a time either way.
+inline bool page_size_supported(int32_t ps) { return ps == 16 || ps == 8; }
+inline size_t pool_page_bytes(const cs_kv_pool& p) { return (size_t)2 * p.num_kv_heads * p.page_size * p.head_dim * 2; }
 constexpr int kMaxGroup = 16;                // query heads per kv head that fit one MFMA tile
 
 // Records a failed HIP call for cs_last_hip_error(); returns CS_ERR_HIP.

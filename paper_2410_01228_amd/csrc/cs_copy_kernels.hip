@@ -55,7 +55,7 @@ int launch_page_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer_
 {
     const int32_t layers = layer_end - layer_begin;
     if (n == 0 || layers == 0) return CS_OK;
-    const int32_t page_bytes = (int32_t)cs_page_bytes(pool.num_kv_heads, pool.head_dim);
+    const int32_t page_bytes = (int32_t)pool_page_bytes(pool);
     const int32_t cpp = (page_bytes + kChunkBytes - 1) / kChunkBytes;
     dim3 grid((uint32_t)n * cpp, (uint32_t)layers);
     // staging[layer][page] (the default) or staging[page][layer] (one page's layers together)
@@ -85,7 +85,7 @@ template <bool kToStaging>
 __global__ __launch_bounds__(kTokenCopyThreads) void token_copy_kernel(
     uint16_t* __restrict__ pool_base, int64_t layer_stride, int64_t page_stride,
     int32_t num_pages, int32_t layer_begin, const int32_t* __restrict__ token_slots, int32_t n,
-    uint16_t* __restrict__ staging, int32_t Hkv, int32_t D)
+    uint16_t* __restrict__ staging, int32_t Hkv, int32_t D, int32_t page_size)
 {
     const int32_t units_per_head = D / 8, units_per_side = Hkv * units_per_head;
     const int32_t units_per_token = 2 * units_per_side;
@@ -94,20 +94,21 @@ __global__ __launch_bounds__(kTokenCopyThreads) void token_copy_kernel(
     const int32_t i = (int32_t)(gid / units_per_token), u = (int32_t)(gid - (int64_t)i * units_per_token);
     const int32_t l = blockIdx.y;
     const int32_t slot = token_slots[i];
-    const int32_t page = slot >> 4, t = slot & (kPage - 1);
+    const int32_t page = slot / page_size, t = slot - page * page_size;
     if (slot < 0 || page >= num_pages) return;                   // never touch a bad slot
+    const int32_t groups = page_size >> 3;                       // 8-token groups of a page
     const int32_t kv = u / units_per_side, r = u - kv * units_per_side;
     const int32_t h = r / units_per_head, d8 = r - h * units_per_head;
     uint16_t* blk = pool_base + (int64_t)(layer_begin + l) * layer_stride + (int64_t)page * page_stride
-                  + (int64_t)(kv * Hkv + h) * (kPage * D);
+                  + (int64_t)(kv * Hkv + h) * (page_size * D);
     uint16_t* row = staging + ((int64_t)l * n + i) * (2 * Hkv * D) + (int64_t)u * 8;
     if (kv == 0) {
-        u32x4* unit = (u32x4*)(blk + (d8 * kPage + t) * 8);
+        u32x4* unit = (u32x4*)(blk + (d8 * page_size + t) * 8);
         if (kToStaging) *(u32x4*)row = *unit; else *unit = *(const u32x4*)row;
     } else {
-        // features d8*8 .. +8 of token t: element (((d/16)*2 + t/8)*16 + d%16)*8 + t%8
+        // features d8*8 .. +8 of token t: element (((d/16)*groups + t/8)*16 + d%16)*8 + t%8
         const int32_t d0 = d8 * 8;
-        uint16_t* first = blk + ((((d0 >> 4) * 2 + (t >> 3)) * 16 + (d0 & 15)) * 8 + (t & 7));
+        uint16_t* first = blk + ((((d0 >> 4) * groups + (t >> 3)) * 16 + (d0 & 15)) * 8 + (t & 7));
         if (kToStaging) {
             uint16_t e[8];
 #pragma unroll
@@ -133,11 +134,11 @@ int launch_token_copy(const cs_kv_pool& pool, int32_t layer_begin, int32_t layer
     if (to_staging)
         hipLaunchKernelGGL(token_copy_kernel<true>, grid, dim3(kTokenCopyThreads), 0, st, (uint16_t*)pool.base,
                            pool.layer_stride, pool.page_stride, pool.num_pages, layer_begin, token_slots, n,
-                           (uint16_t*)staging, pool.num_kv_heads, pool.head_dim);
+                           (uint16_t*)staging, pool.num_kv_heads, pool.head_dim, pool.page_size);
     else
         hipLaunchKernelGGL(token_copy_kernel<false>, grid, dim3(kTokenCopyThreads), 0, st, (uint16_t*)pool.base,
                            pool.layer_stride, pool.page_stride, pool.num_pages, layer_begin, token_slots, n,
-                           (uint16_t*)staging, pool.num_kv_heads, pool.head_dim);
+                           (uint16_t*)staging, pool.num_kv_heads, pool.head_dim, pool.page_size);
     return check_launch("token_copy_kernel");
 }
 
@@ -182,6 +183,7 @@ int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 constexpr int kAppendThreads = 256;
 constexpr int kAppendSlotShift = 4;
 
+template <int PS>
 __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t D, int32_t S,
@@ -206,12 +208,11 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     const int32_t first = ctx_lens[s];                            // the step fills positions [first, last)
     const int32_t last = first + (cu_q_lens[s + 1] - t_seq);
     if (last - first == 1) return;                               // single tokens: append_token_kernel
+    // the workgroup's 16 positions: one page, or (pages of 8 tokens) two consecutive table entries
     const int32_t blk = (first >> 4) + (slot_id - ((t_seq >> kAppendSlotShift) + 2 * s));
-    const int32_t p0 = blk << 4;                                  // first position of the page
-    if (p0 >= last || blk >= max_blocks) return;
-    const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
-    if (page < 0 || page >= num_pages) return;
-    const int32_t block_elems = kPage * D;
+    const int32_t p0 = blk << 4;                                  // first of the 16 positions
+    if (p0 >= last) return;
+    const int32_t block_elems = PS * D;
     const int32_t row = Hkv * D;                                  // elements between consecutive tokens
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (wave * 32 >= D) return;                                   // head_dim 64: two wavefronts suffice
@@ -225,16 +226,26 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     // Either way consecutive lanes store consecutive units: 1 KiB per store instruction.
     const int32_t tok = lane & 15, dblk = wave * 4 + (lane >> 4);
     const int32_t th = (lane >> 4) & 1, feat = wave * 32 + (lane >> 5) * 16 + (lane & 15);
+    // table entries of this lane's K token and of its V half (the same entry for pages of 16)
+    const int32_t k_entry = PS == 16 ? blk : 2 * blk + (tok >> 3);
+    const int32_t v_entry = PS == 16 ? blk : 2 * blk + th;
+    const int32_t* table = block_tables + (int64_t)s * max_blocks;
+    const int32_t k_page = k_entry < max_blocks ? table[k_entry] : -1;
+    const int32_t v_page = v_entry < max_blocks ? table[v_entry] : -1;
+    const bool k_page_ok = k_page >= 0 && k_page < num_pages, v_page_ok = v_page >= 0 && v_page < num_pages;
     // packed token index of page position p0 (may lie before the step's first token)
     const int64_t tok_base = (int64_t)t_seq + (p0 - first);
     const int32_t pos = p0 + tok;
-    const bool k_ok = pos >= first && pos < last;
+    const bool k_ok = k_page_ok && pos >= first && pos < last;
     const int32_t vpos = p0 + th * 8;                             // first position of the half
-    const bool v_full = vpos >= first && vpos + 8 <= last;
+    const bool v_full = v_page_ok && vpos >= first && vpos + 8 <= last;
     const uint16_t* ksrc = k_new + (tok_base + tok) * row + (int64_t)h * D + dblk * 8;
     const uint16_t* vsrc = v_new + (tok_base + th * 8) * row + (int64_t)h * D + feat;
-    uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
-    uint16_t* dst = kblk + (int64_t)Hkv * block_elems + (wave * 64 + lane) * 8;
+    uint16_t* kblk = layer_base + (int64_t)(k_page_ok ? k_page : 0) * page_stride + (int64_t)h * block_elems;
+    // V unit of this lane: 64*wave + lane in a page of 16 tokens (two halves per feature tile),
+    // (2*wave + lane/32)*16 + lane%16 in the page of its half otherwise
+    const int32_t v_unit = PS == 16 ? wave * 64 + lane : (wave * 2 + (lane >> 5)) * 16 + (lane & 15);
+    uint16_t* dst = layer_base + (int64_t)(v_page_ok ? v_page : 0) * page_stride + (int64_t)(Hkv + h) * block_elems + v_unit * 8;
     u32x4 kv;
     uint16_t e[8];
     if (k_ok) kv = __builtin_nontemporal_load((const u32x4*)ksrc);
@@ -242,12 +253,12 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
 #pragma unroll
         for (int j = 0; j < 8; ++j) e[j] = __builtin_nontemporal_load(vsrc + j * row);
     }
-    if (k_ok) __builtin_nontemporal_store(kv, (u32x4*)(kblk + (dblk * 16 + tok) * 8));
+    if (k_ok) __builtin_nontemporal_store(kv, (u32x4*)(kblk + (dblk * PS + (tok & (PS - 1))) * 8));
     if (v_full) {
         const u32x4 unit = { (uint32_t)e[0] | ((uint32_t)e[1] << 16), (uint32_t)e[2] | ((uint32_t)e[3] << 16),
                              (uint32_t)e[4] | ((uint32_t)e[5] << 16), (uint32_t)e[6] | ((uint32_t)e[7] << 16) };
         __builtin_nontemporal_store(unit, (u32x4*)dst);
-    } else {
+    } else if (v_page_ok) {
         // a half the step fills only partly: element by element
 #pragma unroll
         for (int j = 0; j < 8; ++j)
@@ -264,7 +275,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     int32_t Hkv, int32_t D, int32_t S, int32_t T,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
-    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new, int32_t page_size)
 {
     const int32_t units_per_tok = Hkv * (D >> 3);
     const int64_t gid = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
@@ -286,19 +297,19 @@ __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     }
     if (cu_q_lens[s + 1] - cu_q_lens[s] != 1) return;
     const int32_t pos = ctx_lens[s];
-    const int32_t blk = pos >> 4;
+    const int32_t blk = pos / page_size;
     if (pos < 0 || blk >= max_blocks) return;
     const int32_t page = block_tables[(int64_t)s * max_blocks + blk];
     if (page < 0 || page >= num_pages) return;
-    const int32_t slot = pos & 15;
-    const int32_t block_elems = kPage * D;
+    const int32_t slot = pos - blk * page_size;
+    const int32_t block_elems = page_size * D;
     uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)h * block_elems;
     uint16_t* vblk = kblk + (int64_t)Hkv * block_elems;
     const int64_t src = ((int64_t)t * Hkv + h) * D + dblk * 8;
-    *(u32x4*)(kblk + (dblk * 16 + slot) * 8) = *(const u32x4*)(k_new + src);
+    *(u32x4*)(kblk + (dblk * page_size + slot) * 8) = *(const u32x4*)(k_new + src);
     const u32x4 vv = *(const u32x4*)(v_new + src);
-    // feature d = dblk*8 + e  ->  (((d/16)*2 + slot/8)*16 + d%16)*8 + slot%8
-    const int32_t vbase = (((dblk >> 1) * 2 + (slot >> 3)) * 16 + (dblk & 1) * 8) * 8 + (slot & 7);
+    // feature d = dblk*8 + e  ->  (((d/16)*groups + slot/8)*16 + d%16)*8 + slot%8, groups = page_size/8
+    const int32_t vbase = (((dblk >> 1) * (page_size >> 3) + (slot >> 3)) * 16 + (dblk & 1) * 8) * 8 + (slot & 7);
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const uint32_t w = vv[e >> 1];
@@ -321,10 +332,16 @@ int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
         const int64_t slots = (((int64_t)(b.num_tokens >> kAppendSlotShift) + 2ll * b.num_seqs) + 7) & ~7ll;   // whole groups of 8
         const int64_t blocks = slots * pool.num_kv_heads;
         if (blocks > 2147483647ll) return CS_ERR_UNSUPPORTED;
-        hipLaunchKernelGGL(append_page_kernel, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
-                           layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
-                           b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
-                           (const uint16_t*)k_new, (const uint16_t*)v_new);
+        if (pool.page_size == 16)
+            hipLaunchKernelGGL(append_page_kernel<16>, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
+                               layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
+                               b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
+                               (const uint16_t*)k_new, (const uint16_t*)v_new);
+        else
+            hipLaunchKernelGGL(append_page_kernel<8>, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
+                               layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
+                               b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
+                               (const uint16_t*)k_new, (const uint16_t*)v_new);
     }
     if (any_single) {
         const int64_t units = (int64_t)b.num_tokens * pool.num_kv_heads * (pool.head_dim / 8);
@@ -332,7 +349,7 @@ int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
         hipLaunchKernelGGL(append_token_kernel, dim3(blocks), dim3(kAppendThreads), 0, st,
                            layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
                            b.num_seqs, b.num_tokens, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
-                           b.cu_q_lens, (const uint16_t*)k_new, (const uint16_t*)v_new);
+                           b.cu_q_lens, (const uint16_t*)k_new, (const uint16_t*)v_new, pool.page_size);
     }
     return check_launch("append kernels");
 }

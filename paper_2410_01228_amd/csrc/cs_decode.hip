@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kPlanThreads) void decode_plan_kernel(
 
 // grid = items * Hkv workgroups, kv head fastest (the heads of one page are neighbours
 // in memory, so neighbouring workgroups share DRAM pages and translations).
-template <int D, class Src, class E, int kAhead>
+template <int D, class Src, class E, int kAhead, int PS>
 __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G,
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(kDecodeThreads, 2) void decode_split_kernel(
 {
     __shared__ DecodeLds<D> lds;
     const int32_t item = blockIdx.x / Hkv, g = blockIdx.x - item * Hkv;
-    decode_item<D, Src, E, kAhead>(lds, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks, src, ctx_lens,
+    decode_item<D, Src, E, kAhead, PS>(lds, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks, src, ctx_lens,
                            cu_q_lens, q, out, scale_log2e, part_o, part_ml, item, g);
 }
 
@@ -135,11 +135,13 @@ static int launch_decode_as(const cs_kv_pool& pool, int32_t layer, const cs_batc
     const uint32_t n_items = plan.in_args ? plan.total_items : identity ? b.num_seqs : plan.total_items;
     dim3 grid(n_items * (uint32_t)Hkv);
     dim3 mgrid((uint32_t)Hq, (uint32_t)plan.num_multi);
-#define CS_LAUNCH_DECODE_A(DD, SRC, src, AH)                                                            \
-    hipLaunchKernelGGL((decode_split_kernel<DD, SRC, E, AH>), grid, dim3(kDecodeThreads), 0, st, layer_base, \
+#define CS_LAUNCH_DECODE_P(DD, SRC, src, AH, PS)                                                        \
+    hipLaunchKernelGGL((decode_split_kernel<DD, SRC, E, AH, PS>), grid, dim3(kDecodeThreads), 0, st, layer_base, \
                        pool.page_stride, pool.num_pages, Hkv, G, b.block_tables, b.max_blocks_per_seq, \
                        src, b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out,               \
                        scale_log2e, part_o, part_ml);
+#define CS_LAUNCH_DECODE_A(DD, SRC, src, AH)                                                            \
+    if (pool.page_size == 16) { CS_LAUNCH_DECODE_P(DD, SRC, src, AH, 16) } else { CS_LAUNCH_DECODE_P(DD, SRC, src, AH, 8) }
 #define CS_LAUNCH_DECODE(DD, SRC, src)                                                                 \
     if (plan.pages_ahead == 2) { CS_LAUNCH_DECODE_A(DD, SRC, src, 2) } else { CS_LAUNCH_DECODE_A(DD, SRC, src, 1) }
 #define CS_LAUNCH_MERGE(DD, SRC, src)                                                                  \
@@ -167,6 +169,7 @@ static int launch_decode_as(const cs_kv_pool& pool, int32_t layer, const cs_batc
     }
 #undef CS_LAUNCH_DECODE
 #undef CS_LAUNCH_DECODE_A
+#undef CS_LAUNCH_DECODE_P
 #undef CS_LAUNCH_MERGE
     return check_launch("decode kernels");
 }

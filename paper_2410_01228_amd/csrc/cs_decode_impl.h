@@ -34,11 +34,38 @@ struct PageRegs {
     u32x2 v[D / 16];     // V block: tokens 4*(lane/16)..+4 of feature dt*16 + lane%16
 };
 
+// The page ids of one 16-key step: one page of 16 tokens, or two pages of 8 (the second
+// repeats the first where the sequence ends inside the first: what it brings is masked).
+template <int PS> struct StepIds;
+template <> struct StepIds<16> { int32_t a; };
+template <> struct StepIds<8> { int32_t a, b; };
+
+// Ids of step `step`, or an invalid id when the step lies outside [0, step_end).  n_entries:
+// table entries the sequence has.
+template <int PS>
+__device__ __forceinline__ StepIds<PS> step_ids(const int32_t* __restrict__ table, int32_t step, int32_t step_end,
+                                                int32_t n_entries)
+{
+    StepIds<PS> ids;
+    if constexpr (PS == 16) {
+        ids.a = step < step_end ? table[step] : -1;
+    } else {
+        ids.a = step < step_end ? table[2 * step] : -1;
+        ids.b = (step < step_end && 2 * step + 1 < n_entries) ? table[2 * step + 1] : ids.a;
+    }
+    return ids;
+}
+template <int PS>
+__device__ __forceinline__ bool step_ok(const StepIds<PS>& ids, int32_t num_pages) {
+    if constexpr (PS == 16) return ids.a >= 0 && ids.a < num_pages;
+    else return ids.a >= 0 && ids.a < num_pages && ids.b >= 0 && ids.b < num_pages;
+}
+
 template <int D>
 __device__ __forceinline__ void load_page(PageRegs<D>& r, const uint16_t* __restrict__ layer_base,
-                                          int64_t page_stride, int32_t page, int32_t g, int32_t Hkv, int lane)
+                                          int64_t page_stride, StepIds<16> ids, int32_t g, int32_t Hkv, int lane)
 {
-    const uint16_t* kblk = layer_base + (int64_t)page * page_stride + (int64_t)g * (kPage * D);
+    const uint16_t* kblk = layer_base + (int64_t)ids.a * page_stride + (int64_t)g * (kPage * D);
     const uint16_t* vblk = kblk + (int64_t)Hkv * (kPage * D);
 #pragma unroll
     for (int kk = 0; kk < D / 32; ++kk)
@@ -50,6 +77,28 @@ __device__ __forceinline__ void load_page(PageRegs<D>& r, const uint16_t* __rest
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt)
         r.v[dt] = __builtin_nontemporal_load((const u32x2*)vblk + dt * 64 + voff);
+}
+
+// The same registers from two pages of 8 tokens: K rows 0..7 (lanes with bit 3 clear) and the
+// V units of token half 0 (lanes below 32) come from the first page, the rest from the second.
+// Inside a page of 8 tokens a K feature block holds 8 units and a V feature tile 16, so a
+// wavefront load still reads two runs of 512 consecutive bytes.
+template <int D>
+__device__ __forceinline__ void load_page(PageRegs<D>& r, const uint16_t* __restrict__ layer_base,
+                                          int64_t page_stride, StepIds<8> ids, int32_t g, int32_t Hkv, int lane)
+{
+    const int32_t k_id = (lane & 8) ? ids.b : ids.a;
+    const int32_t v_id = (lane & 32) ? ids.b : ids.a;
+    const uint16_t* kblk = layer_base + (int64_t)k_id * page_stride + (int64_t)g * (8 * D);
+    const uint16_t* vblk = layer_base + (int64_t)v_id * page_stride + (int64_t)(Hkv + g) * (8 * D);
+    const int koff = (lane >> 4) * 8 + (lane & 7);                 // in 16-byte units
+#pragma unroll
+    for (int kk = 0; kk < D / 32; ++kk)
+        r.k[kk] = __builtin_nontemporal_load((const u32x4*)kblk + kk * 32 + koff);
+    const int voff = (lane & 15) * 2 + ((lane >> 4) & 1);         // in 8-byte pieces
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+        r.v[dt] = __builtin_nontemporal_load((const u32x2*)vblk + dt * 32 + voff);
 }
 
 // One wavefront's running state.
@@ -164,7 +213,7 @@ struct DecodeLds {
 // decode).  kAhead: pages a wavefront keeps in flight beyond the one it multiplies (1 or 2; a
 // page is 32 registers, so 2 costs the third workgroup per CU: it pays for long items on a
 // full grid, not for short ones on a small grid).
-template <int D, class Src, class E, int kAhead>
+template <int D, class Src, class E, int kAhead, int PS>
 __device__ __forceinline__ void decode_item(
     DecodeLds<D>& lds,
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -179,9 +228,12 @@ __device__ __forceinline__ void decode_item(
     DecodeItem it;
     if (!fetch_item(src, item, ctx_lens, cu_q_lens, it)) return;
     const int32_t s = it.seq, t = it.token, n_keys = it.n_keys;
+    // steps of 16 keys: pages of 16 tokens, or pairs of pages of 8
+    const int32_t n_entries = min((n_keys + PS - 1) / PS, max_blocks);     // table entries in use
     const int32_t page_begin = it.key_begin >> 4;
     // an item can come out empty when a short sequence is cut very finely
-    const int32_t page_end = it.key_end > it.key_begin ? min((it.key_end + kPage - 1) >> 4, max_blocks) : page_begin;
+    const int32_t page_end = it.key_end > it.key_begin
+        ? min((it.key_end + kPage - 1) >> 4, PS == 16 ? max_blocks : (n_entries + 1) >> 1) : page_begin;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int32_t* table = block_tables + (int64_t)s * max_blocks;
@@ -214,17 +266,17 @@ __device__ __forceinline__ void decode_item(
         // flight while the current page is multiplied
         PageRegs<D> cur, nxt;
         int32_t pg = page_begin + wave;
-        int32_t id_cur = pg < page_end ? table[pg] : -1;
-        int32_t id_nxt = pg + kDecodeWaves < page_end ? table[pg + kDecodeWaves] : -1;
-        if (pg < page_end && id_cur >= 0 && id_cur < num_pages)
+        auto id_at = [&](int32_t p) { return step_ids<PS>(table, p, page_end, n_entries); };
+        auto ok = [&](const StepIds<PS>& id) { return step_ok<PS>(id, num_pages); };
+        StepIds<PS> id_cur = id_at(pg);
+        StepIds<PS> id_nxt = id_at(pg + kDecodeWaves);
+        if (ok(id_cur))
             load_page<D>(cur, layer_base, page_stride, id_cur, g, Hkv, lane);
         while (pg < page_end) {
             const int32_t pg_n = pg + kDecodeWaves;
-            const bool have_n = pg_n < page_end;
-            const int32_t id_n2 = pg_n + kDecodeWaves < page_end ? table[pg_n + kDecodeWaves] : -1;
-            const bool ok_n = have_n && id_nxt >= 0 && id_nxt < num_pages;
-            if (ok_n) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
-            if (id_cur >= 0 && id_cur < num_pages)
+            const StepIds<PS> id_n2 = id_at(pg_n + kDecodeWaves);
+            if (ok(id_nxt)) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
+            if (ok(id_cur))
                 process_page<D, E>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
             cur = nxt;
             id_cur = id_nxt;
@@ -236,13 +288,13 @@ __device__ __forceinline__ void decode_item(
         // in flight while the current page is multiplied
         PageRegs<D> b0, b1, b2;
         int32_t pg = page_begin + wave;
-        auto id_at = [&](int32_t p) -> int32_t { return p < page_end ? table[p] : -1; };
-        auto ok = [&](int32_t id) { return id >= 0 && id < num_pages; };
-        int32_t id0 = id_at(pg), id1 = id_at(pg + kDecodeWaves), id2 = id_at(pg + 2 * kDecodeWaves);
+        auto id_at = [&](int32_t p) { return step_ids<PS>(table, p, page_end, n_entries); };
+        auto ok = [&](const StepIds<PS>& id) { return step_ok<PS>(id, num_pages); };
+        StepIds<PS> id0 = id_at(pg), id1 = id_at(pg + kDecodeWaves), id2 = id_at(pg + 2 * kDecodeWaves);
         if (ok(id0)) load_page<D>(b0, layer_base, page_stride, id0, g, Hkv, lane);
         if (ok(id1)) load_page<D>(b1, layer_base, page_stride, id1, g, Hkv, lane);
         auto stage = [&](PageRegs<D>& use, PageRegs<D>& fill) {
-            const int32_t id3 = id_at(pg + 3 * kDecodeWaves);
+            const StepIds<PS> id3 = id_at(pg + 3 * kDecodeWaves);
             if (ok(id2)) load_page<D>(fill, layer_base, page_stride, id2, g, Hkv, lane);
             if (ok(id0)) process_page<D, E>(st, use, qb, scale_log2e, pg << 4, n_keys, lane);
             id0 = id1; id1 = id2; id2 = id3;

@@ -20,7 +20,7 @@ union MixedLds {
     DecodeLds<D> decode;
 };
 
-template <int D, class E, bool kPhasePriority>
+template <int D, class E, bool kPhasePriority, int PS>
 __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G, int32_t S,
@@ -38,13 +38,13 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
         const int32_t pos = rem / Hkv;
         const int32_t g = rem - pos * Hkv;
         const int32_t b = backwards ? (int32_t)(wgs_per_range / Hkv) - 1 - pos : pos;   // longest tiles first
-        prefill_tile<D, E, kPhasePriority>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
+        prefill_tile<D, E, kPhasePriority, PS>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
                            ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, base_slot, prefill_part, g, b,
                            (int32_t)range, max_ranges);
     } else {
         const uint32_t w = blockIdx.x - num_prefill_wgs;
         const int32_t item = w / Hkv, g = w - item * Hkv;
-        decode_item<D, ItemsInArgs, E, 2>(lds.decode, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks,
+        decode_item<D, ItemsInArgs, E, 2, PS>(lds.decode, layer_base, page_stride, num_pages, Hkv, G, block_tables, max_blocks,
                                        items, ctx_lens, cu_q_lens, q, out, scale_log2e, part_o, part_ml, item, g);
     }
 }
@@ -65,15 +65,18 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
     float* part_ml = (float*)((char*)decode_ws + w.part_ml);
     float* part_o = (float*)((char*)decode_ws + w.part_o);
     dim3 grid((uint32_t)(n_prefill + n_decode));
-#define CS_LAUNCH_MIXED(DD, PRIO)                                                                            \
-    hipLaunchKernelGGL((mixed_kernel<DD, E, PRIO>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride, \
+#define CS_LAUNCH_MIXED_P(DD, PRIO, PS)                                                                      \
+    hipLaunchKernelGGL((mixed_kernel<DD, E, PRIO, PS>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride, \
                        pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,    \
                        b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,         \
                        pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,              \
                        (uint32_t)n_prefill, (int32_t)pplan.backwards, dplan.arg_items, part_o, part_ml);
+#define CS_LAUNCH_MIXED(DD, PRIO)                                                                            \
+    if (pool.page_size == 16) { CS_LAUNCH_MIXED_P(DD, PRIO, 16) } else { CS_LAUNCH_MIXED_P(DD, PRIO, 8) }
     if (D == 128) { if (prio) { CS_LAUNCH_MIXED(128, true) } else { CS_LAUNCH_MIXED(128, false) } }
     else          { if (prio) { CS_LAUNCH_MIXED(64, true) } else { CS_LAUNCH_MIXED(64, false) } }
 #undef CS_LAUNCH_MIXED
+#undef CS_LAUNCH_MIXED_P
     return check_launch("mixed kernel");
 }
 

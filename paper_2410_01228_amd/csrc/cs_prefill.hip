@@ -6,7 +6,7 @@
 namespace cs {
 
 // grid.x = slots * Hkv, kv head fastest; grid.y = key ranges
-template <int D, class E>
+template <int D, class E, int PS>
 __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G, int32_t S,
@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t pos = blockIdx.x / Hkv;
     const int32_t g = blockIdx.x - pos * Hkv;
     const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos] : backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos;
-    prefill_tile<D, E, true>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
+    prefill_tile<D, E, true, PS>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
                        q, out, scale_log2e, range_steps, base_slot, part, g, b, blockIdx.y, gridDim.y);
 }
 
@@ -226,16 +226,14 @@ static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_bat
     const uint32_t slots = plan.n_ordered > 0 ? (uint32_t)plan.n_ordered : (uint32_t)slots64;
     dim3 grid((uint32_t)Hkv * slots, (uint32_t)plan.max_ranges);
     float* part = (float*)workspace;
-    if (D == 128)
-        hipLaunchKernelGGL((prefill_kernel<128, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
-                           pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
-                           b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
-                           plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order, (int32_t)plan.backwards);
-    else
-        hipLaunchKernelGGL((prefill_kernel<64, E>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride,
-                           pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,
-                           b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,
-                           plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order, (int32_t)plan.backwards);
+#define CS_LAUNCH_PREFILL(DD, PS)                                                                                   \
+    hipLaunchKernelGGL((prefill_kernel<DD, E, PS>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride, \
+                       pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq,                   \
+                       b.ctx_lens, b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e,                   \
+                       plan.range_steps, plan.base_slot, part, plan.n_ordered, plan.order, (int32_t)plan.backwards);
+    if (pool.page_size == 16) { if (D == 128) { CS_LAUNCH_PREFILL(128, 16) } else { CS_LAUNCH_PREFILL(64, 16) } }
+    else                      { if (D == 128) { CS_LAUNCH_PREFILL(128, 8) } else { CS_LAUNCH_PREFILL(64, 8) } }
+#undef CS_LAUNCH_PREFILL
     if (plan.max_ranges > 1) launch_merge_as<E>(pool, b, plan, out, Hq, workspace, st);
     return check_launch("prefill kernels");
 }

@@ -76,6 +76,28 @@ __device__ __forceinline__ void lds_dma16_two_pages(const void* base_a, const vo
                  :: "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0", "scc");
 }
 
+// The same for pages of 8 tokens: the run's lanes read from four pages, lane set j (of four)
+// from bases[j] + off.  mask_0 selects set 0 and set j is mask_0 << (j * kShift): the K runs
+// interleave the pages in groups of 4 lanes (kShift 4), the V runs in groups of 16 (kShift 16).
+template <int kShift>
+__device__ __forceinline__ void lds_dma16_four_pages(const void* base_0, const void* base_1, const void* base_2,
+                                                     const void* base_3, uint32_t off, uint64_t mask_0,
+                                                     void* dst_wave_base) {
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_base;
+    asm volatile("s_mov_b32 m0, %0\n\t"
+                 "s_mov_b64 exec, %6\n\t"
+                 "global_load_lds_dwordx4 %1, %2\n\t"
+                 "s_lshl_b64 exec, exec, %7\n\t"
+                 "global_load_lds_dwordx4 %1, %3\n\t"
+                 "s_lshl_b64 exec, exec, %7\n\t"
+                 "global_load_lds_dwordx4 %1, %4\n\t"
+                 "s_lshl_b64 exec, exec, %7\n\t"
+                 "global_load_lds_dwordx4 %1, %5\n\t"
+                 "s_mov_b64 exec, -1"
+                 :: "s"(lds_addr), "v"(off), "s"(base_0), "s"(base_1), "s"(base_2), "s"(base_3), "s"(mask_0), "n"(kShift)
+                 : "memory", "m0", "scc");
+}
+
 // max(a, b, c) in one instruction.  fmaxf() makes the compiler canonicalise every operand
 // first (one extra v_max per value, to quiet signalling NaNs); the scores need no such care.
 __device__ __forceinline__ float max3(float a, float b, float c) {
@@ -110,7 +132,7 @@ struct PrefillLds {
 // leaving a partial).  `lds` is the workgroup's own.  kPhasePriority: the wavefront alternates
 // its issue priority between the halves of an iteration (for grids whose other wavefronts are
 // mostly tiles too; beside a decode load of equal weight it costs more than it gains).
-template <int D, class E, bool kPhasePriority>
+template <int D, class E, bool kPhasePriority, int PS>
 __device__ __forceinline__ void prefill_tile(
     PrefillLds<D>& lds,
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -124,7 +146,8 @@ __device__ __forceinline__ void prefill_tile(
     constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block of a page
     constexpr int kStepUnits = 2 * kUnits;            // K (or V) units of one step (two pages)
     constexpr int kLoads = kStepUnits / kPrefillThreads;   // 16-byte loads per lane, for K and for V
-    constexpr int kStepLoads = 4 * kLoads;            // LDS-DMA instructions per wavefront and step
+    constexpr int kStepPages = kKeysPerStep / PS;     // pages of one step: 2 (of 16 tokens) or 4 (of 8)
+    constexpr int kStepLoads = 2 * kStepPages * kLoads;   // LDS-DMA instructions per wavefront and step
     constexpr int kPartRow = D + 4;                   // floats per query row of a partial: D outputs, max, sum, pad
     auto& lds_k = lds.k;
     auto& lds_v = lds.v;
@@ -155,7 +178,7 @@ __device__ __forceinline__ void prefill_tile(
     const int32_t step_begin = range * range_steps;
     if (step_begin >= n_steps) return;
     const int32_t step_end = min(n_steps, step_begin + range_steps);
-    const int32_t n_pages = min((n_seq_keys + kPage - 1) >> 4, max_blocks);
+    const int32_t n_pages = min((n_seq_keys + PS - 1) / PS, max_blocks);
     const int32_t* table = block_tables + (int64_t)s * max_blocks;
     const int32_t Hq = Hkv * G;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -206,31 +229,34 @@ __device__ __forceinline__ void prefill_tile(
     // steady state has no scalar-memory load (whose unordered return would turn every LDS wait
     // into a full lgkmcnt(0)) and no 64-bit multiply.  The registers are refilled once per 32
     // steps; a page the sequence does not have (or a bad id) reads as page 0.
-    int32_t idbase = (2 * step_begin) & ~63;
+    int32_t idbase = (kStepPages * step_begin) & ~63;
     uint32_t pgoff_lo, pgoff_hi;
     auto load_window = [&]() {
         const int32_t id = idbase + lane < n_pages ? table[idbase + lane] : 0;
         const uint64_t off = ((uint64_t)((id < 0 || id >= num_pages) ? 0 : id) * (uint64_t)page_stride
-                              + (uint64_t)g * (kPage * D)) * 2;
+                              + (uint64_t)g * (PS * D)) * 2;
         pgoff_lo = (uint32_t)off;
         pgoff_hi = (uint32_t)(off >> 32);
         asm volatile("" : "+v"(pgoff_lo), "+v"(pgoff_hi));   // take the load's wait here, not at every readlane
     };
     load_window();
-    struct StepPages { const char* a; const char* b; };
-    auto step_pages = [&](int32_t step) -> StepPages {  // wave-uniform addresses of the step's two pages
-        if (2 * step - idbase >= 64) {                   // steps only ever grow
+    struct StepPages { const char* p[kStepPages]; };
+    auto step_pages = [&](int32_t step) -> StepPages {  // wave-uniform addresses of the step's pages
+        if (kStepPages * step - idbase >= 64) {          // steps only ever grow
             idbase += 64;
             load_window();
         }
-        const int j = 2 * step - idbase;
-        // (readlane returns a signed int: widen through uint32_t or the low half's sign bit
-        // would smear over the high half)
-        const uint64_t oa = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_hi, j) << 32)
-                          | (uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_lo, j);
-        const uint64_t ob = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_hi, j + 1) << 32)
-                          | (uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_lo, j + 1);
-        return StepPages{ (const char*)layer_base + oa, (const char*)layer_base + ob };
+        const int j = kStepPages * step - idbase;
+        StepPages pg;
+#pragma unroll
+        for (int e = 0; e < kStepPages; ++e) {
+            // (readlane returns a signed int: widen through uint32_t or the low half's sign bit
+            // would smear over the high half)
+            const uint64_t o = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_hi, j + e) << 32)
+                             | (uint64_t)(uint32_t)__builtin_amdgcn_readlane(pgoff_lo, j + e);
+            pg.p[e] = (const char*)layer_base + o;
+        }
+        return pg;
     };
     // LDS arrangement of a step (two pages A, B; 32 keys), chosen so that every operand read
     // below is linear in the lane id (b128, conflict-free):
@@ -247,21 +273,30 @@ __device__ __forceinline__ void prefill_tile(
     for (int r = 0; r < kLoads; ++r) {
         const int unit0 = (r * kPrefillWaves + wave) * 64;
         const int kk = unit0 >> 7, tile = (unit0 >> 6) & 1, kg = lane >> 4, row = lane & 15;
-        const int tok = ((row >> 2) & 1) * 8 + (row & 3) + 4 * tile;
-        k_off[r] = (uint32_t)(((kk * 4 + kg) * 16 + tok) * 16);
+        // pages of 8 tokens: the half is a page of its own (a K feature block holds 8 units, a V
+        // feature tile one group of 16)
+        const int tok = (PS == 16 ? ((row >> 2) & 1) * 8 : 0) + (row & 3) + 4 * tile;
+        k_off[r] = (uint32_t)(((kk * 4 + kg) * PS + tok) * 16);
         const int dt = unit0 >> 6, half = (lane >> 4) & 1, f = lane & 15;
-        v_off_lane[r] = (uint32_t)(((dt * 2 + half) * 16 + f) * 16);
+        v_off_lane[r] = (uint32_t)(PS == 16 ? ((dt * 2 + half) * 16 + f) * 16 : (dt * 16 + f) * 16);
     }
     auto dma_step = [&](int32_t step, StepPages pg) {
         const uint32_t slot = (uint32_t)step % kRing;
-        const int64_t v_blk = (int64_t)Hkv * (kPage * D) * 2;             // K block -> V block of a page, bytes
+        const int64_t v_blk = (int64_t)Hkv * (PS * D) * 2;                // K block -> V block of a page, bytes
 #pragma unroll
         for (int r = 0; r < kLoads; ++r) {
             const int unit0 = (r * kPrefillWaves + wave) * 64;            // wave-uniform
-            // K rows 0..7 of a tile come from the first page, rows 8..15 from the second
-            lds_dma16_two_pages(pg.a, pg.b, k_off[r], 0x00ff00ff00ff00ffull, &lds_k[slot][unit0]);
-            // V lanes 0..31 hold the first page's two halves, lanes 32..63 the second page's
-            lds_dma16_two_pages(pg.a + v_blk, pg.b + v_blk, v_off_lane[r], 0x00000000ffffffffull, &lds_v[slot][unit0]);
+            if constexpr (PS == 16) {
+                // K rows 0..7 of a tile come from the first page, rows 8..15 from the second
+                lds_dma16_two_pages(pg.p[0], pg.p[1], k_off[r], 0x00ff00ff00ff00ffull, &lds_k[slot][unit0]);
+                // V lanes 0..31 hold the first page's two halves, lanes 32..63 the second page's
+                lds_dma16_two_pages(pg.p[0] + v_blk, pg.p[1] + v_blk, v_off_lane[r], 0x00000000ffffffffull, &lds_v[slot][unit0]);
+            } else {
+                // K rows 4j..4j+3 of a tile come from page j of the step, V lanes 16j..16j+15 too
+                lds_dma16_four_pages<4>(pg.p[0], pg.p[1], pg.p[2], pg.p[3], k_off[r], 0x000f000f000f000full, &lds_k[slot][unit0]);
+                lds_dma16_four_pages<16>(pg.p[0] + v_blk, pg.p[1] + v_blk, pg.p[2] + v_blk, pg.p[3] + v_blk, v_off_lane[r],
+                                         0x000000000000ffffull, &lds_v[slot][unit0]);
+            }
         }
     };
 

@@ -27,6 +27,7 @@ class Shape:
     Hkv: int
     D: int
     L: int = 1
+    page_size: int = PAGE          # tokens per page: 16 (the paper's) or 8
 
     @property
     def G(self):
@@ -38,7 +39,7 @@ class Shape:
 
     @property
     def page_elems(self):
-        return 2 * self.Hkv * PAGE * self.D
+        return 2 * self.Hkv * self.page_size * self.D
 
 
 @dataclass
@@ -63,7 +64,8 @@ class Batch:
         return int(self.cu_q_lens[-1])
 
     def blocks_needed(self):
-        return (self.ctx_lens + self.q_lens + PAGE - 1) // PAGE
+        ps = self.shape.page_size
+        return (self.ctx_lens + self.q_lens + ps - 1) // ps
 
 
 def generator(index: int, device="cpu") -> torch.Generator:
@@ -100,7 +102,8 @@ def make_batch(shape: Shape, ctx_lens, q_lens, gen, num_pages: Optional[int] = N
     ctx_lens = torch.as_tensor(ctx_lens, dtype=torch.int32)
     q_lens = torch.as_tensor(q_lens, dtype=torch.int32)
     S = ctx_lens.numel()
-    need = ((ctx_lens + q_lens + PAGE - 1) // PAGE).to(torch.int64)
+    ps = shape.page_size
+    need = ((ctx_lens + q_lens + ps - 1) // ps).to(torch.int64)
     total = int(need.sum())
     if num_pages is None:
         num_pages = total + spare
@@ -119,13 +122,14 @@ def make_batch(shape: Shape, ctx_lens, q_lens, gen, num_pages: Optional[int] = N
 
 
 def newly_filled_pages(batch: Batch) -> List[int]:
-    """Page ids whose 16th slot is written this step (a page is checkpointed once it is
+    """Page ids whose last slot is written this step (a page is checkpointed once it is
     full and therefore immutable; Sec. 4.4 and Sec. 5), in sequence then block order."""
     out = []
+    ps = batch.shape.page_size
     for s in range(batch.S):
         c, q = int(batch.ctx_lens[s]), int(batch.q_lens[s])
-        for b in range((c + q) // PAGE):
-            last_slot = b * PAGE + PAGE - 1
+        for b in range((c + q) // ps):
+            last_slot = b * ps + ps - 1
             if c <= last_slot < c + q:
                 out.append(int(batch.block_tables[s, b]))
     return out
@@ -146,18 +150,18 @@ def config_tiny(gen=None) -> Batch:
     return b
 
 
-def config_llama8b_decode(gen=None, shrink: int = 1) -> Batch:
+def config_llama8b_decode(gen=None, shrink: int = 1, page_size: int = PAGE) -> Batch:
     """Workload 1: 32/8 heads, D 128; 256 decodes, context uniform in [512, 4096]."""
     gen = gen or generator(1)
     S = max(1, 256 // shrink)
     ctx = uniform_int(512 // shrink, 4096 // shrink, S, gen)
-    b = make_batch(Shape(32, 8, 128), ctx, torch.ones(S, dtype=torch.int32), gen,
+    b = make_batch(Shape(32, 8, 128, page_size=page_size), ctx, torch.ones(S, dtype=torch.int32), gen,
                    name="llama3.1-8b-decode256")
     b.extra["n_online"] = S
     return b
 
 
-def config_qwen7b_mixed(gen=None, shrink: int = 1) -> Batch:
+def config_qwen7b_mixed(gen=None, shrink: int = 1, page_size: int = PAGE) -> Batch:
     """Workload 2: 28/4 heads, D 128; 64 decodes with context uniform in [1024, 8192] plus
     4 prefill chunks of 512 tokens with prior context uniform in [0, 16384]."""
     gen = gen or generator(2)
@@ -165,19 +169,19 @@ def config_qwen7b_mixed(gen=None, shrink: int = 1) -> Batch:
     ctx_d = uniform_int(1024 // shrink, 8192 // shrink, S, gen)
     ctx_p = uniform_int(0, 16384 // shrink, 4, gen)
     chunk = max(16, 512 // shrink)
-    b = make_batch(Shape(28, 4, 128), torch.cat([ctx_d, ctx_p]),
+    b = make_batch(Shape(28, 4, 128, page_size=page_size), torch.cat([ctx_d, ctx_p]),
                    [1] * S + [chunk] * 4, gen, name="qwen2.5-7b-mixed")
     b.extra["n_online"] = S
     return b
 
 
-def config_llama70b_long(gen=None, shrink: int = 1) -> Batch:
+def config_llama70b_long(gen=None, shrink: int = 1, page_size: int = PAGE) -> Batch:
     """Workload 3: 64/8 heads, D 128; 128 decodes with context log-uniform in
     [2048, 32768] plus one prefill chunk of 1024 tokens at prior context 30720."""
     gen = gen or generator(3)
     S = max(1, 128 // shrink)
     ctx_d = log_uniform_int(2048 // shrink, 32768 // shrink, S, gen)
-    b = make_batch(Shape(64, 8, 128), torch.cat([ctx_d, torch.tensor([30720 // shrink], dtype=torch.int32)]),
+    b = make_batch(Shape(64, 8, 128, page_size=page_size), torch.cat([ctx_d, torch.tensor([30720 // shrink], dtype=torch.int32)]),
                    [1] * S + [max(16, 1024 // shrink)], gen, name="llama3.1-70b-long-mixed")
     b.extra["n_online"] = S
     return b

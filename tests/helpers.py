@@ -43,15 +43,16 @@ class Step:
     def prior_pool(self, L=None, fill=NAN_BITS) -> np.ndarray:
         """CPU pool holding only the prior context (written with the oracle's append)."""
         b, sh = self.b, self.b.shape
-        pool = kv_layout.new_pool(L or sh.L, b.num_pages, sh.Hkv, sh.D, fill)
+        pool = kv_layout.new_pool(L or sh.L, b.num_pages, sh.Hkv, sh.D, fill, page_size=sh.page_size)
         kv_layout.ref_append(pool, self.layer, b.block_tables.numpy(), np.zeros(b.S, np.int32),
-                             self.cu_ctx.numpy(), bits(self.k_prior), bits(self.v_prior))
+                             self.cu_ctx.numpy(), bits(self.k_prior), bits(self.v_prior), page_size=sh.page_size)
         return pool
 
     def oracle_append(self, pool: np.ndarray) -> np.ndarray:
         b = self.b
         return kv_layout.ref_append(pool, self.layer, b.block_tables.numpy(), b.ctx_lens.numpy(),
-                                    b.cu_q_lens.numpy(), bits(self.k_new), bits(self.v_new))
+                                    b.cu_q_lens.numpy(), bits(self.k_new), bits(self.v_new),
+                                    page_size=b.shape.page_size)
 
     def logical(self, s: int):
         """float32 logical K, V of sequence s including this step's tokens."""

@@ -15,7 +15,8 @@ def run_step(batch, seed, q_gain=1.0, split=0, check_append=True, dtype=torch.bf
     st = Step(batch, seed, q_gain=q_gain, dtype=dtype)
     sh = batch.shape
     cpu_pool = st.prior_pool()
-    pool = cs.Pool(from_bits(cpu_pool, "cuda", dtype), cpu_pool.shape[0], cpu_pool.shape[1], sh.Hkv, sh.D)
+    pool = cs.Pool(from_bits(cpu_pool, "cuda", dtype), cpu_pool.shape[0], cpu_pool.shape[1], sh.Hkv, sh.D,
+                   page_size=sh.page_size)
     attend = cs.cs_paged_attention_mixed if dtype == torch.bfloat16 else cs.cs_paged_attention_mixed_f16
     bb = cs.Batch(batch.block_tables, batch.ctx_lens, batch.cu_q_lens)
     cs.cs_kv_append(pool, 0, bb, st.k_new.cuda(), st.v_new.cuda())

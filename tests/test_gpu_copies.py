@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 def _dev_pool(np_pool, sh, L=None):
     t = from_bits(np_pool, "cuda")
-    return cs.Pool(t, L or np_pool.shape[0], np_pool.shape[1], sh.Hkv, sh.D)
+    return cs.Pool(t, L or np_pool.shape[0], np_pool.shape[1], sh.Hkv, sh.D, page_size=sh.page_size)
 
 
 def _run_append_case(batch, seed):

@@ -1,0 +1,242 @@
+"""GPU parity of every entry point on pools whose pages hold 8 tokens instead of 16: the copies
+bit-exact, the attention within the same bar as everywhere else.  The attention kernels then
+take two (decode) or four (prefill) table entries per step, so the cases sit on and around
+multiples of 8, 16 and 32 keys."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_layout
+from paper_2410_01228_amd import binding as cs
+from paper_2410_01228_amd import synth
+from helpers import Step, assert_attention_close, bits, from_bits
+from test_gpu_attention import run_step
+
+pytestmark = pytest.mark.gpu
+
+
+def shape8(Hq, Hkv, D, L=1):
+    return synth.Shape(Hq, Hkv, D, L, page_size=8)
+
+
+def _append_case(batch, seed):
+    st = Step(batch, seed)
+    sh = batch.shape
+    cpu_pool = st.prior_pool()
+    assert cpu_pool.shape[-1] == 8 * sh.D
+    pool = cs.Pool(from_bits(cpu_pool, "cuda"), 1, batch.num_pages, sh.Hkv, sh.D, page_size=8)
+    bb = cs.Batch(batch.block_tables, batch.ctx_lens, batch.cu_q_lens)
+    cs.cs_kv_append(pool, 0, bb, st.k_new.cuda(), st.v_new.cuda())
+    torch.cuda.synchronize()
+    st.oracle_append(cpu_pool)
+    np.testing.assert_array_equal(bits(pool.tensor), cpu_pool)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(6, 3, 64), (32, 8, 128), (4, 1, 128)])
+def test_append_page_boundaries(Hq, Hkv, D):
+    # single tokens that complete a page (7 mod 8) or open one (0 mod 8); chunks that start and
+    # end anywhere inside a page, cover one page, many pages; an idle sequence
+    sh = shape8(Hq, Hkv, D)
+    g = synth.generator(111)
+    b = synth.make_batch(sh, [7, 8, 15, 16, 0, 5, 47, 1, 9, 3, 24], [1, 1, 1, 1, 17, 0, 33, 15, 7, 2, 8], g, spare=3)
+    _append_case(b, 111)
+
+
+def test_append_long_chunks_and_decodes():
+    sh = shape8(28, 4, 128)
+    g = synth.generator(112)
+    ctx = [int(x) for x in synth.uniform_int(0, 900, 24, g)] + [0, 333, 1000]
+    ql = [1] * 24 + [512, 256, 100]
+    _append_case(synth.make_batch(sh, ctx, ql, g, spare=2), 112)
+
+
+@pytest.mark.parametrize("L,P,Hkv,D,n,lrange,strided", [
+    (3, 40, 8, 128, 17, (0, 3), False),      # 32 KiB pages
+    (2, 21, 3, 64, 21, (0, 2), True),        # 6 KiB pages, padded strides
+    (4, 33, 1, 64, 5, (1, 3), False),        # 2 KiB pages
+])
+def test_gather_restore_and_token_copies(L, P, Hkv, D, n, lrange, strided):
+    rng = np.random.default_rng(L * 1000 + P)
+    pe = kv_layout.page_elems(Hkv, D, 8)
+    ps = pe + 64 if strided else pe
+    ls = P * ps + (128 if strided else 0)
+    flat = rng.integers(0, 2 ** 16, size=L * ls, dtype=np.uint16)
+    dev = from_bits(flat, "cuda")
+    pool = cs.Pool(dev, L, P, Hkv, D, layer_stride=ls, page_stride=ps, page_size=8)
+    assert cs.cs_pool_page_bytes(pool) == pe * 2
+
+    def view(a):
+        return np.lib.stride_tricks.as_strided(a, (L, P, pe), (ls * 2, ps * 2, 2))
+
+    ids = rng.permutation(P)[:n].astype(np.int32)
+    l0, l1 = lrange
+    staging = torch.full(((l1 - l0), n, pe), -1.0, dtype=torch.bfloat16, device="cuda")
+    cs.cs_kv_ckpt_gather(pool, l0, l1, torch.from_numpy(ids).cuda(), staging)
+    torch.cuda.synchronize()
+    cpu = view(flat).reshape(L, P, 2, Hkv, 8 * D).copy()
+    want = kv_layout.ref_gather(cpu, l0, l1, ids)
+    np.testing.assert_array_equal(bits(staging), want)
+    dst = rng.permutation(P)[:n].astype(np.int32)
+    cs.cs_kv_ckpt_restore(pool, l0, l1, torch.from_numpy(dst).cuda(), staging)
+    torch.cuda.synchronize()
+    kv_layout.ref_restore(cpu, l0, l1, dst, want)
+    expect_flat = flat.copy()
+    view(expect_flat)[...] = cpu.reshape(L, P, pe)
+    np.testing.assert_array_equal(bits(dev), expect_flat)
+    # token-granular: slots are page * 8 + t
+    m = min(P * 8, 7 * n + 3)
+    slots = rng.permutation(P * 8)[:m].astype(np.int32)
+    tok = torch.full(((l1 - l0), m, 2, Hkv, D), -1.0, dtype=torch.bfloat16, device="cuda")
+    cs.cs_kv_ckpt_gather_tokens(pool, l0, l1, torch.from_numpy(slots).cuda(), tok)
+    torch.cuda.synchronize()
+    want_tok = kv_layout.ref_gather_tokens(cpu, l0, l1, slots, page_size=8)
+    np.testing.assert_array_equal(bits(tok), want_tok)
+    dst_slots = rng.permutation(P * 8)[:m].astype(np.int32)
+    cs.cs_kv_ckpt_restore_tokens(pool, l0, l1, torch.from_numpy(dst_slots).cuda(), tok)
+    torch.cuda.synchronize()
+    kv_layout.ref_restore_tokens(cpu, l0, l1, dst_slots, want_tok, page_size=8)
+    view(expect_flat)[...] = cpu.reshape(L, P, pe)
+    np.testing.assert_array_equal(bits(dev), expect_flat)
+
+
+def test_other_page_sizes_are_refused():
+    for ps in (4, 32, 0):
+        pool = cs.Pool(torch.empty(2 * 2 * max(ps, 1) * 64 * 4, dtype=torch.bfloat16, device="cuda"), 1, 4, 2, 64, page_size=ps)
+        with pytest.raises(cs.CsError) as e:
+            cs.cs_kv_ckpt_gather(pool, 0, 1, torch.zeros(1, dtype=torch.int32, device="cuda"),
+                                 torch.empty(2 * 2 * 16 * 64, dtype=torch.bfloat16, device="cuda"))
+        assert e.value.status == cs.CS_ERR_UNSUPPORTED
+        assert cs.cs_pool_page_bytes(pool) == 0
+
+
+def test_batch_longer_than_its_block_table_is_refused():
+    # 5 entries of 8 tokens hold 40 keys: context 39 plus one new token fits, 40 plus one does not
+    sh = shape8(4, 2, 64)
+    pool = cs.Pool.empty(1, 8, sh.Hkv, sh.D, page_size=8)
+    bt = torch.arange(5, dtype=torch.int32).reshape(1, 5)
+    new = torch.zeros((1, sh.Hkv, sh.D), dtype=torch.bfloat16, device="cuda")
+    ok = cs.Batch(bt, torch.tensor([39], dtype=torch.int32), torch.tensor([0, 1], dtype=torch.int32))
+    cs.cs_kv_append(pool, 0, ok, new, new)
+    bad = cs.Batch(bt, torch.tensor([40], dtype=torch.int32), torch.tensor([0, 1], dtype=torch.int32))
+    with pytest.raises(cs.CsError) as e:
+        cs.cs_kv_append(pool, 0, bad, new, new)
+    assert e.value.status == cs.CS_ERR_INVALID_ARG
+    torch.cuda.synchronize()
+
+
+def decode_batch(sh, ctxs, seed, spare=0):
+    return synth.make_batch(sh, ctxs, [1] * len(ctxs), synth.generator(seed), spare=spare)
+
+
+@pytest.mark.parametrize("split,ahead", [(0, 0), (16, 1), (16, 2), (64, 1), (64, 2)])
+def test_decode_small_contexts(split, ahead):
+    # n = ctx + 1 on and around multiples of 8 and 16: the second page of a step present, absent,
+    # holding one key
+    sh = shape8(4, 2, 64)
+    b = decode_batch(sh, [0, 1, 6, 7, 8, 9, 14, 15, 16, 17, 22, 23, 24, 31, 32, 100, 63, 40, 255, 256, 263, 300], 121)
+    out, st, _, _ = run_step(b, 121, split=split, ahead=ahead)
+    assert_attention_close(out, st.oracle_attention(), "page 8 decode small split=%d ahead=%d" % (split, ahead))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(32, 8, 128), (28, 4, 128), (64, 8, 128), (16, 1, 64), (6, 6, 128)])
+def test_decode_group_sizes(Hq, Hkv, D):
+    sh = shape8(Hq, Hkv, D)
+    b = decode_batch(sh, [700, 33, 1024, 257, 511, 1015], 122)
+    out, st, _, _ = run_step(b, 122, split=256)
+    assert_attention_close(out, st.oracle_attention(), "page 8 decode G=%d D=%d" % (Hq // Hkv, D))
+
+
+@pytest.mark.parametrize("S,split", [(881, 0), (300, 64)])
+def test_decode_item_list_sources(S, split):
+    # item list in the kernel arguments, built on the device, and one item per sequence
+    sh = shape8(8, 2, 128)
+    g = synth.generator(123)
+    b = decode_batch(sh, [int(x) for x in synth.uniform_int(0, 200, S, g)], 123)
+    out, st, _, _ = run_step(b, 123, split=split, check_append=False)
+    assert_attention_close(out, st.oracle_attention(), "page 8 decode S=%d split=%d" % (S, split))
+
+
+@pytest.mark.parametrize("Hq,Hkv,D", [(4, 2, 64), (32, 8, 128), (28, 4, 128), (16, 1, 64), (3, 3, 128)])
+def test_prefill_chunks_ragged(Hq, Hkv, D):
+    sh = shape8(Hq, Hkv, D)
+    b = synth.make_batch(sh, [0, 48, 17, 255, 5, 100, 8, 24], [32, 32, 50, 77, 2, 129, 9, 40], synth.generator(131))
+    out, st, _, _ = run_step(b, 131)
+    assert_attention_close(out, st.oracle_attention(), "page 8 prefill ragged %d/%d/%d" % (Hq, Hkv, D))
+
+
+def test_prefill_first_row_is_v0_exactly():
+    sh = shape8(4, 2, 64)
+    b = synth.make_batch(sh, [0], [40], synth.generator(132))
+    out, st, _, _ = run_step(b, 132)
+    for h in range(sh.Hq):
+        assert torch.equal(out[0, h].cpu(), st.v_new[0, h // sh.G])
+
+
+@pytest.mark.parametrize("fuse", [2, 0])
+def test_mixed_batch_fused_and_separate(fuse):
+    # chunks, decode tokens and idle sequences in any order; a context long enough that the
+    # prefill kernel refills its window of page addresses (every 512 keys) several times
+    sh = shape8(8, 2, 128)
+    b = synth.make_batch(sh, [700, 30, 0, 0, 99, 15, 2000, 64, 1100], [40, 1, 33, 0, 1, 1, 64, 300, 1],
+                         synth.generator(134))
+    out, st, _, _ = run_step(b, 134, fuse=fuse)
+    active = [s for s in range(b.S) if int(b.q_lens[s]) > 0]
+    assert_attention_close(out, st.oracle_attention(active), "page 8 mixed fuse=%d" % fuse)
+
+
+@pytest.mark.parametrize("Hq,Hkv,D,gain", [(8, 2, 128, 1.0), (28, 4, 128, 1.0), (16, 1, 64, 6.0)])
+def test_prefill_key_range_split(Hq, Hkv, D, gain):
+    sh = shape8(Hq, Hkv, D)
+    b = synth.make_batch(sh, [3000, 1501, 0, 4100], [40, 17, 33, 1], synth.generator(161))
+    out, st, _, _ = run_step(b, 161, q_gain=gain)
+    assert_attention_close(out, st.oracle_attention(), "page 8 prefill split %d/%d/%d" % (Hq, Hkv, D))
+
+
+def test_f16():
+    sh = shape8(8, 2, 128)
+    b = synth.make_batch(sh, [700, 30, 0, 99, 1500], [40, 1, 33, 1, 1], synth.generator(135))
+    out, st, _, _ = run_step(b, 135, dtype=torch.float16, split=64)
+    assert_attention_close(out, st.oracle_attention(), "page 8 f16")
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_random_mixed_batches(seed):
+    rnd = random.Random(5000 + seed)
+    D = rnd.choice([64, 128])
+    Hkv = rnd.choice([1, 2, 3, 4, 8])
+    G = rnd.choice([1, 2, 4, 5, 7, 8, 16])
+    sh = shape8(Hkv * G, Hkv, D)
+    S = rnd.randint(1, 10)
+    ctx, ql = [], []
+    for _ in range(S):
+        kind = rnd.choice(["decode", "decode", "chunk", "chunk", "idle"])
+        c = rnd.choice([0, 1, 7, 8, 9, 15, 16, 17, 31, 32, rnd.randint(0, 700), rnd.randint(0, 2500)])
+        ctx.append(c)
+        ql.append(1 if kind == "decode" else 0 if kind == "idle" else rnd.choice([2, 8, 16, 17, rnd.randint(2, 150)]))
+    if sum(ql) == 0:
+        ql[0] = 1
+    b = synth.make_batch(sh, ctx, ql, synth.generator(6000 + seed), spare=rnd.randint(0, 5))
+    split = rnd.choice([0, 0, 64, 256])
+    dtype = rnd.choice([torch.bfloat16, torch.bfloat16, torch.float16])
+    fuse = rnd.choice([2, 1, 0])
+    ahead = rnd.choice([0, 1, 2])
+    out, st, _, _ = run_step(b, 6000 + seed, split=split, dtype=dtype, fuse=fuse, ahead=ahead)
+    active = [s for s in range(S) if ql[s] > 0]
+    assert_attention_close(out, st.oracle_attention(active),
+                           "page 8 random seed %d: %d/%d/%d ctx %s q %s split %d %s" % (seed, sh.Hq, Hkv, D, ctx, ql, split, dtype))
+
+
+def test_page_size_changes_no_bit_of_the_output():
+    """The same logical batch in a pool of 16-token pages and in one of 8-token pages: the
+    kernels bring the same operands to the same instructions, so the outputs agree bit for bit."""
+    for (Hq, Hkv, D) in [(8, 2, 128), (4, 2, 64)]:
+        ctx, ql = [700, 30, 0, 99, 15, 1100, 263], [40, 1, 33, 1, 1, 1, 17]
+        outs = []
+        for ps in (16, 8):
+            sh = synth.Shape(Hq, Hkv, D, page_size=ps)
+            b = synth.make_batch(sh, ctx, ql, synth.generator(140))
+            out, _, _, _ = run_step(b, 141)
+            outs.append(out)
+        assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))

@@ -239,3 +239,81 @@ def test_token_gather_layer_range():
 def test_bf16_widening_is_exact():
     x = synth.randn_bf16((1000,), synth.generator(9))
     np.testing.assert_array_equal(kv_layout.bf16_bits_to_f32(bits(x)), x.float().numpy())
+
+
+# ---- pages of 8 tokens ------------------------------------------------------------------
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_page8_format_is_a_bijection_with_the_stated_units(D):
+    t, d = np.meshgrid(np.arange(8), np.arange(D), indexing="ij")
+    ki = kv_layout.k_index(t, d, D, page_size=8)
+    vi = kv_layout.v_index(t, d, D, page_size=8)
+    assert sorted(ki.ravel()) == list(range(8 * D))
+    assert sorted(vi.ravel()) == list(range(8 * D))
+    # K: 8 features of a token adjacent, the 8 tokens of a feature block adjacent, blocks 64 apart
+    assert np.all(ki[:, 1:8] - ki[:, 0:7] == 1)
+    assert np.all(ki[1:, 0] - ki[:-1, 0] == 8)
+    assert np.all(ki[:, 8:] - ki[:, :-8] == 64)
+    # V: the 8 tokens of a feature adjacent, features 8 apart: feature d starts at element 8 d
+    assert np.all(vi[1:, :] - vi[:-1, :] == 1)
+    assert np.all(vi[0, :] == 8 * np.arange(D))
+
+
+@pytest.mark.parametrize("D", [64, 128])
+def test_a_page_of_16_is_two_pages_of_8_interleaved_by_16_byte_units(D):
+    """Tokens 0..7 in page A and 8..15 in page B (8 tokens each) against the same 16 tokens in
+    one page P: every K feature block of P is A's block followed by B's, every V feature tile of
+    P is A's tile followed by B's -- the fact the attention kernels lean on when they put two
+    small pages where one page of 16 would be."""
+    rng = np.random.default_rng(D)
+    k = rng.integers(0, 2 ** 16, size=(16, 1, D), dtype=np.uint16)
+    v = rng.integers(0, 2 ** 16, size=(16, 1, D), dtype=np.uint16)
+    big = kv_layout.new_pool(1, 1, 1, D, 0)
+    kv_layout.ref_append(big, 0, np.array([[0]]), np.array([0]), np.array([0, 16]), k, v)
+    small = kv_layout.new_pool(1, 2, 1, D, 0, page_size=8)
+    kv_layout.ref_append(small, 0, np.array([[1, 0]]), np.array([0]), np.array([0, 16]), k, v, page_size=8)
+    A, B = small[0, 1], small[0, 0]                                  # [2, 1, 8*D]
+    Pk = big[0, 0, 0, 0].reshape(D // 8, 2, 64)                      # [feature block][token half][8 tokens x 8]
+    np.testing.assert_array_equal(Pk[:, 0], A[0, 0].reshape(D // 8, 64))
+    np.testing.assert_array_equal(Pk[:, 1], B[0, 0].reshape(D // 8, 64))
+    Pv = big[0, 0, 1, 0].reshape(D // 16, 2, 128)                    # [feature tile][token half][16 x 8 tokens]
+    np.testing.assert_array_equal(Pv[:, 0], A[1, 0].reshape(D // 16, 128))
+    np.testing.assert_array_equal(Pv[:, 1], B[1, 0].reshape(D // 16, 128))
+
+
+def test_page8_append_reads_back_and_token_copies_invert():
+    sh = synth.Shape(4, 2, 64, page_size=8)
+    g = synth.generator(21)
+    b = synth.make_batch(sh, [7, 8, 23, 0, 5, 40], [1, 1, 1, 17, 0, 9], g, spare=6)
+    assert [int(x) for x in b.blocks_needed()] == [1, 2, 3, 3, 1, 7]
+    k_new = bits(synth.randn_bf16((b.T, sh.Hkv, sh.D), g))
+    v_new = bits(synth.randn_bf16((b.T, sh.Hkv, sh.D), g))
+    pool = kv_layout.new_pool(1, b.num_pages, sh.Hkv, sh.D, 0xDEAD, page_size=8)
+    assert pool.shape[-1] == 8 * sh.D and kv_layout.page_elems(sh.Hkv, sh.D, 8) == sh.page_elems
+    before = pool.copy()
+    bt = b.block_tables.numpy()
+    kv_layout.ref_append(pool, 0, bt, b.ctx_lens.numpy(), b.cu_q_lens.numpy(), k_new, v_new, page_size=8)
+    assert (pool != before).sum() == b.T * 2 * sh.Hkv * sh.D
+    slots = []
+    for s in range(b.S):
+        c, q = int(b.ctx_lens[s]), int(b.q_lens[s])
+        for i in range(q):
+            pos, tok = c + i, int(b.cu_q_lens[s]) + i
+            page, t = int(bt[s, pos // 8]), pos % 8
+            slots.append(page * 8 + t)
+            for h in range(sh.Hkv):
+                for d in (0, 7, 8, 17, sh.D - 1):
+                    assert pool[0, page, 0, h, ((d // 8) * 8 + t) * 8 + d % 8] == k_new[tok, h, d]
+                    assert pool[0, page, 1, h, d * 8 + t] == v_new[tok, h, d]
+        K, V = kv_layout.read_logical(pool, 0, bt[s], c + q, page_size=8)
+        lo = int(b.cu_q_lens[s])
+        np.testing.assert_array_equal(K[c:], k_new[lo:lo + q])
+        np.testing.assert_array_equal(V[c:], v_new[lo:lo + q])
+    # the pages filled this step: a page is full when its 8th slot is written
+    assert synth.newly_filled_pages(b) == [int(bt[0, 0]), int(bt[2, 2]), int(bt[3, 0]), int(bt[3, 1]), int(bt[5, 5])]
+    st = kv_layout.ref_gather_tokens(pool, 0, 1, slots, page_size=8)
+    np.testing.assert_array_equal(st[0, :, 0], k_new)
+    np.testing.assert_array_equal(st[0, :, 1], v_new)
+    moved = before.copy()
+    kv_layout.ref_restore_tokens(moved, 0, 1, slots, st, page_size=8)
+    np.testing.assert_array_equal(moved, pool)
