@@ -26,14 +26,14 @@ def fill(t, gen):
         flat[o:o + n] = torch.randn(n, generator=gen, device=t.device, dtype=torch.float32).to(torch.bfloat16)
 
 
-def logical_from_pool(pool_t, layer, bt_row, n, Hkv, D):
-    """Logical K, V (float32 [n, Hkv, D]) of one sequence: pull its pages to the host with
-    plain torch indexing and undo the page format with the oracle's reader."""
-    nb = (n + 15) // 16
+def logical_from_pool(pool_t, layer, bt_row, n, Hkv, D, ps=16):
+    """Logical K, V (float32 [n, Hkv, D]) of one sequence: pull its pages (of ps tokens) to the
+    host with plain torch indexing and undo the page format with the oracle's reader."""
+    nb = (n + ps - 1) // ps
     ids = bt_row[:nb].to(torch.int64)
-    pages = pool_t[layer].index_select(0, ids.to(pool_t.device)).cpu()            # [nb, 2, Hkv, 16*D]
-    small = bits(pages).reshape(1, nb, 2, Hkv, 16 * D)
-    K, V = kv_layout.read_logical(small, 0, np.arange(nb), n)
+    pages = pool_t[layer].index_select(0, ids.to(pool_t.device)).cpu()            # [nb, 2, Hkv, ps*D]
+    small = bits(pages).reshape(1, nb, 2, Hkv, ps * D)
+    K, V = kv_layout.read_logical(small, 0, np.arange(nb), n, page_size=ps)
     return kv_layout.bf16_bits_to_f32(K), kv_layout.bf16_bits_to_f32(V)
 
 
@@ -43,10 +43,11 @@ def run_full(index, sample_seqs, rows_per_chunk=6):
 
 def run_batch(b, seed, sample_seqs, rows_per_chunk=6):
     sh = b.shape
+    ps = sh.page_size
     gen = torch.Generator(device="cuda")
     gen.manual_seed(seed)
     L_alloc = 1                                     # attention uses one layer of the pool
-    pool = cs.Pool.empty(L_alloc, b.num_pages, sh.Hkv, sh.D)
+    pool = cs.Pool.empty(L_alloc, b.num_pages, sh.Hkv, sh.D, page_size=ps)
     fill(pool.tensor, gen)
     bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
     q = synth.randn_bf16((b.T, sh.Hq, sh.D), gen, "cuda")
@@ -56,7 +57,7 @@ def run_batch(b, seed, sample_seqs, rows_per_chunk=6):
     touched = {}
     for s in sample_seqs:
         c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
-        for blk in range(c // 16, (c + ql - 1) // 16 + 1):
+        for blk in range(c // ps, (c + ql - 1) // ps + 1):
             pid = int(b.block_tables[s, blk])
             touched[pid] = bits(pool.tensor[0, pid].cpu()).copy()
     cs.cs_kv_append(pool, 0, bb, k_new, v_new)
@@ -72,17 +73,18 @@ def run_batch(b, seed, sample_seqs, rows_per_chunk=6):
         c, ql = int(b.ctx_lens[s]), int(b.q_lens[s])
         t0 = int(b.cu_q_lens[s])
         # (1) append, bit exact on every page this sequence wrote: oracle append on the snapshot
-        blks = list(range(c // 16, (c + ql - 1) // 16 + 1))
-        small = np.stack([touched[int(b.block_tables[s, blk])] for blk in blks])[None]   # [1, nb, 2, Hkv, 16D]
-        bt_local = np.full((1, (c + ql + 15) // 16), -1, np.int32)
+        blks = list(range(c // ps, (c + ql - 1) // ps + 1))
+        small = np.stack([touched[int(b.block_tables[s, blk])] for blk in blks])[None]   # [1, nb, 2, Hkv, ps*D]
+        bt_local = np.full((1, (c + ql + ps - 1) // ps), -1, np.int32)
         for j, blk in enumerate(blks):
             bt_local[0, blk] = j
-        kv_layout.ref_append(small, 0, bt_local, np.array([c]), np.array([0, ql]), kn[t0:t0 + ql], vn[t0:t0 + ql])
+        kv_layout.ref_append(small, 0, bt_local, np.array([c]), np.array([0, ql]), kn[t0:t0 + ql], vn[t0:t0 + ql],
+                             page_size=ps)
         for j, blk in enumerate(blks):
             got = bits(pool.tensor[0, int(b.block_tables[s, blk])].cpu())
             np.testing.assert_array_equal(got, small[0, j], err_msg="append, seq %d block %d" % (s, blk))
         # (2) attention on sampled rows, from logical K/V read back through the block table
-        K, V = logical_from_pool(pool.tensor, 0, b.block_tables[s], c + ql, sh.Hkv, sh.D)
+        K, V = logical_from_pool(pool.tensor, 0, b.block_tables[s], c + ql, sh.Hkv, sh.D, ps)
         np.testing.assert_array_equal(K[c:], kv_layout.bf16_bits_to_f32(kn[t0:t0 + ql]))
         rows = sorted(set([0, ql - 1] + list(np.random.default_rng(s).integers(0, ql, rows_per_chunk)))) if ql > 1 else [0]
         ref = attention.attention_rows(qf[[t0 + r for r in rows]], np.array([c + r for r in rows]), K, V, sh.scale)
@@ -110,6 +112,19 @@ def test_llama70b_long_full_size():
     b = synth.config_llama70b_long()
     order = np.argsort(b.ctx_lens[:128].numpy())
     run_full(3, [int(order[0]), int(order[-1]), 77, 128], rows_per_chunk=4)
+
+
+def test_model_shapes_with_pages_of_8_tokens():
+    """The three attention workloads at their stated sizes on pools of 8-token pages."""
+    b = synth.config_llama8b_decode(page_size=8)
+    order = np.argsort(b.ctx_lens.numpy())
+    run_batch(b, synth.BASE_SEED + 11, [int(order[0]), int(order[-1]), 0, 255])
+    b = synth.config_qwen7b_mixed(page_size=8)
+    order = np.argsort(b.ctx_lens[:64].numpy())
+    run_batch(b, synth.BASE_SEED + 12, [int(order[0]), int(order[-1]), 64, 65, 66, 67])
+    b = synth.config_llama70b_long(page_size=8)
+    order = np.argsort(b.ctx_lens[:128].numpy())
+    run_batch(b, synth.BASE_SEED + 13, [int(order[-1]), 77, 128], rows_per_chunk=4)
 
 
 def test_very_long_contexts():

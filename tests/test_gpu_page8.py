@@ -240,3 +240,68 @@ def test_page_size_changes_no_bit_of_the_output():
             out, _, _, _ = run_step(b, 141)
             outs.append(out)
         assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
+
+
+def test_checkpoint_through_the_host_and_layer_loop():
+    """Per-layer loop with a preemption at the second safepoint, then the pages the step filled
+    saved to a pinned host buffer and to the host page store, loaded into fresh pages, and the
+    next step's attention read through the rewritten block tables -- all on 8-token pages."""
+    import ctypes
+    L = 6
+    b = synth.config_qwen7b_mixed(shrink=16, page_size=8)
+    sh = b.shape
+    n_on = b.extra["n_online"]
+    steps = [Step(b, 170 + l) for l in range(L)]
+    pools = np.stack([st.prior_pool()[0] for st in steps])
+    pool = cs.Pool(from_bits(pools, "cuda"), L, b.num_pages, sh.Hkv, sh.D, page_size=8)
+    bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
+    q = torch.stack([st.q for st in steps]).cuda()
+    k = torch.stack([st.k_new for st in steps]).cuda()
+    v = torch.stack([st.v_new for st in steps]).cuda()
+    ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+    calls = []
+
+    def poll(_):
+        calls.append(1)
+        return 1 if len(calls) >= 2 else 0
+
+    cb = cs.POLL_FN(poll)
+    sp = cs.cs_safepoint(None, cb, None, 2, n_on, 0)
+    out = torch.full_like(q, float("nan"))
+    first = cs.cs_run_layers(pool, 0, L, bb, q, k, v, out, sh.Hq, sh.scale, ws, sp)
+    torch.cuda.synchronize()
+    assert first == 2
+    T_on = int(b.cu_q_lens[n_on])
+    assert torch.isnan(out[2:, T_on:].float()).all()
+    assert_attention_close(out[1], steps[1].oracle_attention(), "page 8 layer 1")
+    assert_attention_close(out[4, :T_on], steps[4].oracle_attention(range(n_on))[:T_on], "page 8 online layer 4")
+    # the oracle's pool after the same appends: whole batch in layers 0-1, online prefix after
+    cpu = pools.copy()
+    for l in range(L):
+        if l < 2:
+            cpu[l] = steps[l].oracle_append(cpu[l][None])[0]
+        else:
+            kv_layout.ref_append(cpu, l, b.block_tables.numpy()[:n_on], b.ctx_lens.numpy()[:n_on],
+                                 b.cu_q_lens.numpy()[:n_on + 1], bits(steps[l].k_new)[:T_on], bits(steps[l].v_new)[:T_on],
+                                 page_size=8)
+    np.testing.assert_array_equal(bits(pool.tensor), cpu)
+    # checkpoint the pages layers 0-1 filled, through a plain host buffer and through the page store
+    dirty = synth.newly_filled_pages(b)
+    assert len(dirty) > 4
+    fresh = [int(x) for x in b.spare_pages[:len(dirty)]] if len(b.spare_pages) >= len(dirty) else None
+    ids = torch.tensor(dirty, dtype=torch.int32, device="cuda")
+    staging = torch.empty((L, len(dirty), sh.page_elems), dtype=torch.bfloat16, device="cuda")
+    host = torch.empty((L, len(dirty), sh.page_elems), dtype=torch.bfloat16).pin_memory()
+    cs.cs_kv_ckpt_save(pool, 0, L, ids, staging, host)
+    torch.cuda.synchronize()
+    want = kv_layout.ref_gather(cpu, 0, L, dirty)
+    np.testing.assert_array_equal(bits(host), want)
+    store = cs.HostStore(torch.zeros((len(dirty) + 2, L, sh.page_elems), dtype=torch.bfloat16).pin_memory())
+    cs.cs_kv_ckpt_save_run(pool, 0, L, ids, staging, store, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(store.tensor[1:1 + len(dirty)]), want.transpose(1, 0, 2))
+    # overwrite the pages, bring them back from the store, same pages
+    pool.tensor[:, dirty] = float("nan")
+    cs.cs_kv_ckpt_load_run(pool, 0, L, ids, staging, store, 1)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(bits(pool.tensor), cpu)
