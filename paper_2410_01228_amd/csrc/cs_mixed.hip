@@ -38,7 +38,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
         const int32_t pos = rem / Hkv;
         const int32_t g = rem - pos * Hkv;
         const int32_t b = backwards ? (int32_t)(wgs_per_range / Hkv) - 1 - pos : pos;   // longest tiles first
-        prefill_tile<D, E, kPhasePriority, PS>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
+        prefill_tile<D, E, kPhasePriority, PS, true>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
                            ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, base_slot, prefill_part, g, b,
                            (int32_t)range, max_ranges);
     } else {

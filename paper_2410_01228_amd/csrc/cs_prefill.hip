@@ -20,7 +20,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t pos = blockIdx.x / Hkv;
     const int32_t g = blockIdx.x - pos * Hkv;
     const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos] : backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos;
-    prefill_tile<D, E, true, PS>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
+    prefill_tile<D, E, true, PS, false>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
                        q, out, scale_log2e, range_steps, base_slot, part, g, b, blockIdx.y, gridDim.y);
 }
 
