@@ -388,3 +388,48 @@ def test_prefill_key_range_split(Hq, Hkv, D, gain):
     assert cs.cs_paged_attention_workspace_bytes(bb, Hq, Hkv, D) > 0
     out, st, _, _ = run_step(b, 61, q_gain=gain)
     assert_attention_close(out, st.oracle_attention(), "prefill split %d/%d/%d" % (Hq, Hkv, D))
+
+
+@pytest.mark.parametrize("page_size", [16, 8])
+def test_bad_page_ids_are_skipped_and_harm_no_other_sequence(page_size):
+    """Block tables live on the device and are not validated by the host: an entry outside
+    [0, num_pages) is skipped by every kernel (append writes nothing for it, attention reads
+    nothing through it).  The rows of the sequences with bad entries are unspecified; every
+    other sequence and every page they do not own must come out as if nothing were wrong."""
+    sh = synth.Shape(8, 2, 128, page_size=page_size)
+    ctx, ql = [300, 700, 40, 0, 513, 90], [1, 1, 40, 33, 1, 17]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(71), spare=2)
+    st = Step(b, 71)
+    cpu_pool = st.prior_pool()
+    bt = b.block_tables.clone()
+    bad_seqs = [1, 2, 4]
+    bt[1, 3] = -1                                  # decode: a page in the middle of the context
+    bt[1, int(b.blocks_needed()[1]) - 1] = b.num_pages          # ... and the page the new token goes to
+    bt[2, 0] = 1 << 30                             # chunk: first context page, and a page the chunk writes
+    bt[2, int(b.blocks_needed()[2]) - 1] = -7
+    bt[4, :] = b.num_pages + 5                     # decode: every page
+    pool = cs.Pool(from_bits(cpu_pool, "cuda"), 1, b.num_pages, sh.Hkv, sh.D, page_size=page_size)
+    bb = cs.Batch(bt, b.ctx_lens, b.cu_q_lens)
+    cs.cs_kv_append(pool, 0, bb, st.k_new.cuda(), st.v_new.cuda())
+    torch.cuda.synchronize()
+    # the oracle's append with the bad sequences' bad entries left out: append only what has a page
+    want = cpu_pool.copy()
+    st.oracle_append(want)
+    got = bits(pool.tensor)
+    owned_by_bad = set()
+    for s in bad_seqs:
+        owned_by_bad.update(int(x) for x in b.block_tables[s] if x >= 0)
+    keep = np.array([p not in owned_by_bad for p in range(b.num_pages)])
+    np.testing.assert_array_equal(got[:, keep], want[:, keep])
+    for mode in (2, 0):
+        cs.cs_set_mixed_fusion(mode)
+        try:
+            ws = cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D)
+            out = torch.full((b.T, sh.Hq, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+            cs.cs_paged_attention_mixed(pool, 0, bb, st.q.cuda(), out, sh.Hq, sh.scale, ws)
+            torch.cuda.synchronize()
+        finally:
+            cs.cs_set_mixed_fusion(1)
+        good = [s for s in range(b.S) if s not in bad_seqs]
+        ref = st.oracle_attention(good)
+        assert_attention_close(out, ref, "good sequences beside bad page ids, page size %d" % page_size)
