@@ -44,7 +44,7 @@ def test_page_bytes_and_status_strings():
 
 
 def _pool(base=0x1000, L=2, P=8, Hkv=2, D=64, page=16, ls=None, ps=None):
-    pe = 2 * Hkv * 16 * D
+    pe = 2 * Hkv * page * D
     ps = pe if ps is None else ps
     return cs.cs_kv_pool(base, L, P, page, Hkv, D, P * ps if ls is None else ls, ps)
 
@@ -71,7 +71,15 @@ def test_checkpoint_argument_checks_happen_on_the_host():
     # empty work is legal and launches nothing
     assert lib.cs_kv_ckpt_gather(ctypes.byref(p), 0, 2, None, 0, None, 0, None) == cs.CS_OK
     assert lib.cs_kv_ckpt_restore(ctypes.byref(p), 1, 1, ids, 3, st, 0, None) == cs.CS_OK
+    # pages of 8 tokens: half the bytes per page
+    p8 = _pool(page=8)
+    assert lib.cs_pool_page_bytes(ctypes.byref(p8)) == page // 2 and lib.cs_pool_page_bytes(ctypes.byref(p)) == page
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p8), 0, 2, ids, 3, st, 2 * 3 * (page // 2) - 1, None) == cs.CS_ERR_STAGING_TOO_SMALL
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(p8), 0, 2, None, 0, None, 0, None) == cs.CS_OK
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(page=8, ps=2 * 2 * 8 * 64 - 8)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
     # unsupported / malformed pools
+    assert lib.cs_pool_page_bytes(ctypes.byref(_pool(page=32))) == 0 and lib.cs_pool_page_bytes(None) == 0
+    assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(page=4)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_UNSUPPORTED
     assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(page=32)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_UNSUPPORTED
     assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(D=96)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_UNSUPPORTED
     assert lib.cs_kv_ckpt_gather(ctypes.byref(_pool(ps=100)), 0, 1, ids, 1, st, 1 << 30, None) == cs.CS_ERR_INVALID_ARG
@@ -88,6 +96,8 @@ def test_batch_checks_and_empty_batches():
     assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b), None, q, None) == cs.CS_ERR_INVALID_ARG
     b2, keep2 = _batch([5, 40], [1, 3], max_blocks=2)                       # 43 tokens need 3 blocks
     assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b2), q, q, None) == cs.CS_ERR_INVALID_ARG
+    b3, keep3 = _batch([5, 40], [1, 3], max_blocks=5)                       # ... and 6 blocks of 8 tokens
+    assert lib.cs_kv_append(ctypes.byref(_pool(page=8)), 0, ctypes.byref(b3), q, q, None) == cs.CS_ERR_INVALID_ARG
     b3, keep3 = _batch([5, -1], [1, 1])
     assert lib.cs_kv_append(ctypes.byref(p), 0, ctypes.byref(b3), q, q, None) == cs.CS_ERR_INVALID_ARG
     b4, keep4 = _batch([5, 6], [1, 1])
