@@ -76,11 +76,13 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         // Few, long work items stream best: each pays its start-up latencies once, and when no
         // sequence is cut the plan and merge kernels are not launched at all.  Start from items
         // of about 2 MiB of K/V per kv head and halve only until the grid has enough workgroups:
-        // three per CU, or two per CU when the sequences are of nearly equal length (then the
-        // items are too, and nothing straggles).
+        // three per CU, or one per CU when the sequences are of nearly equal length (then the
+        // items are too, nothing straggles, and a workgroup that has its CU to itself streams
+        // fastest: over 159 uniform batches of three model shapes, 256-511 workgroups beat both
+        // fewer and the 512-1023 of the next halving by 5-8%).
         const int32_t cap = head_dim >= 128 ? 4096 : 8192;
         const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
-        const int64_t need = uniform ? 512 : 768;
+        const int64_t need = uniform ? 256 : 768;
         // no sequence is cut into more than about 16 pieces: beyond that the partials, their merge
         // and the start-up of ever shorter items cost more than the fuller grid gains
         int32_t floor_split = 256;
@@ -109,6 +111,11 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
     {
         const int64_t kv_bytes = p.decode_keys * 2 * Hkv * head_dim * 2;
         p.pages_ahead = kv_bytes >= 650000000ll ? 2 : 1;
+        // equal items run in rounds over the workgroup slots: between 513 and 768 of them are one
+        // round of three per CU, but a round and a quarter of two per CU
+        const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
+        const int64_t wgs = (int64_t)p.total_items * Hkv;
+        if (uniform && wgs > 512 && wgs <= 768) p.pages_ahead = 1;
         const int32_t forced = g_forced_ahead.load();
         if (forced == 1 || forced == 2) p.pages_ahead = forced;
     }
