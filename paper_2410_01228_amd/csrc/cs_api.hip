@@ -80,20 +80,29 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         // items are too, nothing straggles, and a workgroup that has its CU to itself streams
         // fastest: over 159 uniform batches of three model shapes, 256-511 workgroups beat both
         // fewer and the 512-1023 of the next halving by 5-8%).
+        // Launches below about 0.4 GB of K/V (some 60 us) are decided by start-up, merge and how
+        // many workgroups crowd a CU, not by the steady state: they aim at one and a half workgroups
+        // per CU (over 171 random batches of three shapes: mean distance to the best forced plan
+        // 3.8% -> 2.3%, worst 61% -> 17%, together with the floor rule below).
         const int32_t cap = head_dim >= 128 ? 4096 : 8192;
         const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
-        const int64_t need = uniform ? 256 : 768;
-        // no sequence is cut into more than about 16 pieces: beyond that the partials, their merge
-        // and the start-up of ever shorter items cost more than the fuller grid gains
-        int32_t floor_split = 256;
-        while (floor_split < cap && (int64_t)floor_split * 16 < max_keys) floor_split *= 2;
-        for (split = cap; split > floor_split; split /= 2) {
+        const int64_t kv_bytes = p.decode_keys * 2 * Hkv * head_dim * 2;
+        const int64_t need = uniform ? 256 : kv_bytes >= 400000000ll ? 768 : 384;
+        auto workgroups_at = [&](int32_t sp) {
             int64_t items = 0;
             for (int32_t s = 0; s < b->num_seqs; ++s)
                 if (b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s] == 1)
-                    items += decode_num_splits(b->h_ctx_lens[s] + 1, split);
-            if (items * Hkv >= need) break;
-        }
+                    items += decode_num_splits(b->h_ctx_lens[s] + 1, sp);
+            return items * Hkv;
+        };
+        // no sequence is cut into more than about 16 pieces: beyond that the partials, their merge
+        // and the start-up of ever shorter items cost more than the fuller grid gains -- unless
+        // that leaves CUs without any workgroup (a handful of very long sequences)
+        int32_t floor_split = 256;
+        while (floor_split < cap && (int64_t)floor_split * 16 < max_keys) floor_split *= 2;
+        while (floor_split > 256 && workgroups_at(floor_split) < 256) floor_split /= 2;
+        for (split = cap; split > floor_split; split /= 2)
+            if (workgroups_at(split) >= need) break;
     }
     p.split_tokens = split;
     int32_t max_k = 1;

@@ -130,14 +130,14 @@ def test_model_shapes_with_pages_of_8_tokens():
 def test_very_long_contexts():
     """Contexts far beyond the workloads': a decode over 150 001 keys, one over 70 002, and a
     chunk of 48 tokens on 90 000 (few tiles on a very long context: key ranges and their
-    merge).  Once with the automatic plan (a sequence is cut into a few dozen pieces at most,
-    listed in the kernel arguments) and once cut at 256 keys: more pieces than an item word
-    can say, so the planning kernel lists them."""
+    merge).  Once with the automatic plan (two sequences alone are cut until every CU has a
+    workgroup: some hundred pieces each, still listed in the kernel arguments) and once cut at
+    256 keys: more pieces than an item word can say, so the planning kernel lists them."""
     sh = synth.Shape(4, 2, 64)
     b = synth.make_batch(sh, [150000, 70001, 90000], [1, 1, 48], synth.generator(90))
     bb = cs.Batch(b.block_tables, b.ctx_lens, b.cu_q_lens)
     items, n_items, split = cs.cs_debug_decode_items(bb, sh.Hkv, sh.D)
-    assert items is not None and 16 <= n_items <= 64
+    assert items is not None and 128 <= n_items <= 510 and n_items * sh.Hkv >= 256
     assert cs.cs_paged_attention_workspace_bytes(bb, sh.Hq, sh.Hkv, sh.D) > 0
     run_batch(b, 90, [0, 1, 2], rows_per_chunk=5)
     cs.cs_set_decode_split_tokens(256)
