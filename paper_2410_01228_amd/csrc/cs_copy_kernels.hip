@@ -183,8 +183,10 @@ int launch_plain_copy(void* dst, const void* src, size_t bytes, hipStream_t st)
 constexpr int kAppendThreads = 256;
 constexpr int kAppendSlotShift = 4;
 
+// The work of workgroup `block` of the chunk path.
 template <int PS>
-__global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
+__device__ __forceinline__ void append_page_block(
+    int32_t block,
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t D, int32_t S,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
     // slots are numbered head-major, so the workgroups of one page -- which together read
     // whole token rows and write one whole page -- all land on the same XCD.
     const int32_t per = 8 * Hkv;
-    const int32_t group = blockIdx.x / per, in_group = blockIdx.x - group * per;
+    const int32_t group = block / per, in_group = block - group * per;
     const int32_t h = in_group >> 3;
     const int32_t slot_id = group * 8 + (in_group & 7);
     int32_t lo = 0, hi = S;                                       // largest s with start(s) <= slot_id
@@ -270,7 +272,8 @@ __global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
 // and V row.  The K unit is stored as it is; the V unit is scattered as 8 two-byte stores
 // (the V block keeps 8 consecutive TOKENS of one feature together).  Sequences with more
 // than one new token are left to append_page_kernel.
-__global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
+__device__ __forceinline__ void append_token_block(
+    int32_t block,
     uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t D, int32_t S, int32_t T,
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
@@ -278,7 +281,7 @@ __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new, int32_t page_size)
 {
     const int32_t units_per_tok = Hkv * (D >> 3);
-    const int64_t gid = (int64_t)blockIdx.x * kAppendThreads + threadIdx.x;
+    const int64_t gid = (int64_t)block * kAppendThreads + threadIdx.x;
     const int32_t t = (int32_t)(gid / units_per_tok);
     if (t >= T) return;
     const int32_t u = (int32_t)(gid - (int64_t)t * units_per_tok);
@@ -317,6 +320,48 @@ __global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
     }
 }
 
+template <int PS>
+__global__ __launch_bounds__(kAppendThreads) void append_page_kernel(
+    uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t D, int32_t S,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new)
+{
+    append_page_block<PS>((int32_t)blockIdx.x, layer_base, page_stride, num_pages, Hkv, D, S, block_tables, max_blocks,
+                          ctx_lens, cu_q_lens, k_new, v_new);
+}
+
+__global__ __launch_bounds__(kAppendThreads) void append_token_kernel(
+    uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t D, int32_t S, int32_t T,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new, int32_t page_size)
+{
+    append_token_block((int32_t)blockIdx.x, layer_base, page_stride, num_pages, Hkv, D, S, T, block_tables, max_blocks,
+                       ctx_lens, cu_q_lens, k_new, v_new, page_size);
+}
+
+// A step with both chunks and single tokens (a mixed batch): the workgroups of the chunk path
+// first, those of the single-token path behind them, in one launch (the calls are launch-bound
+// at the batch sizes of a serving step, so the second launch was a third of the time).
+template <int PS>
+__global__ __launch_bounds__(kAppendThreads) void append_mixed_kernel(
+    uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
+    int32_t Hkv, int32_t D, int32_t S, int32_t T,
+    const int32_t* __restrict__ block_tables, int32_t max_blocks,
+    const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
+    const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new, uint32_t page_blocks)
+{
+    if (blockIdx.x < page_blocks)
+        append_page_block<PS>((int32_t)blockIdx.x, layer_base, page_stride, num_pages, Hkv, D, S, block_tables, max_blocks,
+                              ctx_lens, cu_q_lens, k_new, v_new);
+    else
+        append_token_block((int32_t)(blockIdx.x - page_blocks), layer_base, page_stride, num_pages, Hkv, D, S, T,
+                           block_tables, max_blocks, ctx_lens, cu_q_lens, k_new, v_new, PS);
+}
+
 int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
                   const void* k_new, const void* v_new, hipStream_t st)
 {
@@ -328,28 +373,39 @@ int launch_append(const cs_kv_pool& pool, int32_t layer, const cs_batch& b,
         any_chunk |= ql > 1;
     }
     uint16_t* layer_base = (uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
-    if (any_chunk) {
-        const int64_t slots = (((int64_t)(b.num_tokens >> kAppendSlotShift) + 2ll * b.num_seqs) + 7) & ~7ll;   // whole groups of 8
-        const int64_t blocks = slots * pool.num_kv_heads;
-        if (blocks > 2147483647ll) return CS_ERR_UNSUPPORTED;
+    const int64_t slots = (((int64_t)(b.num_tokens >> kAppendSlotShift) + 2ll * b.num_seqs) + 7) & ~7ll;   // whole groups of 8
+    const int64_t page_blocks = any_chunk ? slots * pool.num_kv_heads : 0;
+    const int64_t units = (int64_t)b.num_tokens * pool.num_kv_heads * (pool.head_dim / 8);
+    const int64_t token_blocks = any_single ? (units + kAppendThreads - 1) / kAppendThreads : 0;
+    if (page_blocks + token_blocks > 2147483647ll) return CS_ERR_UNSUPPORTED;
+    const uint16_t* kn = (const uint16_t*)k_new;
+    const uint16_t* vn = (const uint16_t*)v_new;
+    if (any_chunk && any_single) {
+        const dim3 grid((uint32_t)(page_blocks + token_blocks));
         if (pool.page_size == 16)
-            hipLaunchKernelGGL(append_page_kernel<16>, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
+            hipLaunchKernelGGL(append_mixed_kernel<16>, grid, dim3(kAppendThreads), 0, st,
                                layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
-                               b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
-                               (const uint16_t*)k_new, (const uint16_t*)v_new);
+                               b.num_seqs, b.num_tokens, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
+                               kn, vn, (uint32_t)page_blocks);
         else
-            hipLaunchKernelGGL(append_page_kernel<8>, dim3((uint32_t)blocks), dim3(kAppendThreads), 0, st,
+            hipLaunchKernelGGL(append_mixed_kernel<8>, grid, dim3(kAppendThreads), 0, st,
                                layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
-                               b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
-                               (const uint16_t*)k_new, (const uint16_t*)v_new);
-    }
-    if (any_single) {
-        const int64_t units = (int64_t)b.num_tokens * pool.num_kv_heads * (pool.head_dim / 8);
-        const uint32_t blocks = (uint32_t)((units + kAppendThreads - 1) / kAppendThreads);
-        hipLaunchKernelGGL(append_token_kernel, dim3(blocks), dim3(kAppendThreads), 0, st,
+                               b.num_seqs, b.num_tokens, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens,
+                               kn, vn, (uint32_t)page_blocks);
+    } else if (any_chunk) {
+        if (pool.page_size == 16)
+            hipLaunchKernelGGL(append_page_kernel<16>, dim3((uint32_t)page_blocks), dim3(kAppendThreads), 0, st,
+                               layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
+                               b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens, kn, vn);
+        else
+            hipLaunchKernelGGL(append_page_kernel<8>, dim3((uint32_t)page_blocks), dim3(kAppendThreads), 0, st,
+                               layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
+                               b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens, b.cu_q_lens, kn, vn);
+    } else if (any_single) {
+        hipLaunchKernelGGL(append_token_kernel, dim3((uint32_t)token_blocks), dim3(kAppendThreads), 0, st,
                            layer_base, pool.page_stride, pool.num_pages, pool.num_kv_heads, pool.head_dim,
                            b.num_seqs, b.num_tokens, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,
-                           b.cu_q_lens, (const uint16_t*)k_new, (const uint16_t*)v_new, pool.page_size);
+                           b.cu_q_lens, kn, vn, pool.page_size);
     }
     return check_launch("append kernels");
 }
