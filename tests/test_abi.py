@@ -175,6 +175,32 @@ def test_decode_plan_lists_every_piece_once_longest_first():
     assert all(a[1] >= b[1] for a, b in zip(length, length[1:]))                                # longest first
 
 
+def test_decode_plan_sizes_the_grid_by_the_batch():
+    """Workgroups = items x kv heads.  Equal lengths: the fewest pieces that give every CU (256)
+    a workgroup.  Uneven lengths: one and a half per CU for small launches, three per CU from about
+    0.4 GB of K/V on.  A handful of very long sequences is cut past the sixteen-pieces limit
+    until every CU has a workgroup."""
+    def wgs(ctx, Hkv, D=128):
+        items, n, split = _plan(ctx, [1] * len(ctx), Hkv, D)
+        return n * Hkv, split
+    assert wgs([4095] * 32, 8) == (256, 4096)                 # 32 x 8 = 256 uncut
+    assert wgs([4095] * 48, 8) == (384, 4096)
+    assert wgs([2047] * 8, 8) == (256, 512)                   # 8 x 8 x 4 pieces
+    assert wgs([4095] * 24, 4) == (384, 1024)                 # 96 workgroups uncut, 192 in halves: quarters
+    import random
+    rnd = random.Random(11)
+    small = [rnd.randint(1024, 8192) for _ in range(24)]      # 0.24 GB at 4 heads
+    w, split = wgs(small, 4)
+    assert 384 <= w < 768 and split == 1024
+    large = [rnd.randint(1024, 8192) for _ in range(64)]      # 0.6 GB
+    w, split = wgs(large, 4)
+    assert 768 <= w < 1536 and split == 1024
+    w, split = wgs([30000, 9000, 25000, 2100], 8)             # a sixteenth of the longest is 2048: 264 workgroups there
+    assert split == 2048 and w >= 256
+    w, split = wgs([30000, 9000], 8)                          # 152 at 2048: cut finer although that makes 29 pieces
+    assert split == 1024 and w >= 256
+
+
 def test_decode_plan_falls_back_to_the_planning_kernel_beyond_the_argument_block():
     ctx = [100] * 880
     items, n, _ = _plan(ctx, [1] * 880, 2, 64)
