@@ -185,6 +185,10 @@ __device__ __forceinline__ void prefill_tile(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 
+    // kFold (element types that stand it, see cs_elem.h): Q is scaled once by scale*log2(e), so the
+    // matrix unit delivers the scores in the exponent's domain, and the score accumulators start
+    // from minus the running offset, so exp2 takes them as they come -- no multiply-add per score.
+    constexpr bool kFold = E::kScaleFoldsIntoQ;
     // ---- this wavefront's column tiles: ct = wave*4 + c -> (token block, head) ----
     u32x4 qb[kNCT][D / 32];
     int32_t pos_q[kNCT];                               // absolute position of this lane's query
@@ -201,6 +205,10 @@ __device__ __forceinline__ void prefill_tile(
             u32x4 v = zero4;
             if (valid)
                 v = *(const u32x4*)(q + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + kk * 32 + (lane >> 4) * 8);
+            if constexpr (kFold) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) v[e] = E::scale2(v[e], scale_log2e);
+            }
             qb[c][kk] = v;
         }
     }
@@ -329,6 +337,11 @@ __device__ __forceinline__ void prefill_tile(
     // K operands of the step whose scores are computed next.  They are fetched from LDS one
     // phase ahead (while the P.V products of the previous step run), so that the score
     // products never wait for an LDS round trip.
+    // kFold: minus the offset the score accumulators start from -- the running maximum once a
+    // score has been seen, 0 before (m_run is then still the "none yet" mark)
+    f32x4 neg_off[kNCT];
+#pragma unroll
+    for (int c = 0; c < kNCT; ++c) neg_off[c] = f32x4{0.f, 0.f, 0.f, 0.f};
     u32x4 kreg[2 * (D / 32)];
     auto load_k = [&](int32_t step) {
         const u32x4* kA = &lds_k[(uint32_t)step % kRing][0];
@@ -339,7 +352,10 @@ __device__ __forceinline__ void prefill_tile(
         constexpr bool kMask = decltype(masked)::value;
         f32x4 s0[kNCT], s1[kNCT];
 #pragma unroll
-        for (int c = 0; c < kNCT; ++c) { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        for (int c = 0; c < kNCT; ++c) {
+            if constexpr (kFold) { s0[c] = neg_off[c]; s1[c] = neg_off[c]; }
+            else { s0[c] = f32x4{0.f, 0.f, 0.f, 0.f}; s1[c] = f32x4{0.f, 0.f, 0.f, 0.f}; }
+        }
 #pragma unroll
         for (int kk = 0; kk < D / 32; ++kk) {
 #pragma unroll
@@ -370,7 +386,7 @@ __device__ __forceinline__ void prefill_tile(
 #pragma unroll
     for (int c = 0; c < kNCT; ++c) thr[c] = -INFINITY;
     const float inv_scale = 1.f / scale_log2e;
-    auto raise_max = [&](const float (&xs)[kNCT][8]) {
+    auto raise_max = [&](float (&xs)[kNCT][8]) {
         bool need = false;
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
@@ -382,13 +398,32 @@ __device__ __forceinline__ void prefill_tile(
                 float m = max8(xs[c]);
                 m = fmaxf(m, __shfl_xor(m, 16, 64));
                 m = fmaxf(m, __shfl_xor(m, 32, 64));
-                const float m_new = fmaxf(m_run[c], m * scale_log2e);
-                const float alpha = __builtin_amdgcn_exp2f(m_run[c] - m_new);   // 0 while m_run is -inf
-                lacc[c] *= alpha;
+                if constexpr (kFold) {
+                    // xs are relative to the offset the accumulators started from; thr likewise
+                    // (-inf until a score has been seen, the lazy margin after)
+                    const float off = -neg_off[c][0];
+                    const float m_new = fmaxf(m_run[c], off + m);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[c] - m_new);
+                    lacc[c] *= alpha;
 #pragma unroll
-                for (int dt = 0; dt < D / 16; ++dt) o[c][dt] *= alpha;
-                m_run[c] = m_new;
-                thr[c] = (m_new + kLazyLog2) * inv_scale;
+                    for (int dt = 0; dt < D / 16; ++dt) o[c][dt] *= alpha;
+                    m_run[c] = m_new;
+                    const bool seen = m_new > kNoMax;
+                    const float off_new = seen ? m_new : 0.f;
+                    const float d = off_new - off;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) xs[c][j] -= d;             // -inf stays -inf
+                    neg_off[c] = f32x4{-off_new, -off_new, -off_new, -off_new};
+                    thr[c] = seen ? kLazyLog2 : -INFINITY;
+                } else {
+                    const float m_new = fmaxf(m_run[c], m * scale_log2e);
+                    const float alpha = __builtin_amdgcn_exp2f(m_run[c] - m_new);   // 0 while m_run is -inf
+                    lacc[c] *= alpha;
+#pragma unroll
+                    for (int dt = 0; dt < D / 16; ++dt) o[c][dt] *= alpha;
+                    m_run[c] = m_new;
+                    thr[c] = (m_new + kLazyLog2) * inv_scale;
+                }
             }
         }
     };
@@ -431,7 +466,9 @@ __device__ __forceinline__ void prefill_tile(
         for (int c = 0; c < kNCT; ++c) {
             float p[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(xc[c][j], scale_log2e, -m_run[c]));
+            for (int j = 0; j < 8; ++j)
+                p[j] = kFold ? __builtin_amdgcn_exp2f(xc[c][j])
+                             : __builtin_amdgcn_exp2f(__builtin_fmaf(xc[c][j], scale_log2e, -m_run[c]));
             pb[c] = u32x4{ E::pack(p[0], p[1]), E::pack(p[2], p[3]), E::pack(p[4], p[5]), E::pack(p[6], p[7]) };
         }
         const u32x4* vA = &lds_v[(uint32_t)i % kRing][0];
