@@ -8,8 +8,13 @@
  *   - returns a cs_status (0 = CS_OK, negative = error); all checks that need only host
  *     data are made before anything is enqueued, and a failed call enqueues nothing;
  *   - work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream);
- *     calls never synchronise, never allocate or free, and keep no state between calls
- *     (the one exception is the host-side cs_page_map object at the end of this file);
+ *     calls never synchronise and never allocate or free device memory.  State kept between
+ *     calls: the host-side cs_page_map object at the end of this file; the measurement knobs
+ *     cs_set_decode_split_tokens / cs_set_decode_pages_ahead / cs_set_mixed_fusion /
+ *     cs_debug_set_cu_count, which are process-wide, change launch plans and workspace sizes,
+ *     and are meant for benchmarks and tests only (a serving process leaves them alone); and,
+ *     invisible to the caller, each thread's memo of the last launch plans it made and each
+ *     device's compute-unit count, asked once;
  *   - every pointer is owned by the caller and must stay valid until the enqueued work has
  *     run.  "device" pointers are HIP device memory of the current device, "host" pointers
  *     are ordinary host memory read during the call only;
@@ -21,7 +26,14 @@
  *     Sec. 4.3): sequences are expected online-first, and passing a smaller num_seqs /
  *     num_tokens with the same arrays drops the offline tail without rebuilding metadata;
  *   - device index arrays (block tables, page id lists) are not validated on the host (that
- *     would need a synchronisation); kernels skip any page id outside [0, num_pages).
+ *     would need a synchronisation).  A page id outside [0, num_pages) is never dereferenced:
+ *     the copies (append, gather, restore) skip it.  The attention output of a sequence whose
+ *     block table holds such an id within its length is unspecified (the decode path leaves
+ *     the page's keys out and writes zeros if no key is left; the chunk path reads page 0 of
+ *     the pool in its place); every other sequence of the batch is unaffected;
+ *   - the explicit K/V, head and token strides a generic paged pool would carry are absent on
+ *     purpose: inside a (layer, page) the format below is fixed, because it is what lets the
+ *     kernels load matrix operands without shuffles; only the layer and page strides vary.
  *
  * KV pool format (this library's own; the paper fixes only the 16-token page and the
  * per-request page table).  In bf16 elements:
@@ -112,8 +124,9 @@ int cs_kv_append(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
 /* Workspace the attention call needs for this batch: the fp32 partial results of decode
  * sequences cut into work items and of prefill tiles cut into key ranges (the launch plan is
  * made here from the host arrays of `batch` and the shape, and again, identically, in the
- * attention call).  Zero for many batches; a few MB to a few hundred MB when chunks of up to a
- * few thousand tokens are cut to fill the chip.  Returns 0 on bad arguments. */
+ * attention call, which finds it remembered).  Zero for many batches; a few MB to a few hundred
+ * MB when chunks of up to a few thousand tokens are cut to fill the chip.  Returns 0 on bad
+ * arguments. */
 size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t num_q_heads,
                                           int32_t num_kv_heads, int32_t head_dim);
 
@@ -217,13 +230,21 @@ typedef struct {
  * safepoints above (safepoint == NULL: none).  Per-layer tensors: layer l uses
  * q + (l - layer_begin) * q_layer_stride elements, likewise k_new / v_new (kv_layer_stride)
  * and out (q_layer_stride); strides in bf16 elements.  *preempted_before_layer (host,
- * nullable) receives the first layer that ran online-only, or -1.  Workspace as for
- * cs_paged_attention_mixed of the full batch.  Errors as for the two calls. */
+ * nullable) receives the first layer that ran online-only, or -1.  workspace: at least
+ * cs_run_layers_workspace_bytes() -- the larger of what the full batch and what its online
+ * prefix need (fewer sequences are cut finer, so the prefix can need more than the whole).
+ * Everything that can refuse the iteration (shapes, pointers, workspace size for both plans)
+ * is checked before the first layer is enqueued.  Errors as for the two calls. */
 int cs_run_layers(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end, const cs_batch* batch,
                   const void* q, const void* k_new, const void* v_new, void* out,
                   int64_t q_layer_stride, int64_t kv_layer_stride,
                   int32_t num_q_heads, float softmax_scale, void* workspace, size_t workspace_bytes,
                   const cs_safepoint* safepoint, int32_t* preempted_before_layer, void* stream);
+
+/* Workspace of cs_run_layers for this batch when a safepoint may cut it down to its first
+ * num_online_seqs sequences (0 or num_seqs: no cut).  Host only.  Returns 0 on bad arguments. */
+size_t cs_run_layers_workspace_bytes(const cs_batch* batch, int32_t num_online_seqs, int32_t num_q_heads,
+                                     int32_t num_kv_heads, int32_t head_dim);
 
 /* The same loop for fp16 data (see cs_paged_attention_mixed_f16). */
 int cs_run_layers_f16(const cs_kv_pool* pool, int32_t layer_begin, int32_t layer_end, const cs_batch* batch,
@@ -311,6 +332,12 @@ int cs_debug_copy(void* dst, const void* src, size_t bytes, void* stream);
  * *split_tokens (optional) receives the target keys per item.  No device work. */
 int32_t cs_debug_decode_items(const cs_batch* batch, int32_t num_kv_heads, int32_t head_dim,
                               uint32_t* items, int32_t capacity, int32_t* split_tokens);
+
+/* The launch plans size their grids by the compute-unit count of the current device
+ * (hipDeviceAttributeMultiprocessorCount, asked once per device; 256 where no device answers).
+ * For host tests: plan as if the device had `cus` compute units; 0 = ask the device again.
+ * Process-wide; changes launch plans and workspace sizes. */
+void cs_debug_set_cu_count(int32_t cus);
 
 /* Tuning knob for measurements: force the decode path's tokens per split (multiple of 16,
  * 0 = automatic).  Process-wide; affects cs_paged_attention_workspace_bytes() as well. */

@@ -116,6 +116,9 @@ def lib():
         L.cs_run_layers_f16.argtypes = L.cs_run_layers.argtypes = [PP, i32, i32, BP, vp, vp, vp, vp, ctypes.c_int64, ctypes.c_int64, i32,
                                     ctypes.c_float, vp, sz, ctypes.POINTER(cs_safepoint),
                                     ctypes.POINTER(ctypes.c_int32), vp]
+        L.cs_run_layers_workspace_bytes.restype = sz
+        L.cs_run_layers_workspace_bytes.argtypes = [BP, i32, i32, i32, i32]
+        L.cs_debug_set_cu_count.restype, L.cs_debug_set_cu_count.argtypes = None, [i32]
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
@@ -137,7 +140,7 @@ EXPORTS = [
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
-    "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
+    "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_run_layers_workspace_bytes", "cs_debug_set_cu_count", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
     "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_status_string", "cs_last_hip_error",
 ]
 
@@ -400,6 +403,19 @@ def cs_run_layers(pool: Pool, layer_begin: int, layer_end: int, batch: Batch, q:
                                ctypes.byref(safepoint) if safepoint is not None else None,
                                ctypes.byref(first), _stream(stream)), "cs_run_layers")
     return first.value
+
+
+def cs_run_layers_workspace_bytes(batch: Batch, num_online_seqs: int, Hq: int, Hkv: int, D: int) -> int:
+    return int(lib().cs_run_layers_workspace_bytes(ctypes.byref(batch.c), num_online_seqs, Hq, Hkv, D))
+
+
+def run_layers_workspace_for(batch: Batch, num_online_seqs: int, Hq: int, Hkv: int, D: int, device="cuda") -> torch.Tensor:
+    n = cs_run_layers_workspace_bytes(batch, num_online_seqs, Hq, Hkv, D)
+    return torch.empty(max(n, 16), dtype=torch.uint8, device=device)
+
+
+def cs_debug_set_cu_count(cus: int):
+    lib().cs_debug_set_cu_count(int(cus))
 
 
 def cs_debug_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):

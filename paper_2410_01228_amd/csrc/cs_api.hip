@@ -3,6 +3,7 @@
 #include <algorithm>
 #include "cs_common.h"
 #include <atomic>
+#include <vector>
 #include <string.h>
 #include <stdio.h>
 
@@ -12,6 +13,33 @@ static thread_local char g_hip_error[256] = "";
 static std::atomic<int32_t> g_forced_split{0};
 static std::atomic<int32_t> g_fuse_mixed{1};
 static std::atomic<int32_t> g_forced_ahead{0};
+static std::atomic<int32_t> g_forced_cus{0};
+
+// Compute units of the current device, asked once per device.  The launch plans size their
+// grids by it.  A host without a device (a plan query in a CPU-only test) plans for 256.
+constexpr int kMaxDevices = 64;
+static std::atomic<int32_t> g_device_cus[kMaxDevices];
+int32_t device_cus() {
+    const int32_t forced = g_forced_cus.load();
+    if (forced > 0) return forced;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return 256;
+    }
+    int32_t n = g_device_cus[dev].load();
+    if (n <= 0) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0) {
+            (void)hipGetLastError();
+            v = 256;
+        }
+        n = v;
+        g_device_cus[dev].store(n);
+    }
+    return n;
+}
+
 
 int hip_failed(hipError_t e, const char* what) {
     snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", what, hipGetErrorString(e));
@@ -71,6 +99,7 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
     p.split_tokens = 256;
     p.pages_ahead = 1;
     if (p.num_decode == 0) return p;
+    const int64_t cus = device_cus();
     int32_t split = g_forced_split.load();
     if (split <= 0) {
         // Few, long work items stream best: each pays its start-up latencies once, and when no
@@ -84,10 +113,11 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         // many workgroups crowd a CU, not by the steady state: they aim at one and a half workgroups
         // per CU (over 171 random batches of three shapes: mean distance to the best forced plan
         // 3.8% -> 2.3%, worst 61% -> 17%, together with the floor rule below).
+        // (the workgroup counts and byte volumes below were measured on 256 CUs and scale with the chip)
         const int32_t cap = head_dim >= 128 ? 4096 : 8192;
         const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
         const int64_t kv_bytes = p.decode_keys * 2 * Hkv * head_dim * 2;
-        const int64_t need = uniform ? 256 : kv_bytes >= 400000000ll ? 768 : 384;
+        const int64_t need = uniform ? cus : kv_bytes >= 400000000ll * cus / 256 ? 3 * cus : cus * 3 / 2;
         auto workgroups_at = [&](int32_t sp) {
             int64_t items = 0;
             for (int32_t s = 0; s < b->num_seqs; ++s)
@@ -100,7 +130,7 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
         // that leaves CUs without any workgroup (a handful of very long sequences)
         int32_t floor_split = 256;
         while (floor_split < cap && (int64_t)floor_split * 16 < max_keys) floor_split *= 2;
-        while (floor_split > 256 && workgroups_at(floor_split) < 256) floor_split /= 2;
+        while (floor_split > 256 && workgroups_at(floor_split) < cus) floor_split /= 2;
         for (split = cap; split > floor_split; split /= 2)
             if (workgroups_at(split) >= need) break;
     }
@@ -119,12 +149,12 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
     // smaller launches, where start-up and tail decide and every workgroup slot counts.
     {
         const int64_t kv_bytes = p.decode_keys * 2 * Hkv * head_dim * 2;
-        p.pages_ahead = kv_bytes >= 650000000ll ? 2 : 1;
+        p.pages_ahead = kv_bytes >= 650000000ll * cus / 256 ? 2 : 1;
         // equal items run in rounds over the workgroup slots: between 513 and 768 of them are one
         // round of three per CU, but a round and a quarter of two per CU
         const bool uniform = (int64_t)max_keys * 4 <= (int64_t)min_keys * 5;
         const int64_t wgs = (int64_t)p.total_items * Hkv;
-        if (uniform && wgs > 512 && wgs <= 768) p.pages_ahead = 1;
+        if (uniform && wgs > 2 * cus && wgs <= 3 * cus) p.pages_ahead = 1;
         const int32_t forced = g_forced_ahead.load();
         if (forced == 1 || forced == 2) p.pages_ahead = forced;
     }
@@ -205,12 +235,69 @@ static int attention_shape_ok(int32_t Hq, int32_t Hkv, int32_t D) {
     return CS_OK;
 }
 
+// The launch plan of a batch: a pure function of the host lengths, the shape, the chip and the
+// measurement knobs.  The workspace query and the attention call of one layer, and the calls of
+// the next layers, ask for the same plan again and again (an item list of up to 880 entries and a
+// sort each time), so each thread remembers the last two it made, keyed by everything the plan
+// depends on, the lengths compared value by value.
+struct Plans {
+    DecodePlan d;
+    PrefillPlan p;
+    size_t decode_bytes, need;
+};
+struct PlanMemo {
+    bool valid = false;
+    int32_t S = 0, T = 0, Hq = 0, Hkv = 0, D = 0, split = 0, ahead = 0, cus = 0;
+    std::vector<int32_t> ctx, cu;
+    Plans plans;
+};
+static const Plans& plans_for(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) {
+    static thread_local PlanMemo memo[2];
+    static thread_local int next = 0;
+    const int32_t S = b->num_seqs, split = g_forced_split.load(), ahead = g_forced_ahead.load(), cus = device_cus();
+    for (PlanMemo& m : memo)
+        if (m.valid && m.S == S && m.T == b->num_tokens && m.Hq == Hq && m.Hkv == Hkv && m.D == D && m.split == split &&
+            m.ahead == ahead && m.cus == cus && memcmp(m.ctx.data(), b->h_ctx_lens, sizeof(int32_t) * S) == 0 &&
+            memcmp(m.cu.data(), b->h_cu_q_lens, sizeof(int32_t) * (S + 1)) == 0)
+            return m.plans;
+    PlanMemo& m = memo[next];
+    next ^= 1;
+    m.valid = false;
+    m.S = S; m.T = b->num_tokens; m.Hq = Hq; m.Hkv = Hkv; m.D = D; m.split = split; m.ahead = ahead; m.cus = cus;
+    m.ctx.assign(b->h_ctx_lens, b->h_ctx_lens + S);
+    m.cu.assign(b->h_cu_q_lens, b->h_cu_q_lens + S + 1);
+    m.plans.d = plan_decode(b, Hkv, D);
+    m.plans.p = m.plans.d.num_prefill ? plan_prefill(b, Hq, Hkv, D) : PrefillPlan{};
+    m.plans.decode_bytes = decode_workspace(m.plans.d, S, Hq, D).total;
+    m.plans.need = m.plans.decode_bytes + m.plans.p.bytes;
+    m.valid = true;
+    return m.plans;
+}
+
 size_t cs_paged_attention_workspace_bytes(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D) {
     if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return 0;
     if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return 0;
-    const DecodePlan p = plan_decode(batch, Hkv, D);
-    const PrefillPlan pp = p.num_prefill ? plan_prefill(batch, Hq, Hkv, D) : PrefillPlan{};
-    return decode_workspace(p, batch->num_seqs, Hq, D).total + pp.bytes;
+    return plans_for(batch, Hq, Hkv, D).need;
+}
+
+// The first num_online_seqs sequences of a batch over the same arrays (what is left of an
+// iteration once it is preempted: paper Sec. 4.3).
+static cs_batch online_prefix(const cs_batch& b, int32_t num_online_seqs) {
+    cs_batch cur = b;
+    cur.num_seqs = num_online_seqs;
+    cur.num_tokens = num_online_seqs > 0 ? b.h_cu_q_lens[num_online_seqs] : 0;
+    return cur;
+}
+
+size_t cs_run_layers_workspace_bytes(const cs_batch* batch, int32_t num_online_seqs, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return 0;
+    if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return 0;
+    size_t need = plans_for(batch, Hq, Hkv, D).need;
+    if (num_online_seqs > 0 && num_online_seqs < batch->num_seqs) {
+        const cs_batch cur = online_prefix(*batch, num_online_seqs);
+        need = std::max(need, plans_for(&cur, Hq, Hkv, D).need);
+    }
+    return need;
 }
 
 static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
@@ -226,10 +313,10 @@ static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch
     if (batch->num_tokens == 0) return CS_OK;
     if (!q || !out || ((uintptr_t)q & 15) || ((uintptr_t)out & 15)) return CS_ERR_INVALID_ARG;
     if (!(softmax_scale > 0.f) || softmax_scale > 3.0e38f) return CS_ERR_INVALID_ARG;   // positive, finite
-    const DecodePlan plan = plan_decode(batch, pool->num_kv_heads, pool->head_dim);
-    const size_t decode_bytes = decode_workspace(plan, batch->num_seqs, Hq, pool->head_dim).total;
-    const PrefillPlan pplan = plan.num_prefill ? plan_prefill(batch, Hq, pool->num_kv_heads, pool->head_dim) : PrefillPlan{};
-    const size_t need = decode_bytes + pplan.bytes;
+    const Plans& plans = plans_for(batch, Hq, pool->num_kv_heads, pool->head_dim);
+    const DecodePlan& plan = plans.d;
+    const PrefillPlan& pplan = plans.p;
+    const size_t decode_bytes = plans.decode_bytes, need = plans.need;
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
@@ -403,6 +490,19 @@ static int run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_b
     if (rc) return rc;
     if (sp && (sp->check_every <= 0 || sp->num_online_seqs < 0 || sp->num_online_seqs > batch->num_seqs))
         return CS_ERR_INVALID_ARG;
+    // Everything that can refuse the iteration is checked before its first layer is enqueued.  The
+    // workspace must hold the full batch's plan AND the online prefix's: fewer sequences are cut
+    // finer (more partials), so the prefix can need more than the whole.
+    if (l1 > l0 && batch->num_tokens > 0) {
+        rc = attention_shape_ok(Hq, pool->num_kv_heads, pool->head_dim);
+        if (rc) return rc;
+        if (!q || !out || !k_new || !v_new) return CS_ERR_INVALID_ARG;
+        if (!(scale > 0.f) || scale > 3.0e38f) return CS_ERR_INVALID_ARG;
+        const size_t need = cs_run_layers_workspace_bytes(batch, sp ? sp->num_online_seqs : 0, Hq, pool->num_kv_heads,
+                                                          pool->head_dim);
+        if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
+        if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
+    }
     cs_batch cur = *batch;
     bool preempted = false;
     for (int32_t l = l0; l < l1; ++l) {
@@ -417,8 +517,7 @@ static int run_layers(const cs_kv_pool* pool, int32_t l0, int32_t l1, const cs_b
             if (raise) {
                 // drop the offline tail: same arrays, fewer sequences
                 preempted = true;
-                cur.num_seqs = sp->num_online_seqs;
-                cur.num_tokens = cur.num_seqs > 0 ? batch->h_cu_q_lens[cur.num_seqs] : 0;
+                cur = online_prefix(*batch, sp->num_online_seqs);
                 if (preempted_before_layer) *preempted_before_layer = l;
             }
         }
@@ -484,6 +583,10 @@ int32_t cs_debug_prefill_order(const cs_batch* batch, int32_t Hq, int32_t Hkv, i
     const PrefillPlan p = plan_prefill(batch, Hq, Hkv, D);
     for (int32_t i = 0; i < p.n_ordered && i < capacity; ++i) slots[i] = p.order.slot[i];
     return p.n_ordered;
+}
+
+void cs_debug_set_cu_count(int32_t cus) {
+    g_forced_cus.store(cus > 0 ? cus : 0);
 }
 
 void cs_set_decode_pages_ahead(int32_t pages) {

@@ -22,6 +22,10 @@ inline int check_launch(const char* what) {
     return e == hipSuccess ? CS_OK : hip_failed(e, what);
 }
 
+// Compute units of the current device (memoised per device; 256 where no device answers, and
+// whatever cs_debug_set_cu_count forces).  The launch plans size their grids by it.
+int32_t device_cus();
+
 // Host-side checks common to every entry point.  Return CS_OK or the error.
 int validate_pool(const cs_kv_pool* pool);
 int validate_batch(const cs_kv_pool* pool, const cs_batch* batch);

@@ -112,7 +112,7 @@ __global__ __launch_bounds__(D) void decode_merge_kernel(
         L += part_ml[slot * 2 + 1] * f;
         O += part_o[slot * D + d] * f;
     }
-    out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(E::pack(O / L, 0.f) & 0xffffu);
+    out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(E::pack(L > 0.f ? O / L : 0.f, 0.f) & 0xffffu);
 }
 
 template <class E>

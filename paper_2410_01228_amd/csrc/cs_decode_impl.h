@@ -342,7 +342,7 @@ __device__ __forceinline__ void decode_item(
         }
         const int32_t hq = g * G + head;
         if (it.n_splits == 1) {
-            const float r = O / L;
+            const float r = L > 0.f ? O / L : 0.f;                    // no key at all (every page id bad): zeros
             out[((int64_t)t * Hq + hq) * D + d] = (uint16_t)(E::pack(r, 0.f) & 0xffffu);
         } else {
             const int64_t slot = (int64_t)item * Hq + hq;

@@ -115,14 +115,17 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     p.max_ranges = 1;
     if (tiles == 0) return p;
     const int64_t wgs = tiles * Hkv;
-    if (wgs <= 192 && max_steps < 128) {
+    // The chip: `cus` compute units, two workgroup slots each.  (The counts in the comments below
+    // are those of the 256-CU part the rules were measured on.)
+    const int64_t cus = device_cus(), slots = 2 * cus;
+    if (wgs <= cus * 3 / 4 && max_steps < 128) {
         // few and short tiles: about four workgroups per CU, ranges of at least 32 steps
-        const int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 1023) / 1024);
+        const int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 4 * cus - 1) / (4 * cus));
         if (rs < max_steps) {
             p.range_steps = (int32_t)rs;
             p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
         }
-    } else if (wgs <= 1024) {
+    } else if (wgs <= 4 * cus) {
         // Up to four workgroups per CU the grid runs as one or two rounds over the 512 workgroup
         // slots (or leaves CUs empty), and a round that is not full costs almost as much as a
         // full one.  Cutting every tile into r key ranges multiplies the workgroups and divides
@@ -137,9 +140,9 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
         auto cost = [&](int r) -> double {
             const double W = (double)wgs * r;
             double c;
-            if (W <= 256) c = 0.76 * ((double)max_steps / r + 8);
-            else if (W <= 512) c = (0.76 + (W - 256) / 256 * 0.24) * ((double)max_steps / r + 8);
-            else c = 0.5 * (W / 512 + std::ceil(W / 512)) * (avg_steps / r + 8);
+            if (W <= cus) c = 0.76 * ((double)max_steps / r + 8);
+            else if (W <= slots) c = (0.76 + (W - cus) / cus * 0.24) * ((double)max_steps / r + 8);
+            else c = 0.5 * (W / slots + std::ceil(W / slots)) * (avg_steps / r + 8);
             if (r > 1) {
                 const double part_bytes = W * kTileCols * 16 * (D + 4) * 4.0;
                 c += (10.0 + 2.0 * part_bytes / 5.0e6) / 0.87;     // microseconds -> steps
@@ -166,12 +169,12 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     // slots the longest go first and the short ones fill the end; the natural order is the
     // opposite (a chunk's later tiles see more keys).  The order travels as a table in the kernel
     // arguments; a batch with more tiles than the table holds is simply walked backwards.
-    const int32_t first_round = 256 / Hkv;                       // slot positions of the first 256 workgroups
+    const int32_t first_round = (int32_t)(cus / Hkv);            // slot positions of the first round (a CU each)
     bool slots_fit = true;                                       // a table entry is 16 bits
     for (int32_t k = 0; k < n_listed; ++k) slots_fit = slots_fit && tile_list[k].slot < 65536;
-    if (p.max_ranges == 1 && wgs > 256) {
+    if (p.max_ranges == 1 && wgs > cus) {
         const bool listed = tiles == n_listed && slots_fit;
-        if (listed && wgs <= 512 && 256 % Hkv == 0) {
+        if (listed && wgs <= slots && cus % Hkv == 0) {
             std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
             const int32_t n_pair = (int32_t)tiles - first_round, n_solo = first_round - n_pair;
             for (int32_t k = 0; k < n_solo; ++k) p.order.slot[n_pair + k] = (uint16_t)tile_list[k].slot;
@@ -180,7 +183,7 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
                 p.order.slot[first_round + k] = (uint16_t)tile_list[n_solo + 2 * n_pair - 1 - k].slot;    // short
             }
             p.n_ordered = (int32_t)tiles;
-        } else if (wgs > 512) {
+        } else if (wgs > slots) {
             if (listed) {
                 std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
                 for (int32_t k = 0; k < n_listed; ++k) p.order.slot[k] = (uint16_t)tile_list[k].slot;

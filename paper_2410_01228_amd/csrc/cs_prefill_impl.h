@@ -60,20 +60,26 @@ __device__ __forceinline__ void wait_vmcnt() {
 // the lanes in mask_a fetch from base_a + off, the others from base_b + off (off = this
 // lane's byte offset inside a page's K or V block).  Scalar bases and a per-lane 32-bit
 // offset keep all address arithmetic out of the vector ALU; EXEC is narrowed to each lane
-// set in turn and restored.  Must be called with all 64 lanes active.  s_not_b64 writes SCC,
-// hence the clobber: without it the compiler may keep the carry of a 64-bit address addition
-// alive across this block (s_add_u32 before it, s_addc_u32 after it), and the address that
-// comes out is 4 GiB off.
+// set in turn -- the caller's active lanes inside mask_a, then those outside it -- and put
+// back as it was found.  (Every caller here runs with all 64 lanes active, and the counting of
+// outstanding copies relies on both instructions being issued; under divergent control flow
+// the block would still touch only the caller's lanes.)  The scalar logic instructions write
+// SCC, hence the clobber: without it the compiler may keep the carry of a 64-bit address
+// addition alive across this block (s_add_u32 before it, s_addc_u32 after it), and the address
+// that comes out is 4 GiB off.
 __device__ __forceinline__ void lds_dma16_two_pages(const void* base_a, const void* base_b, uint32_t off,
                                                     uint64_t mask_a, void* dst_wave_base) {
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)dst_wave_base;
-    asm volatile("s_mov_b32 m0, %0\n\t"
-                 "s_mov_b64 exec, %4\n\t"
-                 "global_load_lds_dwordx4 %1, %2\n\t"
-                 "s_not_b64 exec, exec\n\t"
-                 "global_load_lds_dwordx4 %1, %3\n\t"
-                 "s_mov_b64 exec, -1"
-                 :: "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0", "scc");
+    uint64_t saved_exec;
+    asm volatile("s_mov_b64 %0, exec\n\t"
+                 "s_mov_b32 m0, %1\n\t"
+                 "s_and_b64 exec, %0, %5\n\t"
+                 "global_load_lds_dwordx4 %2, %3\n\t"
+                 "s_andn2_b64 exec, %0, %5\n\t"
+                 "global_load_lds_dwordx4 %2, %4\n\t"
+                 "s_mov_b64 exec, %0"
+                 : "=&s"(saved_exec)
+                 : "s"(lds_addr), "v"(off), "s"(base_a), "s"(base_b), "s"(mask_a) : "memory", "m0", "scc");
 }
 
 // One LDS-DMA load whose lanes bring their own 64-bit global addresses (+ kImm bytes).  The

@@ -87,3 +87,73 @@ def assert_attention_close(gpu_out: torch.Tensor, ref: np.ndarray, what=""):
     rel = np.linalg.norm(g - r) / np.linalg.norm(r)
     assert err <= ABS_TOL and rel <= REL_TOL, "%s: max abs err %.3e, rel Frobenius err %.3e" % (what, err, rel)
     return err, rel
+
+
+# ---------------------------------------------------------------------------------------
+# Probe data: inputs on which NO page of a sequence can go missing unseen.
+#
+# With N(0,1) keys and thousands of them the softmax is flat: one dropped, duplicated or
+# swapped 16-key page moves an output by well under the 1e-2 bar.  So a probed sequence gets
+# one planted key in EVERY page -- token `probe_token(p)` of page p carries PROBE_GAIN * u_p
+# in every kv head, u_p a seeded N(0,1) bf16 vector of its own -- and the queries are aimed:
+# a (query row, head) that holds u_p puts (almost) all of its weight on that one key, so its
+# output is the V row of that token.  Lose page p, read another page in its place, mask one
+# key too many or shift a key range by a page, and that output changes by O(1).
+# A decode token has one row of Hq heads, so its pages are probed Hq at a time over several
+# attention calls (same pool, same lengths, same launch plan; only q differs).  A chunk has
+# q_len * Hq (row, head) pairs, enough to aim at all of its pages in one call.
+# ---------------------------------------------------------------------------------------
+PROBE_GAIN = 4.0      # a power of two: the planted key is exact in bf16
+
+
+def probe_vectors(seed: int, n_pages: int, D: int) -> torch.Tensor:
+    """u_p for p < n_pages: bf16 [n_pages, D]."""
+    g = torch.Generator()
+    g.manual_seed(77000 + seed)
+    return torch.randn((n_pages, D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+
+
+def probe_tokens(seed: int, n_keys: int, page_size: int = 16) -> np.ndarray:
+    """The planted token of every page of a sequence of n_keys keys: int64 [pages]."""
+    n_pages = (n_keys + page_size - 1) // page_size
+    r = np.random.default_rng(88000 + seed).integers(0, page_size, n_pages)
+    first = np.arange(n_pages, dtype=np.int64) * page_size
+    room = np.minimum(page_size, n_keys - first)          # the last page may be partly filled
+    return first + r % room
+
+
+def chunk_probe_targets(C: int, q_len: int, Hq: int, tokens: np.ndarray):
+    """(row, head) of a chunk that probes each page: distinct pairs, and the row can see the
+    planted token (its position C + row is not before it).  Returns int arrays [pages] (row -1:
+    more pages than pairs, this page is not probed)."""
+    rows = np.full(len(tokens), -1, np.int64)
+    heads = np.zeros(len(tokens), np.int64)
+    used = set()
+    nxt = 0                                               # next (row, head) pair in row-major order
+    for p, j in enumerate(tokens):
+        lo = max(0, int(j) - C)                           # first row that sees token j
+        if nxt < lo * Hq:
+            nxt = lo * Hq
+        while nxt < q_len * Hq and nxt in used:
+            nxt += 1
+        if nxt >= q_len * Hq:
+            continue
+        used.add(nxt)
+        rows[p], heads[p] = nxt // Hq, nxt % Hq
+        nxt += 1
+    return rows, heads
+
+
+def parity_counts(got: np.ndarray, ref: np.ndarray):
+    """(max abs error, relative Frobenius error, number of elements outside
+    |g - o| <= ABS_TOL + REL_TOL * |o|); the last is reported for information."""
+    d = np.abs(got - ref)
+    return float(d.max()), float(np.linalg.norm(got - ref) / np.linalg.norm(ref)), int((d > ABS_TOL + REL_TOL * np.abs(ref)).sum())
+
+
+def assert_rows_close(got: np.ndarray, ref: np.ndarray, what=""):
+    """The parity bar on already-selected rows (float64 arrays of equal shape)."""
+    assert np.isfinite(got).all(), what + ": non-finite output"
+    err, rel, nfail = parity_counts(got, ref)
+    assert err <= ABS_TOL and rel <= REL_TOL, "%s: max abs err %.3e, rel Frobenius err %.3e, %d elements outside the mixed bound" % (what, err, rel, nfail)
+    return err, rel, nfail

@@ -322,3 +322,94 @@ def test_debug_copy_argument_checks():
     assert lib.cs_debug_copy(0x1000, 0x2000, 24, None) == cs.CS_ERR_INVALID_ARG          # not a multiple of 16
     assert lib.cs_debug_copy(0x1008, 0x2000, 32, None) == cs.CS_ERR_INVALID_ARG          # misaligned
     assert lib.cs_debug_copy(None, None, 0, None) == cs.CS_OK
+
+
+def test_run_layers_checks_the_workspace_of_both_plans_before_anything_is_enqueued():
+    """A preempted iteration runs its remaining layers on the online prefix, whose plan can need
+    MORE workspace than the full batch's: fewer decode sequences are cut finer, and a lone long
+    chunk is cut into key ranges where many chunks fill the chip uncut.  cs_run_layers must ask
+    for the larger of the two and refuse up front, not at the safepoint (host-side checks only:
+    the device pointers here are never dereferenced)."""
+    lib = cs.lib()
+    Hq, Hkv, D = 32, 8, 128
+    p = _pool(L=8, P=1 << 20, Hkv=Hkv, D=D)
+    x = 0x5000
+    first = ctypes.c_int32(7)
+    # 512 equal decodes: nothing is cut.  Their first 16 alone: cut into pieces, partials needed.
+    b, keep = _batch([4096] * 512, [1] * 512, max_blocks=512)
+    full = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), Hq, Hkv, D)
+    assert full == 0
+    assert lib.cs_run_layers_workspace_bytes(ctypes.byref(b), 0, Hq, Hkv, D) == 0
+    assert lib.cs_run_layers_workspace_bytes(ctypes.byref(b), 512, Hq, Hkv, D) == 0
+    need = lib.cs_run_layers_workspace_bytes(ctypes.byref(b), 16, Hq, Hkv, D)
+    assert need > 0
+    sp = cs.cs_safepoint(None, cs.POLL_FN(0), None, 4, 16, 0)
+    args = (ctypes.byref(p), 0, 8, ctypes.byref(b), x, x, x, x, 0, 0, Hq, ctypes.c_float(0.1))
+    assert lib.cs_run_layers(*args, 0x6000, need - 16, ctypes.byref(sp), ctypes.byref(first), None) == cs.CS_ERR_WORKSPACE_TOO_SMALL
+    assert first.value == -1
+    assert lib.cs_run_layers(*args, None, 0, ctypes.byref(sp), ctypes.byref(first), None) == cs.CS_ERR_INVALID_ARG
+    # one long chunk online-first, 64 short chunks behind it: the prefix alone is cut into key ranges
+    b2, keep2 = _batch([8192] + [2048] * 64, [256] + [256] * 64, max_blocks=1024)
+    full2 = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b2), Hq, Hkv, D)
+    need2 = lib.cs_run_layers_workspace_bytes(ctypes.byref(b2), 1, Hq, Hkv, D)
+    assert need2 > full2
+    sp2 = cs.cs_safepoint(None, cs.POLL_FN(0), None, 4, 1, 0)
+    args2 = (ctypes.byref(p), 0, 8, ctypes.byref(b2), x, x, x, x, 0, 0, Hq, ctypes.c_float(0.1))
+    assert lib.cs_run_layers(*args2, 0x6000, need2 - 16, ctypes.byref(sp2), ctypes.byref(first), None) == cs.CS_ERR_WORKSPACE_TOO_SMALL
+    # shape and scale are refused before the first layer too
+    assert lib.cs_run_layers(ctypes.byref(p), 0, 8, ctypes.byref(b), x, x, x, x, 0, 0, 33, ctypes.c_float(0.1), 0x6000, need,
+                             ctypes.byref(sp), ctypes.byref(first), None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_run_layers(*args[:-1], ctypes.c_float(0.0), 0x6000, need, ctypes.byref(sp), ctypes.byref(first), None) == cs.CS_ERR_INVALID_ARG
+    assert lib.cs_run_layers_workspace_bytes(ctypes.byref(b), 16, 33, Hkv, D) == 0
+
+
+def test_plans_scale_with_the_compute_unit_count():
+    """The launch plans size their grids by the device's compute-unit count (256 where no device
+    answers).  With the count faked, the same batches are planned for a chip half and twice as
+    wide: equal decodes are cut until every CU has a workgroup, and a chunk that gives a 256-CU
+    chip exactly one tile workgroup per CU (cut in two there) fills a 128-CU chip's slots (left
+    alone) and is only half a round on 512 CUs (cut finer)."""
+    lib = cs.lib()
+
+    def decode_wgs(ctx, Hkv):
+        items, n, split = _plan(ctx, [1] * len(ctx), Hkv, 128)
+        return n * Hkv
+
+    def ranges(Hq, Hkv, P, C):
+        b, keep = _batch([C], [P], max_blocks=1 << 16)
+        by = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), Hq, Hkv, 128)
+        slots = (P * (Hq // Hkv) + 127) // 128 + 1
+        return by / (slots * Hkv * 8 * 16 * 132 * 4)
+
+    try:
+        seen = {}
+        for cus in (128, 256, 512):
+            lib.cs_debug_set_cu_count(cus)
+            seen[cus] = (decode_wgs([4095] * 16, 8), ranges(32, 8, 1024, 32768))
+            assert seen[cus][0] >= cus and seen[cus][0] < 2 * cus           # the fewest pieces that give every CU one
+        assert seen[128][1] == 0                                            # 256 tiles = both slots of 128 CUs
+        assert 1.9 < seen[256][1] < 2.1
+        assert seen[512][1] > 2.1
+        # the memo of the last plans is keyed by the count too: asking again after a change re-plans
+        lib.cs_debug_set_cu_count(128)
+        assert ranges(32, 8, 1024, 32768) == 0
+    finally:
+        lib.cs_debug_set_cu_count(0)
+    assert 1.9 < ranges(32, 8, 1024, 32768) < 2.1
+
+
+def test_workspace_query_is_remembered_but_never_stale():
+    """The plan of the last batches is memoised per thread; the key is the VALUES of the host
+    length arrays, so reusing a buffer with other lengths re-plans."""
+    lib = cs.lib()
+    b, keep = _batch([5000, 40000], [1, 1], max_blocks=4096)
+    a1 = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64)
+    a2 = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64)
+    assert a1 == a2 > 0
+    keep[0][0] = 10
+    keep[0][1] = 20                                        # same arrays, other lengths: two short decodes, nothing cut
+    assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64) == 0
+    keep[0][0] = 5000
+    keep[0][1] = 40000
+    assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64) == a1
+    assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 8, 2, 64) > a1     # other shape, other plan

@@ -1,6 +1,7 @@
 """Host-side check of the generated gfx950 code around the hand-written inline assembly.
 
-The LDS-DMA helper of the prefill kernel narrows EXEC with s_not_b64, which also writes SCC.
+The LDS-DMA helper of the prefill kernel narrows EXEC with scalar logic instructions (s_and_b64,
+s_andn2_b64; formerly s_not_b64), which also write SCC.
 If the asm statement did not declare that, the compiler could keep the carry of a 64-bit
 address addition alive across the block (s_add_u32 before it, s_addc_u32 after it); the
 address then comes out 4 GiB off and the copy faults.  This test compiles every file whose kernels
@@ -40,7 +41,7 @@ def scc_reads_after_asm(asm_text):
             while "ASMEND" not in lines[j]:
                 body.append(lines[j].strip())
                 j += 1
-            if any(b.startswith("s_not_b64") for b in body):
+            if any(b.startswith(("s_not_b64", "s_and_b64", "s_andn2_b64")) for b in body):
                 k = j + 1
                 while k < len(lines):
                     t = lines[k].strip()
@@ -72,6 +73,8 @@ def test_scanner_sees_a_planted_hazard():
     good = bad.replace("s_addc_u32 s67, s23, s39", "s_add_i32 s7, s60, s21\n\ts_addc_u32 s67, s23, s39")
     assert len(scc_reads_after_asm(bad)) == 1
     assert scc_reads_after_asm(good) == []
+    bad2 = bad.replace("s_not_b64 exec, exec", "s_andn2_b64 exec, s[4:5], s[6:7]")
+    assert len(scc_reads_after_asm(bad2)) == 1
 
 
 @pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="no hipcc")
@@ -89,3 +92,5 @@ def test_no_scc_value_lives_across_the_dma_asm(tmp_path, src):
     assert hazards == [], "SCC read after an inline-asm block that rewrote it: %r" % hazards[:5]
     # and the statement says so itself
     assert '"scc"' in open(ASM_HOME).read()
+    # EXEC is put back as it was found, never forced to all lanes
+    assert "s_mov_b64 exec, -1" not in text and "s_andn2_b64 exec" in text

@@ -433,3 +433,6 @@ def test_bad_page_ids_are_skipped_and_harm_no_other_sequence(page_size):
         good = [s for s in range(b.S) if s not in bad_seqs]
         ref = st.oracle_attention(good)
         assert_attention_close(out, ref, "good sequences beside bad page ids, page size %d" % page_size)
+        # a decode with no valid page at all has no key: its row is written as zeros, not 0/0
+        t4 = int(b.cu_q_lens[4])
+        assert (out[t4].float() == 0).all()
