@@ -107,10 +107,13 @@ PROBE_GAIN = 4.0      # a power of two: the planted key is exact in bf16
 
 
 def probe_vectors(seed: int, n_pages: int, D: int) -> torch.Tensor:
-    """u_p for p < n_pages: bf16 [n_pages, D]."""
+    """u_p for p < n_pages: bf16 [n_pages, D], random directions of squared length D (so that
+    every probe's own score, PROBE_GAIN * sqrt(D), stands the same distance above the others')."""
     g = torch.Generator()
     g.manual_seed(77000 + seed)
-    return torch.randn((n_pages, D), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    u = torch.randn((n_pages, D), generator=g, dtype=torch.float32)
+    u = u * (D ** 0.5) / u.norm(dim=1, keepdim=True)
+    return u.to(torch.bfloat16)
 
 
 def probe_tokens(seed: int, n_keys: int, page_size: int = 16) -> np.ndarray:
