@@ -75,7 +75,8 @@ typedef enum {
     CS_ERR_WORKSPACE_TOO_SMALL = -3,
     CS_ERR_STAGING_TOO_SMALL = -4,
     CS_ERR_HIP = -5,                /* a launch failed; see cs_last_hip_error()          */
-    CS_ERR_NO_HOST_PAGES = -6       /* the host page store has no free run long enough   */
+    CS_ERR_NO_HOST_PAGES = -6,      /* the host page store has no free run long enough   */
+    CS_ERR_STATIC_SCRATCH_TOO_SMALL = -7   /* the batch's plan needs more than CS_STATIC_SCRATCH_BYTES */
 } cs_status;
 
 #define CS_PAGE_SIZE 16
@@ -153,6 +154,26 @@ int cs_paged_attention_mixed_f16(const cs_kv_pool* pool, int32_t layer, const cs
                                  const void* q, void* out, int32_t num_q_heads,
                                  float softmax_scale, void* workspace, size_t workspace_bytes,
                                  void* stream);
+
+/* For callers that cannot allocate device memory or bring a workspace -- code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc: cs_paged_attention_mixed (bf16)
+ * with its workspace taken from a buffer of CS_STATIC_SCRATCH_BYTES that lives in the library's
+ * code object (one copy per device the library runs on, held until the process ends).  The call
+ * allocates and frees nothing, on the device or through any library.  Inputs and outputs are the
+ * caller's as before; results are bit-identical to cs_paged_attention_mixed on the same batch.
+ *   - a batch whose launch plan needs more than the buffer holds is refused with
+ *     CS_ERR_STATIC_SCRATCH_TOO_SMALL and nothing is enqueued (ask
+ *     cs_paged_attention_workspace_bytes() beforehand; most batches need nothing at all);
+ *   - all calls on one device share that device's buffer, which keeps the last call's contents:
+ *     nothing in it needs clearing, but two calls that overlap in time on one device (two
+ *     streams, two threads) race on it.  Calls on one stream, or otherwise ordered, are safe;
+ *   - the buffer's device address is looked up on the first call on each device
+ *     (hipGetSymbolAddress); make that first call outside a stream capture. */
+#define CS_STATIC_SCRATCH_BYTES (64u << 20)
+size_t cs_static_scratch_bytes(void);
+int cs_paged_attention_mixed_static(const cs_kv_pool* pool, int32_t layer, const cs_batch* batch,
+                                    const void* q, void* out, int32_t num_q_heads,
+                                    float softmax_scale, void* stream);
 
 /* Checkpoint gather (Sec. 5: the KV of scattered pages is gathered into one contiguous
  * buffer and transferred once; Sec. 4.4: only newly filled pages are checkpointed).

@@ -20,6 +20,7 @@ CS_ERR_WORKSPACE_TOO_SMALL = -3
 CS_ERR_STAGING_TOO_SMALL = -4
 CS_ERR_HIP = -5
 CS_ERR_NO_HOST_PAGES = -6
+CS_ERR_STATIC_SCRATCH_TOO_SMALL = -7
 PAGE = 16
 
 
@@ -95,6 +96,9 @@ def lib():
         L.cs_paged_attention_workspace_bytes.argtypes = [BP, i32, i32, i32]
         for f in (L.cs_paged_attention_mixed, L.cs_paged_attention_mixed_f16):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp, sz, vp]
+        L.cs_paged_attention_mixed_static.restype = ctypes.c_int
+        L.cs_paged_attention_mixed_static.argtypes = [PP, i32, BP, vp, vp, i32, ctypes.c_float, vp]
+        L.cs_static_scratch_bytes.restype, L.cs_static_scratch_bytes.argtypes = sz, []
         for f in (L.cs_kv_ckpt_gather, L.cs_kv_ckpt_restore, L.cs_kv_ckpt_gather_tokens, L.cs_kv_ckpt_restore_tokens):
             f.restype, f.argtypes = ctypes.c_int, [PP, i32, i32, vp, i32, vp, sz, vp]
         for f in (L.cs_kv_ckpt_save, L.cs_kv_ckpt_load):
@@ -136,7 +140,7 @@ def lib():
 
 EXPORTS = [
     "cs_page_bytes", "cs_pool_page_bytes", "cs_kv_append", "cs_paged_attention_workspace_bytes",
-    "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
+    "cs_paged_attention_mixed", "cs_paged_attention_mixed_f16", "cs_paged_attention_mixed_static", "cs_static_scratch_bytes", "cs_kv_ckpt_gather", "cs_kv_ckpt_restore", "cs_kv_ckpt_gather_tokens",
     "cs_kv_ckpt_restore_tokens", "cs_kv_ckpt_save",
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
@@ -247,6 +251,17 @@ def cs_paged_attention_mixed_f16(pool: Pool, layer: int, batch: Batch, q: torch.
     _check(lib().cs_paged_attention_mixed_f16(ctypes.byref(pool.c), layer, ctypes.byref(batch.c), _ptr(q),
                                               _ptr(out), Hq, softmax_scale, _ptr(workspace), wb, _stream(stream)),
            "cs_paged_attention_mixed_f16")
+
+
+def cs_paged_attention_mixed_static(pool: Pool, layer: int, batch: Batch, q: torch.Tensor, out: torch.Tensor,
+                                    Hq: int, softmax_scale: float, stream=None):
+    """cs_paged_attention_mixed with the library's own static scratch as workspace (allocates nothing)."""
+    _check(lib().cs_paged_attention_mixed_static(ctypes.byref(pool.c), layer, ctypes.byref(batch.c), _ptr(q), _ptr(out),
+                                                 Hq, softmax_scale, _stream(stream)), "cs_paged_attention_mixed_static")
+
+
+def cs_static_scratch_bytes() -> int:
+    return int(lib().cs_static_scratch_bytes())
 
 
 def cs_kv_ckpt_gather(pool: Pool, layer_begin: int, layer_end: int, page_ids: torch.Tensor,

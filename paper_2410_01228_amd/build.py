@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libconserve_kv.so")
-SOURCES = ["cs_api.hip", "cs_copy_kernels.hip", "cs_decode.hip", "cs_prefill.hip", "cs_mixed.hip", "cs_page_map.hip"]
+SOURCES = ["cs_api.hip", "cs_copy_kernels.hip", "cs_decode.hip", "cs_prefill.hip", "cs_mixed.hip", "cs_page_map.hip", "cs_static_scratch.hip"]
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
     # packed fp32 arithmetic stays off: the compiler must not form v_pk_*_f32

@@ -611,6 +611,7 @@ const char* cs_status_string(int status) {
         case CS_ERR_STAGING_TOO_SMALL: return "staging buffer too small";
         case CS_ERR_HIP: return "HIP error";
         case CS_ERR_NO_HOST_PAGES: return "no free run of host pages";
+        case CS_ERR_STATIC_SCRATCH_TOO_SMALL: return "the batch needs more scratch than the library's static buffer holds";
         default: return "unknown status";
     }
 }
