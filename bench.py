@@ -1,15 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the co-serving attention / KV hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--detail]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--only] [--detail]
 
 One "step" is one pass of the per-layer hot path over one synthetic batch: cs_kv_append of
 the step's new K/V followed by cs_paged_attention_mixed (for the checkpoint workload also
 cs_kv_ckpt_gather + cs_kv_ckpt_restore over all layers).  Inputs are resident in HBM before
 the timed region.  Prints ONE JSON line on stdout; everything else goes to stderr.
 
-The default workload is the Llama-3.1-8B decode batch (256 sequences, context uniform in
-[512, 4096], 32/8 heads, head dim 128, 16-token pages) the headline metric is quoted on.
+The default workload is the largest single-GPU mixed batch: the Llama-3.1-70B long-context
+step (128 decodes on contexts log-uniform in [2048, 32768] plus one 1024-token chunk on
+30720 keys; 64/8 heads, head dim 128, 16-token pages).  Its decode-only and prefill-only
+sub-batches are timed as legs of their own, so the line carries the decode path's HBM
+fraction and the prefill path's matrix-core fraction beside the whole call; the key
+`workloads` holds the legs of the other four workloads from the same run.
 """
 import argparse
 import json
@@ -30,6 +34,9 @@ WORKLOADS = ["tiny", "llama8b_decode", "qwen7b_mixed", "llama70b_long", "qwen14b
 _ONE_GRID = "prefill tiles and decode work items in one grid"
 KERNEL_OF = {("llama8b_decode", "paged_attention_mixed"): ("cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16,", "the call's only kernel here"),
              ("qwen14b_ckpt", "ckpt_gather"): ("cs::page_copy_kernel<true>", ""),
+             ("qwen14b_ckpt", "ckpt_restore"): ("cs::page_copy_kernel<false>", ""),
+             ("qwen7b_mixed", "decode_only"): ("cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16,", ""),
+             ("llama70b_long", "decode_only"): ("cs::decode_split_kernel<128, cs::ItemsInArgs, cs::Bf16,", ""),
              ("qwen7b_mixed", "paged_attention_mixed"): ("cs::mixed_kernel<128, cs::Bf16,", _ONE_GRID),
              ("llama70b_long", "paged_attention_mixed"): ("cs::mixed_kernel<128, cs::Bf16,", _ONE_GRID),
              ("qwen14b_ckpt", "paged_attention_mixed"): ("cs::mixed_kernel<128, cs::Bf16,", _ONE_GRID),
@@ -56,9 +63,20 @@ def fill_randn_bf16(t, gen, dtype=None):
 class Leg:
     """One timed call of the step with its algorithmic work."""
 
-    def __init__(self, name, fn, bound, work, unit_count=None):
-        self.name, self.fn, self.bound, self.work = name, fn, bound, work
+    def __init__(self, name, fn, bound, work, also=None):
+        """bound / work: the roofline the call is priced against and its algorithmic work (bytes
+        for "hbm", flops for "mfma").  also: (bound, work) of the other kind of work the same
+        launch does (the fused grid of a mixed batch reads the decode sequences' K/V AND multiplies
+        the chunks' tiles); it is reported beside the main figure."""
+        self.name, self.fn, self.bound, self.work, self.also = name, fn, bound, work, also
         self.us = self.us_median = self.us_min = None
+
+    def also_record(self):
+        bound, work = self.also
+        peak = HBM_PEAK if bound == "hbm" else MFMA_BF16_PEAK
+        ach = work / (self.us * 1e-6)
+        return {"bound": bound, "achieved": round(ach / (1e9 if bound == "hbm" else 1e12), 2),
+                "unit": "GB/s" if bound == "hbm" else "TFLOP/s", "frac": round(ach / peak, 4), "work": work}
 
     def roofline(self, traffic=None):
         peak = HBM_PEAK if self.bound == "hbm" else MFMA_BF16_PEAK
@@ -125,10 +143,16 @@ def build(name, f16=False, page_size=16):
         legs.append(Leg("ckpt_gather", lambda: cs.cs_kv_ckpt_gather(pool, 0, sh.L, dirty, staging), "hbm", cp_bytes))
         legs.append(Leg("ckpt_restore", lambda: cs.cs_kv_ckpt_restore(pool, 0, sh.L, fresh, staging), "hbm", cp_bytes))
     legs.append(Leg("kv_append", lambda: cs.cs_kv_append(pool, layer[0], bb, k_new, v_new), "hbm", append_bytes))
+    # the attention call is priced against the roofline its larger ideal time belongs to; in a mixed
+    # batch the bytes of the decode side also include the K/V the chunks must read once
     att_bound = "hbm" if pre_flops / MFMA_BF16_PEAK < dec_bytes / HBM_PEAK else "mfma"
+    att_bytes = dec_bytes + pre_bytes
+    also = None
+    if dec_bytes and pre_flops:
+        also = ("mfma", pre_flops) if att_bound == "hbm" else ("hbm", att_bytes)
     legs.append(Leg("paged_attention_mixed",
                     lambda: attend(pool, layer[0], bb, q, out, sh.Hq, sh.scale, ws),
-                    att_bound, dec_bytes if att_bound == "hbm" else pre_flops))
+                    att_bound, att_bytes if att_bound == "hbm" else pre_flops, also))
 
     detail = []
     n_on = b.extra.get("n_online", 0)
@@ -440,7 +464,7 @@ def preemption_loop(b, layers=32, iters=10):
     return r
 
 
-def fit_latency_model(reps=8):
+def fit_latency_model(reps=8, dump=""):
     """Offline profiler of the paper's latency model, restricted to this path: time
     append + attention on a grid of (compute tokens, context) batches at the Llama-3.1-8B
     shape, least-squares fit of the per-token, attention, memory-access and constant terms,
@@ -488,6 +512,9 @@ def fit_latency_model(reps=8):
         e1.record()
         torch.cuda.synchronize()
         samples.append((batch, e0.elapsed_time(e1) / reps * 1e-3))
+    if dump:
+        with open(dump, "w") as f:
+            json.dump([{"batch": bt, "seconds": t} for bt, t in samples], f)
     m, rel = fit(samples)
     import numpy as np
     big = np.array([t >= 150e-6 for _, t in samples])           # batches long enough to matter to an SLO
@@ -558,13 +585,70 @@ def read_traffic(name, kernel):
     return best[0], best[1]
 
 
+def leg_record(leg, workload, dtype="bf16", page_size=16, fused=True):
+    """One leg of the JSON line: times, roofline fraction against the leg's own bound and, where a
+    committed counter summary covers the leg's kernel, that kernel's measured HBM bytes per launch."""
+    r = leg.roofline()
+    rec = {"us": round(leg.us, 2), "us_median": round(leg.us_median, 2), "us_min": round(leg.us_min, 2),
+           "bound": leg.bound, "frac": r["frac"], "achieved": r["achieved"], "unit": r["unit"], "work": leg.work}
+    if getattr(leg, "also", None):
+        rec["also"] = leg.also_record()
+    prefix, note = KERNEL_OF.get((workload, leg.name), (None, ""))
+    if prefix and dtype == "f16":
+        prefix = prefix.replace("cs::Bf16", "cs::F16")
+    if prefix and page_size == 16 and (fused or "mixed_kernel" not in prefix):
+        full, traffic = read_traffic(workload, prefix)
+        if full is None:
+            log("ERROR: profiles/%s_hbm_traffic.txt has no row for kernel '%s...' (leg %s): the committed counter summary "
+                "is stale -- regenerate it from this binary" % (workload, prefix, leg.name))
+            rec["traffic_error"] = "no row for %s in profiles/%s_hbm_traffic.txt" % (prefix, workload)
+        rec["kernel"] = (full or prefix + " ...>") + (" (%s)" % note if note else "")
+        rec["traffic"] = traffic
+        rec["traffic_source"] = ("profiles/%s_hbm_traffic.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this kernel on this "
+                                 "workload, scaled by the plain copy kernel's readings; a committed summary, not measured in this run"
+                                 % workload)
+    return rec
+
+
+def measure(name, steps, warmup, args, sub_batches=True):
+    """Build one workload, time its step (and, for a mixed one, its decode-only and prefill-only
+    sub-batches), and return (batch, info, legs, detail legs, seconds per step)."""
+    b, legs, detail, info = build(name, f16=args.dtype == "f16", page_size=args.page_size)
+    log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
+        % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))
+    sec_per_step = time_legs(legs, steps, warmup)
+    if sub_batches and detail:
+        time_legs(detail, steps, warmup)
+    else:
+        detail = []
+    for leg in legs + detail:
+        r = leg.roofline()
+        extra = ""
+        if getattr(leg, "also", None):
+            a = leg.also_record()
+            extra = "  + %.1f %s (%.1f%% of %s peak) in the same launch" % (a["achieved"], a["unit"], 100 * a["frac"], a["bound"])
+        log("  %-24s %9.1f us  %10.1f %s  (%.1f%% of %s peak)%s" % (leg.name, leg.us, r["achieved"], r["unit"], 100 * r["frac"], r["bound"], extra))
+    return b, info, legs, detail, sec_per_step
+
+
+def dominant_leg(name, legs, detail):
+    """The leg whose kernel the roofline object is quoted for: the checkpoint gather for the
+    checkpoint workload, otherwise the attention call (whose one grid holds both kinds of work in
+    a mixed batch; its decode bytes and prefill flops are then both reported)."""
+    by_name = {l.name: l for l in legs}
+    return by_name["ckpt_gather"] if name == "qwen14b_ckpt" else by_name["paged_attention_mixed"]
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="llama8b_decode", choices=WORKLOADS)
-    ap.add_argument("--detail", action="store_true", help="also time the decode-only and prefill-only sub-batches")
+    ap.add_argument("--workload", default="llama70b_long", choices=WORKLOADS,
+                    help="the workload the headline value is quoted on (default: the largest single-GPU mixed batch)")
+    ap.add_argument("--only", action="store_true", help="time only --workload (no `workloads` key with the other four)")
+    ap.add_argument("--detail", action="store_true",
+                    help="also run the workload's extra experiments (preemption loop, graph replay, checkpoint pipeline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--page-size", type=int, default=16, choices=[16, 8],
                     help="tokens per page of the pool (16: the paper's; 8: the smaller variant)")
@@ -577,6 +661,7 @@ def main():
     ap.add_argument("--append-sweep", action="store_true", help="also time cs_kv_append over growing token counts")
     ap.add_argument("--fit-latency-model", action="store_true",
                     help="also run the (P, C) timing grid and fit the paper's latency model to this path")
+    ap.add_argument("--dump-latency-samples", default="", help="with --fit-latency-model: write the timed samples to this JSON file")
     ap.add_argument("--calibration-copy-gib", type=float, default=0.0,
                     help="also run the plain copy kernel on this many GiB three times (the known-size "
                          "reference that hardware byte counters are scaled by)")
@@ -603,38 +688,19 @@ def main():
         del src, dst
     if args.page_size != 16 and args.workload not in ("llama8b_decode", "qwen7b_mixed", "llama70b_long"):
         sys.exit("bench.py: --page-size 8 is for the workloads llama8b_decode, qwen7b_mixed and llama70b_long")
-    b, legs, detail, info = build(args.workload, f16=args.dtype == "f16", page_size=args.page_size)
-    log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
-        % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))
-    sec_per_step = time_legs(legs, args.steps, args.warmup)
-    for leg in legs:
-        r = leg.roofline()
-        log("  %-24s %9.1f us  %10.1f %s  (%.1f%% of %s peak)" % (leg.name, leg.us, r["achieved"], r["unit"], 100 * r["frac"], r["bound"]))
-    if args.detail and detail:
-        time_legs(detail, args.steps, args.warmup)
-        for leg in detail:
-            r = leg.roofline()
-            log("  %-24s %9.1f us  %10.1f %s  (%.1f%% of %s peak)" % (leg.name, leg.us, r["achieved"], r["unit"], 100 * r["frac"], r["bound"]))
 
+    fused = not args.separate_launches
+    b, info, legs, detail, sec_per_step = measure(args.workload, args.steps, args.warmup, args)
     by_name = {l.name: l for l in legs}
     att_us = by_name["kv_append"].us + by_name["paged_attention_mixed"].us
-    if args.workload == "qwen14b_ckpt":
-        dom = by_name["ckpt_gather"]
-    elif args.detail and detail and by_name["paged_attention_mixed"].bound == "mfma":
-        dom = detail[1]
-    else:
-        dom = by_name["paged_attention_mixed"]
-    dom_prefix, dom_note = KERNEL_OF.get((args.workload, dom.name), (None, ""))
-    if dom_prefix and args.dtype == "f16":
-        dom_prefix = dom_prefix.replace("cs::Bf16", "cs::F16")
-    if args.separate_launches and dom_prefix and "mixed_kernel" in dom_prefix:
-        dom_prefix = None
-    if args.page_size != 16:
-        dom_prefix = None                          # the committed counter summaries are of 16-token pages
-    dom_full, dom_traffic = read_traffic(args.workload, dom_prefix) if dom_prefix else (None, None)
-    dom_kernel = dom_full or (dom_prefix + " ...>" if dom_prefix and dom_prefix.endswith(",") else dom_prefix) or dom.name
-    if dom_note:
-        dom_kernel += " (%s)" % dom_note
+    dom = dominant_leg(args.workload, legs, detail)
+    dom_rec = leg_record(dom, args.workload, args.dtype, args.page_size, fused)
+    roofline = dict(dom.roofline(dom_rec.get("traffic")), kernel=dom_rec.get("kernel", dom.name),
+                    us=dom_rec["us"], call=dom.name)
+    if "traffic_source" in dom_rec:
+        roofline["traffic_source"] = dom_rec["traffic_source"]
+    if "also" in dom_rec:
+        roofline["also"] = dom_rec["also"]
     result = {
         "metric": "mixed-batch paged-attn tokens/s per layer",
         "value": round(info["T"] / (att_us * 1e-6), 1),
@@ -646,28 +712,49 @@ def main():
         "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
                    "page_size": args.page_size, "layers_per_step": 1,
                    "step": "+".join(l.name for l in legs)},
-        "roofline": dict(dom.roofline(dom_traffic), kernel=dom_kernel),
-        "legs": {l.name: {"us": round(l.us, 2), "us_median": round(l.us_median, 2), "us_min": round(l.us_min, 2),
-                          "frac": l.roofline()["frac"], "bound": l.bound} for l in legs + (detail if args.detail else [])},
+        "roofline": roofline,
+        "legs": {l.name: leg_record(l, args.workload, args.dtype, args.page_size, fused) for l in legs + detail},
     }
-    if args.append_sweep:
-        del info["keep"][:]
-        result["append_sweep"] = append_sweep()
-    if args.fit_latency_model:
-        del info["keep"][:]
-        result["latency_model"] = fit_latency_model()
-    if args.detail and args.workload == "qwen7b_mixed":
-        del info["keep"][:]
-        result["preemption_loop"] = preemption_loop(b)
-    if args.detail and args.workload == "tiny":
-        del info["keep"][:]
-        result["graph_replay"] = graph_replay(b)
     if args.detail and args.workload == "qwen14b_ckpt":
         result["ckpt_pipeline"] = checkpoint_pipeline(info)
+    cpu_b = b
+    del info["keep"][:]
+    del legs, detail, dom, by_name
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    if not args.only:
+        # the other workloads, from the same run: every call of their step and, for the mixed ones,
+        # the two attention paths on their own sub-batches
+        result["workloads"] = {}
+        o_steps, o_warm = min(args.steps, 20), min(args.warmup, 5)
+        for name in WORKLOADS:
+            if name == args.workload or (args.page_size != 16 and name in ("tiny", "qwen14b_ckpt")):
+                continue
+            ob, oinfo, olegs, odetail, osec = measure(name, o_steps, o_warm, args)
+            on = {l.name: l for l in olegs}
+            result["workloads"][oinfo["name"]] = {
+                "num_seqs": oinfo["S"], "num_tokens": oinfo["T"], "steps": o_steps, "warmup": o_warm,
+                "tokens_per_s": round(oinfo["T"] / ((on["kv_append"].us + on["paged_attention_mixed"].us) * 1e-6), 1),
+                "ms_per_step": round(osec * 1e3, 4),
+                "legs": {l.name: leg_record(l, name, args.dtype, args.page_size, fused) for l in olegs + odetail}}
+            del oinfo["keep"][:]
+            del olegs, odetail, on, ob, oinfo
+            gc.collect()
+            torch.cuda.empty_cache()
+    if args.append_sweep:
+        result["append_sweep"] = append_sweep()
+    if args.fit_latency_model:
+        result["latency_model"] = fit_latency_model(dump=args.dump_latency_samples)
+    if args.detail and args.workload == "qwen7b_mixed":
+        result["preemption_loop"] = preemption_loop(cpu_b)
+    if args.detail and args.workload == "tiny":
+        result["graph_replay"] = graph_replay(cpu_b)
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(b)
+        result["cpu_baseline"] = cpu_baseline(cpu_b)
         if args.workload == "qwen14b_ckpt":
-            result["cpu_baseline_copies"] = cpu_copy_baseline(b)
+            result["cpu_baseline_copies"] = cpu_copy_baseline(cpu_b)
     print(json.dumps(result), flush=True)
 
 

@@ -37,3 +37,27 @@ def test_can_schedule_matches_brute_force():
     # more context -> fewer tokens fit (the point of a context-aware model)
     assert m.can_schedule(batch, 2048, 30000, 2e-4) < m.can_schedule(batch, 2048, 0, 2e-4)
     assert m.can_schedule(batch, 2048, 0, 1e-9) == 0
+
+
+def test_fit_never_returns_a_negative_coefficient():
+    """Timings in which the per-token term is not identifiable (noise larger than its effect) must
+    come back with that term at zero, not negative -- an unconstrained fit of these samples trades
+    it against the constant -- and can_schedule on the result stays monotone in context."""
+    import pytest
+    true = LatencyModel(k_p=0.0, k2=1.5e-11, k4=6e-10, k5=2.2e-5)
+    rng = np.random.default_rng(8)
+    samples = []
+    for _ in range(40):
+        batch = [(int(rng.integers(1, 2048)), int(rng.integers(0, 30000))) for _ in range(int(rng.integers(1, 4)))]
+        samples.append((batch, true.predict(batch) * float(1 + 0.05 * rng.standard_normal())))
+    A = np.stack([features(b) for b, _ in samples])
+    y = np.array([t for _, t in samples])
+    free, *_ = np.linalg.lstsq(A / y[:, None], np.ones(len(y)), rcond=None)
+    assert free.min() < 0, "the planted case must be one where the unconstrained fit goes negative"
+    m, rel = fit(samples)
+    assert m.coef.min() >= 0 and rel.mean() < 0.06
+    batch = [(1, 4000)] * 64
+    fits = [m.can_schedule(batch, 2048, ctx, 5e-4) for ctx in (0, 4000, 16000, 32000)]
+    assert fits == sorted(fits, reverse=True) and fits[0] > fits[-1] >= 0
+    with pytest.raises(ValueError):
+        LatencyModel(k_p=-1e-9, k2=1e-11, k4=1e-10, k5=1e-5).can_schedule(batch, 100, 0, 1e-3)
