@@ -436,3 +436,24 @@ def test_bad_page_ids_are_skipped_and_harm_no_other_sequence(page_size):
         # a decode with no valid page at all has no key: its row is written as zeros, not 0/0
         t4 = int(b.cu_q_lens[4])
         assert (out[t4].float() == 0).all()
+
+
+@pytest.mark.parametrize("cus", [64, 128, 304, 512])
+def test_plans_for_other_compute_unit_counts_are_still_correct(cus):
+    """The launch plans are sized by the device's compute-unit count.  Planned as if the chip had a
+    quarter, half, a fifth more or twice the units it has -- other split sizes, other numbers of
+    key ranges, other tile orders -- the same batches must still meet the oracle (a plan sized
+    for another chip is slower on this one, never wrong)."""
+    cs.cs_debug_set_cu_count(cus)
+    try:
+        # decode sequences that are cut, a chunk cut into key ranges, chunks whose tiles are reordered
+        sh = synth.Shape(8, 2, 128)
+        b = synth.make_batch(sh, [5000, 300, 2500, 3000, 0, 700], [1, 1, 1, 40, 33, 200], synth.generator(81))
+        out, st, _, _ = run_step(b, 81, q_gain=3.0)
+        assert_attention_close(out, st.oracle_attention(), "planned for %d CUs, mixed" % cus)
+        sh = synth.Shape(32, 8, 128)
+        b = synth.make_batch(sh, [900, 100, 400], [320, 256, 290], synth.generator(82))
+        out, st, _, _ = run_step(b, 82, fuse=2)
+        assert_attention_close(out, st.oracle_attention(), "planned for %d CUs, chunks" % cus)
+    finally:
+        cs.cs_debug_set_cu_count(0)
