@@ -90,3 +90,39 @@ def test_static_scratch_entry_point_refuses_what_does_not_fit_and_passes_errors_
     empty = cs.cs_batch(0, 0, None, 0, None, None, None, None)
     assert lib.cs_paged_attention_mixed_static(ctypes.byref(pool.c), 0, ctypes.byref(empty), None, None, sh.Hq,
                                                ctypes.c_float(sh.scale), stream) == cs.CS_OK
+
+
+def test_static_scratch_entry_point_under_graph_capture():
+    """What the entry point is for: a caller that records its layer loop into a HIP graph and so
+    cannot allocate a workspace.  The first call on the device runs eagerly (it looks the
+    buffer's address up); then append + attention are captured and replayed three times, with
+    eager work between the replays, each replay bit-identical to the workspace entry point."""
+    lib = cs.lib()
+    sh = synth.Shape(8, 2, 128)
+    b, st, pool, bb, q = make([7000, 200, 3100, 2000], [1, 1, 1, 24], 304, sh)
+    assert cs.cs_paged_attention_workspace_bytes(bb, sh.Hq, sh.Hkv, sh.D) > 0
+    want = torch.full((b.T, sh.Hq, sh.D), float("nan"), dtype=torch.bfloat16, device="cuda")
+    cs.cs_paged_attention_mixed(pool, 0, bb, q, want, sh.Hq, sh.scale, cs.workspace_for(bb, sh.Hq, sh.Hkv, sh.D))
+    out = torch.full_like(want, float("nan"))
+    k_new, v_new = st.k_new.cuda(), st.v_new.cuda()
+
+    def run():
+        cs.cs_kv_append(pool, 0, bb, k_new, v_new)
+        cs.cs_paged_attention_mixed_static(pool, 0, bb, q, out, sh.Hq, sh.scale)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        run()                                                  # eager first call: address lookup, warm-up
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int16), want.view(torch.int16))
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        run()
+    for replay in range(3):
+        out.fill_(float("nan"))
+        assert torch.isfinite(torch.randn(1 << 16, device="cuda").sum()).item()      # eager work and a synchronisation
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), "replay %d differs" % replay
