@@ -1,6 +1,8 @@
 // C ABI entry points: host-side validation and launch planning.  See include/conserve_kv.h
-// for the contract of each call.
+// for the contract of each call.  This file holds no device code, so that it can be built and
+// exercised on the host alone (tests/host_sanitize).
 #include <algorithm>
+#include <cmath>
 #include "cs_common.h"
 #include <atomic>
 #include <vector>
@@ -179,6 +181,121 @@ DecodePlan plan_decode(const cs_batch* b, int32_t Hkv, int32_t head_dim) {
             for (int32_t i = 0; i < recs[r].k; ++i)
                 p.arg_items.e[item++] = (uint32_t)recs[r].seq | ((uint32_t)i << 16) | ((uint32_t)recs[r].k << 24);
         }
+    }
+    return p;
+}
+
+// Host plan of the key-range split (a pure function of the host lengths).
+PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) {
+    PrefillPlan p = {};
+    const int32_t G = Hq / Hkv;
+    int64_t total_steps = 0, tiles = 0;
+    int32_t max_steps = 0, first = -1;
+    struct Tile { int32_t steps, slot; };
+    Tile tile_list[kMaxSlotOrder];
+    int32_t n_listed = 0;
+    for (int32_t s = 0; s < b->num_seqs; ++s) {
+        const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+        if (ql <= 1) continue;
+        if (first < 0) first = s;
+        const int32_t C = b->h_ctx_lens[s];
+        const int32_t n_ct = ((ql + 15) >> 4) * G;
+        for (int32_t ct0 = 0; ct0 < n_ct; ct0 += kTileCols) {
+            const int32_t tb_max = (std::min(ct0 + kTileCols, n_ct) - 1) / G;
+            const int32_t n_keys = C + std::min(ql, (tb_max + 1) * 16);
+            const int32_t steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
+            total_steps += steps;
+            max_steps = std::max(max_steps, steps);
+            if (tiles < kMaxSlotOrder)
+                tile_list[n_listed++] = Tile{steps, (int32_t)(prefill_slot_start(b->h_cu_q_lens[s], s, G) + ct0 / kTileCols)};
+            ++tiles;
+        }
+    }
+    p.range_steps = std::max(max_steps, 1);
+    p.max_ranges = 1;
+    if (tiles == 0) return p;
+    const int64_t wgs = tiles * Hkv;
+    // The chip: `cus` compute units, two workgroup slots each.  (The counts in the comments below
+    // are those of the 256-CU part the rules were measured on.)
+    const int64_t cus = device_cus(), slots = 2 * cus;
+    if (wgs <= cus * 3 / 4 && max_steps < 128) {
+        // few and short tiles: about four workgroups per CU, ranges of at least 32 steps
+        const int64_t rs = std::max<int64_t>(32, (total_steps * Hkv + 4 * cus - 1) / (4 * cus));
+        if (rs < max_steps) {
+            p.range_steps = (int32_t)rs;
+            p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
+        }
+    } else if (wgs <= 4 * cus) {
+        // Up to four workgroups per CU the grid runs as one or two rounds over the 512 workgroup
+        // slots (or leaves CUs empty), and a round that is not full costs almost as much as a
+        // full one.  Cutting every tile into r key ranges multiplies the workgroups and divides
+        // their length: pick the r whose rounds come out fullest.  The cost model is fitted to
+        // measurements (it reproduces them within a few percent), in steps of a workgroup that
+        // shares its CU: a workgroup with the CU to itself runs a step in 0.76 of that; while all
+        // workgroups are resident the longest tile decides, beyond that the average tile and a
+        // round count halfway between W/512 and its ceiling (tiles end at different times, so
+        // rounds blur); every workgroup pays about 8 steps of start-up and store; the partials
+        // cost a launch plus their bytes written and read back at 5 TB/s.
+        const double avg_steps = (double)total_steps / (double)tiles;
+        auto cost = [&](int r) -> double {
+            const double W = (double)wgs * r;
+            double c;
+            if (W <= cus) c = 0.76 * ((double)max_steps / r + 8);
+            else if (W <= slots) c = (0.76 + (W - cus) / cus * 0.24) * ((double)max_steps / r + 8);
+            else c = 0.5 * (W / slots + std::ceil(W / slots)) * (avg_steps / r + 8);
+            if (r > 1) {
+                const double part_bytes = W * kTileCols * 16 * (D + 4) * 4.0;
+                c += (10.0 + 2.0 * part_bytes / 5.0e6) / 0.87;     // microseconds -> steps
+            }
+            return c;
+        };
+        int best = 1;
+        double best_cost = cost(1);
+        for (int r = 2; r <= 16; ++r) {
+            if (max_steps / r < 32) break;
+            const double c = cost(r);
+            if (c < best_cost) { best = r; best_cost = c; }
+        }
+        if (best > 1 && best_cost <= 0.92 * cost(1)) {
+            p.range_steps = (max_steps + best - 1) / best;
+            p.max_ranges = (max_steps + p.range_steps - 1) / p.range_steps;
+        }
+    }
+    // Uncut tiles in an order that suits the dispatcher, which deals workgroup i to XCD i % 8,
+    // gives the first 256 a CU each and puts workgroup i + 256 beside workgroup i (observed with
+    // a probe that records where each workgroup runs).  While everything is resident (up to 512
+    // workgroups) the call lasts as long as the slowest CU: the longest tiles get the CUs of their
+    // own (positions W-256 .. 255) and the rest are paired long with short.  With more tiles than
+    // slots the longest go first and the short ones fill the end; the natural order is the
+    // opposite (a chunk's later tiles see more keys).  The order travels as a table in the kernel
+    // arguments; a batch with more tiles than the table holds is simply walked backwards.
+    const int32_t first_round = (int32_t)(cus / Hkv);            // slot positions of the first round (a CU each)
+    bool slots_fit = true;                                       // a table entry is 16 bits
+    for (int32_t k = 0; k < n_listed; ++k) slots_fit = slots_fit && tile_list[k].slot < 65536;
+    if (p.max_ranges == 1 && wgs > cus) {
+        const bool listed = tiles == n_listed && slots_fit;
+        if (listed && wgs <= slots && cus % Hkv == 0) {
+            std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
+            const int32_t n_pair = (int32_t)tiles - first_round, n_solo = first_round - n_pair;
+            for (int32_t k = 0; k < n_solo; ++k) p.order.slot[n_pair + k] = (uint16_t)tile_list[k].slot;
+            for (int32_t k = 0; k < n_pair; ++k) {
+                p.order.slot[k] = (uint16_t)tile_list[n_solo + k].slot;                                   // long
+                p.order.slot[first_round + k] = (uint16_t)tile_list[n_solo + 2 * n_pair - 1 - k].slot;    // short
+            }
+            p.n_ordered = (int32_t)tiles;
+        } else if (wgs > slots) {
+            if (listed) {
+                std::stable_sort(tile_list, tile_list + n_listed, [](const Tile& a, const Tile& c) { return a.steps > c.steps; });
+                for (int32_t k = 0; k < n_listed; ++k) p.order.slot[k] = (uint16_t)tile_list[k].slot;
+                p.n_ordered = (int32_t)tiles;
+            }
+            p.backwards = true;
+        }
+    }
+    if (p.max_ranges > 1) {
+        p.base_slot = (int32_t)prefill_slot_start(b->h_cu_q_lens[first], first, G);
+        p.num_slots = (int32_t)(prefill_slot_start(b->num_tokens, b->num_seqs, G) - p.base_slot);
+        p.bytes = (size_t)p.num_slots * Hkv * p.max_ranges * kTileCols * 16 * (D + 4) * sizeof(float);
     }
     return p;
 }

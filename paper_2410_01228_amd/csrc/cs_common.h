@@ -42,6 +42,22 @@ __host__ __device__ inline int32_t decode_chunk_keys(int32_t n_keys, int32_t n_s
     return (c + kPage - 1) & ~(kPage - 1);
 }
 
+// Tile arithmetic of the prefill path, shared by the host plan and the kernels.
+constexpr int kPrefillWaves = 4;
+constexpr int kPrefillThreads = kPrefillWaves * 64;
+constexpr int kNCT = 2;                       // column tiles (16 query rows) per wavefront
+constexpr int kKeysPerStep = 32;              // keys a workgroup walks per step: two pages of 16
+constexpr int kTileCols = kPrefillWaves * kNCT;   // column tiles per workgroup
+
+// Workgroup slots.  A sequence with q new tokens has ceil(q/16) * G column tiles, numbered
+// token-block major (ct = token_block * G + head), and needs ceil(that / kTileCols)
+// workgroups.  Slots are dealt without a prefix sum over tile counts: sequence s starts at
+//   start(s) = floor((cu_q_lens[s] + 16 s) * G / (16 * kTileCols)) + s,
+// which is strictly increasing and leaves every sequence at least as many slots as it needs.
+__host__ __device__ inline int64_t prefill_slot_start(int32_t cu_q, int32_t s, int32_t G) {
+    return ((int64_t)cu_q + 16ll * s) * G / (16 * kTileCols) + s;
+}
+
 // Small batches carry their work-item list inside the kernel arguments: the host already has
 // the lengths, so it lists the items itself, longest first, and no planning kernel and no
 // host-to-device copy is needed.  One word per item: sequence (bits 0-15), piece (16-23),

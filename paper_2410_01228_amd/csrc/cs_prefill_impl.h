@@ -34,10 +34,8 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kPrefillWaves = 4;
-constexpr int kPrefillThreads = kPrefillWaves * 64;
-constexpr int kNCT = 2;                       // column tiles per wavefront
-constexpr int kKeysPerStep = 32;              // two pages
+// (kPrefillWaves, kPrefillThreads, kNCT, kKeysPerStep, kTileCols and prefill_slot_start are in
+// cs_common.h: the host's launch plan uses them too)
 constexpr float kLazyLog2 = 6.0f;             // weights may reach 2^6 before the max is raised
 constexpr float kNoMax = -1.0e30f;            // "no score seen yet": finite, so that -inf minus it stays -inf
 constexpr int kRing = 4;                      // LDS slots for K and for V steps (copies kRing-1 steps ahead)
@@ -107,16 +105,6 @@ __device__ __forceinline__ float max8(const float (&x)[8]) {
     return max3(max3(x[0], x[1], x[2]), max3(x[3], x[4], x[5]), max3(x[6], x[7], x[7]));
 }
 
-constexpr int kTileCols = kPrefillWaves * kNCT;   // column tiles per workgroup
-
-// Workgroup slots.  A sequence with q new tokens has ceil(q/16) * G column tiles, numbered
-// token-block major (ct = token_block * G + head), and needs ceil(that / kTileCols)
-// workgroups.  Slots are dealt without a prefix sum over tile counts: sequence s starts at
-//   start(s) = floor((cu_q_lens[s] + 16 s) * G / (16 * kTileCols)) + s,
-// which is strictly increasing and leaves every sequence at least as many slots as it needs.
-__host__ __device__ inline int64_t prefill_slot_start(int32_t cu_q, int32_t s, int32_t G) {
-    return ((int64_t)cu_q + 16ll * s) * G / (16 * kTileCols) + s;
-}
 
 // LDS of one prefill workgroup: the ring of K and of V steps.
 template <int D>
