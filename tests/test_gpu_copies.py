@@ -47,6 +47,21 @@ def test_append_page_boundaries_and_idle_sequences():
     _run_append_case(b, 11)
 
 
+@pytest.mark.parametrize("Hkv,D,ps,S,qmax", [(4, 64, 16, 40, 1200), (8, 128, 8, 16, 1500), (8, 128, 16, 12, 2048)])
+def test_append_of_tens_of_thousands_of_chunk_tokens(Hkv, D, ps, S, qmax):
+    """Chunk appends of 18-35 thousand tokens (some nine thousand (page, kv head) workgroups):
+    ragged chunk lengths and contexts, so that first and last pages are partly filled; every
+    element of the pool is compared with the oracle's append."""
+    import random
+    rnd = random.Random(S * 1000 + D)
+    sh = synth.Shape(2 * Hkv, Hkv, D, page_size=ps)
+    ctx = [rnd.randint(0, 40) for _ in range(S)]
+    ql = [rnd.randint(qmax // 2, qmax) for _ in range(S)]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(12), spare=5)
+    assert b.T >= 17000
+    _run_append_case(b, 12)
+
+
 def test_append_empty_batch_is_a_noop():
     sh = synth.Shape(4, 2, 64)
     pool = cs.Pool.empty(1, 4, sh.Hkv, sh.D)
