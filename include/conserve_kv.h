@@ -386,11 +386,17 @@ int32_t cs_debug_decode_pages_ahead(const cs_batch* batch, int32_t num_kv_heads,
  * grid size).  Process-wide. */
 void cs_set_decode_pages_ahead(int32_t pages);
 
-/* Tuning knob for measurements and tests: 1 (default) lets a call that holds both prefill
- * chunks and decode tokens run them as one fused launch when its plan allows and the chunks are
- * not a sliver beside the decode work; 2 fuses whenever the plan allows; 0 always launches the prefill
- * kernel and the decode kernel one after the other.  Process-wide. */
+/* Tuning knob for measurements and tests.  A call that holds both prefill chunks and decode
+ * tokens can run as two kernels in a row, as one grid with the decode work behind the tiles, or
+ * as one grid with one decode workgroup per CU beside the tiles (paper Sec. 4.2: both kinds of
+ * work share an iteration).  1 (default): the host chooses from the batch's lengths; 0: always
+ * two kernels; 2: always behind; 3: always beside.  All give the same bits.  Process-wide. */
 void cs_set_mixed_fusion(int32_t mode);
+
+/* Host-only view of that choice, for tests: 0 two kernels (also when the batch has only one kind
+ * of work), 1 decode behind the tiles, 2 decode beside the tiles; CS_ERR_INVALID_ARG on bad
+ * arguments.  No device work. */
+int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
 
 const char* cs_status_string(int status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */

@@ -126,6 +126,7 @@ def lib():
         L.cs_debug_copy.restype, L.cs_debug_copy.argtypes = ctypes.c_int, [vp, vp, sz, vp]
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
+        L.cs_debug_mixed_arrangement.restype, L.cs_debug_mixed_arrangement.argtypes = i32, [BP, i32, i32, i32]
         L.cs_set_decode_pages_ahead.restype, L.cs_set_decode_pages_ahead.argtypes = None, [i32]
         L.cs_debug_prefill_order.restype = ctypes.c_int32
         L.cs_debug_prefill_order.argtypes = [BP, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32]
@@ -145,7 +146,7 @@ EXPORTS = [
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
     "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_run_layers_workspace_bytes", "cs_debug_set_cu_count", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
-    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_status_string", "cs_last_hip_error",
+    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_status_string", "cs_last_hip_error",
 ]
 
 
@@ -457,8 +458,17 @@ def cs_set_decode_pages_ahead(pages: int):
 
 
 def cs_set_mixed_fusion(mode):
-    """True / 1: fuse when it pays (default); 2: fuse whenever the plan allows; False / 0: never."""
+    """1: the host chooses how a mixed batch is launched (default); 0: two kernels in a row; 2: one
+    grid, decode work behind the tiles; 3: one grid, a decode workgroup per CU beside the tiles."""
     lib().cs_set_mixed_fusion(int(mode))
+
+
+def cs_debug_mixed_arrangement(batch: "Batch", Hq: int, Hkv: int, D: int) -> int:
+    """0 two kernels, 1 decode behind the tiles, 2 decode beside the tiles -- host only."""
+    rc = lib().cs_debug_mixed_arrangement(ctypes.byref(batch.c), Hq, Hkv, D)
+    if rc < 0:
+        raise CsError(rc, "cs_debug_mixed_arrangement")
+    return rc
 
 
 def cs_set_decode_split_tokens(tokens: int):

@@ -5,6 +5,7 @@
 #include <cmath>
 #include "cs_common.h"
 #include <atomic>
+#include <functional>
 #include <vector>
 #include <string.h>
 #include <stdio.h>
@@ -214,7 +215,10 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     p.range_steps = std::max(max_steps, 1);
     p.max_ranges = 1;
     if (tiles == 0) return p;
+    p.base_slot = (int32_t)prefill_slot_start(b->h_cu_q_lens[first], first, G);
+    p.num_slots = (int32_t)(prefill_slot_start(b->num_tokens, b->num_seqs, G) - p.base_slot);
     const int64_t wgs = tiles * Hkv;
+
     // The chip: `cus` compute units, two workgroup slots each.  (The counts in the comments below
     // are those of the 256-CU part the rules were measured on.)
     const int64_t cus = device_cus(), slots = 2 * cus;
@@ -293,11 +297,118 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
         }
     }
     if (p.max_ranges > 1) {
-        p.base_slot = (int32_t)prefill_slot_start(b->h_cu_q_lens[first], first, G);
-        p.num_slots = (int32_t)(prefill_slot_start(b->num_tokens, b->num_seqs, G) - p.base_slot);
         p.bytes = (size_t)p.num_slots * Hkv * p.max_ranges * kTileCols * 16 * (D + 4) * sizeof(float);
     }
     return p;
+}
+
+// How a batch with both kinds of work is launched (see cs_mixed.hip): as two kernels in a row, as
+// one grid with the decode pairs behind the tiles, or as one grid with a decode workgroup per CU
+// beside the tiles.  mode: cs_set_mixed_fusion's (0 never fuse, 1 choose, 2 always behind, 3
+// always beside).
+//
+// The choice between "behind" and "beside" comes from a small simulation of both grids over the
+// chip's 2 * CUs workgroup slots, in microseconds.  A tile workgroup of n steps lasts (n + 8) * c
+// (c = 0.88 us per 32-key step at head dim 128 for a workgroup that shares its CU); workgroups
+// take the earliest free slot in launch order.  Behind: the decode bytes flow at 6.5 TB/s times
+// min(1, free slots / (1.5 CUs)) into the slots the tiles have left for good.  Beside: one slot
+// per CU is the decode workgroup's until all bytes have passed at 6.5 TB/s, a tile next to it
+// runs 1.1 times longer.  Over 72 mixes of two model shapes, taking the faster of the two by this
+// model is on average 0.6% slower than taking the faster by measurement (always behind: 5.0%,
+// always beside: 3.0%); the merges of cut tiles and cut sequences cost the same either way.
+struct FusePlan {
+    int32_t arrangement;       // 0 two kernels, 1 decode behind the tiles, 2 decode beside the tiles
+    bool prio;                 // tiles alternate their issue priority (decode side small)
+    int32_t persistent_wgs;    // arrangement 2: decode workgroups (one per CU)
+};
+
+static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, const PrefillPlan& p, int32_t Hq, int32_t Hkv,
+                            int32_t D, int32_t mode) {
+    FusePlan f = {0, false, 0};
+    if (d.num_prefill == 0 || d.num_decode == 0 || !d.in_args || mode == 0) return f;
+    const int32_t G = Hq / Hkv;
+    double pairs = 0;
+    for (int32_t s = 0; s < b->num_seqs; ++s) {
+        const double ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+        if (ql > 1) pairs += ql * ((double)b->h_ctx_lens[s] + (ql + 1) / 2);
+    }
+    // ideal times: flops at 1 PFLOP/s, bytes at 6 TB/s
+    const double t_prefill = 4.0 * Hq * D * pairs / 1.0e15;
+    const double decode_bytes = (double)d.decode_keys * 2 * Hkv * D * 2;
+    const double t_decode = decode_bytes / 6.0e12;
+    // Behind the tiles, unless the prefill side is a sliver: with a small chunk beside a long
+    // decode (decode time over ten times the prefill time) two kernels in a row are as fast or a
+    // little faster.  Where the decode side is the smaller one (under 0.3 of the prefill time)
+    // the tiles alternate their issue priority as the prefill kernel's do; beside a decode load
+    // of equal weight that costs more than it gains.
+    f.arrangement = (mode == 2 || t_decode <= 10.0 * t_prefill) ? 1 : 0;
+    f.prio = t_decode < 0.3 * t_prefill;
+    const int32_t cus = device_cus();
+    if (mode == 2 || (mode == 1 && D != 128)) return f;   // (head dim 64 fits three workgroups per CU: not measured beside)
+    bool beside = mode == 3;
+    if (mode == 1) {
+        // steps of every tile slot, in the fused grid's launch order
+        std::vector<int32_t> slot_steps((size_t)p.num_slots, 0);
+        for (int32_t s = 0; s < b->num_seqs; ++s) {
+            const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+            if (ql <= 1) continue;
+            const int32_t n_ct = ((ql + 15) >> 4) * G;
+            const int64_t slot0 = prefill_slot_start(b->h_cu_q_lens[s], s, G) - p.base_slot;
+            for (int32_t ct0 = 0; ct0 < n_ct; ct0 += kTileCols) {
+                const int32_t tb_max = (std::min(ct0 + kTileCols, n_ct) - 1) / G;
+                const int32_t n_keys = b->h_ctx_lens[s] + std::min(ql, (tb_max + 1) * 16);
+                slot_steps[(size_t)(slot0 + ct0 / kTileCols)] = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
+            }
+        }
+        const double c_step = 0.88, t_dec = decode_bytes / 6.5e6;           // microseconds
+        const size_t n_slots = 2 * (size_t)cus;
+        // list scheduling of the tile workgroups over slots that become available at avail[]
+        auto schedule = [&](std::vector<double>& avail, double stretch) {
+            std::make_heap(avail.begin(), avail.end(), std::greater<double>());
+            double end = 0;
+            for (int32_t r = 0; r < p.max_ranges; ++r)
+                for (int32_t pos = 0; pos < p.num_slots; ++pos) {
+                    const int32_t steps = slot_steps[(size_t)(p.backwards ? p.num_slots - 1 - pos : pos)];
+                    const int32_t n = std::min(steps, (r + 1) * p.range_steps) - r * p.range_steps;
+                    if (n <= 0) continue;
+                    for (int32_t g = 0; g < Hkv; ++g) {
+                        std::pop_heap(avail.begin(), avail.end(), std::greater<double>());
+                        const double t = avail.back() + (n + 8) * c_step * stretch;
+                        avail.back() = t;
+                        end = std::max(end, t);
+                        std::push_heap(avail.begin(), avail.end(), std::greater<double>());
+                    }
+                }
+            return end;
+        };
+        const int64_t tile_wgs = (int64_t)p.num_slots * Hkv * p.max_ranges;
+        if (tile_wgs > 65536) {
+            beside = t_decode >= 0.05 * t_prefill;     // many rounds of tiles: beside always overlaps
+        } else {
+            std::vector<double> avail(n_slots, 0.0);
+            schedule(avail, 1.0);
+            std::sort(avail.begin(), avail.end());       // when each slot is free for good
+            double t = 0, left = t_dec, t_behind = 0;
+            const double sat = 1.5 * cus;
+            for (size_t i = 0; ; ++i) {
+                const double rate = std::min(1.0, (double)i / sat);          // i slots are free
+                const double next = i < n_slots ? avail[i] : 1.0e300;
+                if (rate > 0 && t + left / rate <= next) { t_behind = t + left / rate; break; }
+                left -= rate * (next - t);
+                t = next;
+            }
+            std::vector<double> avail2(n_slots, 0.0);
+            for (size_t i = 0; i < (size_t)cus; ++i) avail2[i] = t_dec;
+            const double t_beside = std::max(schedule(avail2, 1.1), t_dec);
+            beside = t_beside < t_behind;
+        }
+    }
+    if (beside) {
+        f.arrangement = 2;
+        f.prio = false;
+        f.persistent_wgs = cus;
+    }
+    return f;
 }
 
 static size_t align16(size_t x) { return (x + 15) & ~(size_t)15; }
@@ -360,11 +471,12 @@ static int attention_shape_ok(int32_t Hq, int32_t Hkv, int32_t D) {
 struct Plans {
     DecodePlan d;
     PrefillPlan p;
+    FusePlan f;
     size_t decode_bytes, need;
 };
 struct PlanMemo {
     bool valid = false;
-    int32_t S = 0, T = 0, Hq = 0, Hkv = 0, D = 0, split = 0, ahead = 0, cus = 0;
+    int32_t S = 0, T = 0, Hq = 0, Hkv = 0, D = 0, split = 0, ahead = 0, cus = 0, fuse = 0;
     std::vector<int32_t> ctx, cu;
     Plans plans;
 };
@@ -372,19 +484,21 @@ static const Plans& plans_for(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_
     static thread_local PlanMemo memo[2];
     static thread_local int next = 0;
     const int32_t S = b->num_seqs, split = g_forced_split.load(), ahead = g_forced_ahead.load(), cus = device_cus();
+    const int32_t fuse = g_fuse_mixed.load();
     for (PlanMemo& m : memo)
-        if (m.valid && m.S == S && m.T == b->num_tokens && m.Hq == Hq && m.Hkv == Hkv && m.D == D && m.split == split &&
+        if (m.valid && m.fuse == fuse && m.S == S && m.T == b->num_tokens && m.Hq == Hq && m.Hkv == Hkv && m.D == D && m.split == split &&
             m.ahead == ahead && m.cus == cus && memcmp(m.ctx.data(), b->h_ctx_lens, sizeof(int32_t) * S) == 0 &&
             memcmp(m.cu.data(), b->h_cu_q_lens, sizeof(int32_t) * (S + 1)) == 0)
             return m.plans;
     PlanMemo& m = memo[next];
     next ^= 1;
     m.valid = false;
-    m.S = S; m.T = b->num_tokens; m.Hq = Hq; m.Hkv = Hkv; m.D = D; m.split = split; m.ahead = ahead; m.cus = cus;
+    m.S = S; m.T = b->num_tokens; m.Hq = Hq; m.Hkv = Hkv; m.D = D; m.split = split; m.ahead = ahead; m.cus = cus; m.fuse = fuse;
     m.ctx.assign(b->h_ctx_lens, b->h_ctx_lens + S);
     m.cu.assign(b->h_cu_q_lens, b->h_cu_q_lens + S + 1);
     m.plans.d = plan_decode(b, Hkv, D);
     m.plans.p = m.plans.d.num_prefill ? plan_prefill(b, Hq, Hkv, D) : PrefillPlan{};
+    m.plans.f = plan_fusion(b, m.plans.d, m.plans.p, Hq, Hkv, D, fuse);
     m.plans.decode_bytes = decode_workspace(m.plans.d, S, Hq, D).total;
     m.plans.need = m.plans.decode_bytes + m.plans.p.bytes;
     m.valid = true;
@@ -437,30 +551,11 @@ static int attention_mixed(const cs_kv_pool* pool, int32_t layer, const cs_batch
     if (need > 0 && (!workspace || ((uintptr_t)workspace & 15))) return CS_ERR_INVALID_ARG;
     if (workspace_bytes < need) return CS_ERR_WORKSPACE_TOO_SMALL;
     hipStream_t st = (hipStream_t)stream;
-    // One grid for both kinds of work, unless the prefill side is a sliver: with a small chunk
-    // beside a long decode (ideal decode time, bytes at 6 TB/s, over ten times the ideal prefill
-    // time, flops at 1 PFLOP/s) two kernels in a row are as fast or a little faster.  Where the
-    // decode side is the smaller one (under 0.3 of the prefill time) the tiles of the fused grid
-    // alternate their issue priority as the prefill kernel's do; beside a decode load of equal
-    // weight that costs more than it gains.  Measured over 110 mixes of three model shapes: the
-    // fused grid is 1-18% faster than two kernels wherever this rule takes it.
-    bool fuse = plan.num_prefill > 0 && plan.num_decode > 0 && plan.in_args && g_fuse_mixed.load() != 0;
-    bool prio = false;
-    if (fuse) {
-        double pairs = 0;
-        for (int32_t s = 0; s < batch->num_seqs; ++s) {
-            const double ql = batch->h_cu_q_lens[s + 1] - batch->h_cu_q_lens[s];
-            if (ql > 1) pairs += ql * ((double)batch->h_ctx_lens[s] + (ql + 1) / 2);
-        }
-        const double t_prefill = 4.0 * Hq * pool->head_dim * pairs / 1.0e15;
-        const double t_decode = (double)plan.decode_keys * 2 * pool->num_kv_heads * pool->head_dim * 2 / 6.0e12;
-        prio = t_decode < 0.3 * t_prefill;
-        if (g_fuse_mixed.load() == 1) fuse = t_decode <= 10.0 * t_prefill;
-    }
-    if (fuse) {
+    if (plans.f.arrangement != 0) {
         // both kinds of work in one grid, then the merges of whatever was cut
         void* prefill_ws = (char*)workspace + decode_bytes;
-        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, prefill_ws, st, f16, prio);
+        rc = launch_mixed(*pool, layer, *batch, plan, pplan, q, out, Hq, softmax_scale, workspace, prefill_ws, st, f16,
+                          plans.f.prio, plans.f.arrangement == 2 ? plans.f.persistent_wgs : 0);
         if (rc) return rc;
         rc = launch_prefill_merge(*pool, *batch, pplan, out, Hq, prefill_ws, st, f16);
         if (rc) return rc;
@@ -710,8 +805,14 @@ void cs_set_decode_pages_ahead(int32_t pages) {
     g_forced_ahead.store(pages == 1 || pages == 2 ? pages : 0);
 }
 
+int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return CS_ERR_INVALID_ARG;
+    if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return CS_ERR_INVALID_ARG;
+    return plans_for(batch, Hq, Hkv, D).f.arrangement;
+}
+
 void cs_set_mixed_fusion(int32_t mode) {
-    g_fuse_mixed.store(mode == 0 || mode == 2 ? mode : 1);
+    g_fuse_mixed.store(mode == 0 || mode == 2 || mode == 3 ? mode : 1);
 }
 
 void cs_set_decode_split_tokens(int32_t tokens) {

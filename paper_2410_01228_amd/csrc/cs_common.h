@@ -113,8 +113,8 @@ struct PrefillPlan {
     bool    backwards;         // where no table is used: grid position p takes slot (slots - 1 - p)
     int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
     int32_t max_ranges;        // grid depth: ranges of the longest tile
-    int32_t base_slot;         // first workgroup slot that can belong to a prefill sequence
-    int32_t num_slots;         // slots from base_slot on (partials are indexed by slot)
+    int32_t base_slot;         // first workgroup slot that can belong to a prefill sequence (set whenever there is a chunk)
+    int32_t num_slots;         // slots from base_slot on: the grid's extent; partials are indexed by slot - base_slot
     size_t  bytes;             // workspace for the partials (0 when nothing is cut)
 };
 PrefillPlan plan_prefill(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
@@ -123,15 +123,17 @@ int launch_prefill(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, con
 // The merge of the key-range partials alone (what launch_prefill ends with when tiles are cut).
 int launch_prefill_merge(const cs_kv_pool& pool, const cs_batch& b, const PrefillPlan& plan, void* out, int32_t Hq,
                          void* workspace, hipStream_t st, bool f16);
-// One launch for a batch that holds both chunks and decode tokens: the prefill workgroups
-// first, the decode items (longest first) behind them, so that decode work fills the slots the
-// uneven prefill tiles leave empty instead of waiting for the last of them.  Needs the item
-// list in the kernel arguments (dplan.in_args).  Tiles cut into key ranges bring one workgroup
-// per range; the caller merges their partials (launch_prefill_merge) and the cut decode
-// sequences (launch_decode with merge_only) afterwards.
+// One launch for a batch that holds both chunks and decode tokens.  persistent_wgs == 0: the
+// prefill workgroups first, one workgroup per decode (item, kv head) pair behind them, so that
+// decode work fills the slots the uneven prefill tiles leave empty instead of waiting for the
+// last of them.  persistent_wgs > 0: that many decode workgroups first (the host passes the CU
+// count: one per CU), each walking several pairs, the tiles beside them.  Needs the item list
+// in the kernel arguments (dplan.in_args).  Tiles cut into key ranges bring one workgroup per
+// range; the caller merges their partials (launch_prefill_merge) and the cut decode sequences
+// (launch_decode with merge_only) afterwards.
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
                  void* decode_workspace_base, void* prefill_workspace, hipStream_t st, bool f16,
-                 bool phase_priority);
+                 bool phase_priority, int32_t persistent_wgs);
 
 }  // namespace cs

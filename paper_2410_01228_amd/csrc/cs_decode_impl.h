@@ -61,6 +61,21 @@ __device__ __forceinline__ bool step_ok(const StepIds<PS>& ids, int32_t num_page
     else return ids.a >= 0 && ids.a < num_pages && ids.b >= 0 && ids.b < num_pages;
 }
 
+// Ids that can always be read: a step outside the range, or one with a bad id, reads page 0 of
+// the pool instead (its result is never used).
+template <int PS>
+__device__ __forceinline__ StepIds<PS> loadable(const StepIds<PS>& ids, int32_t num_pages) {
+    StepIds<PS> r = ids;
+    if constexpr (PS == 16) {
+        r.a = (ids.a >= 0 && ids.a < num_pages) ? ids.a : 0;
+    } else {
+        const bool good = ids.a >= 0 && ids.a < num_pages && ids.b >= 0 && ids.b < num_pages;
+        r.a = good ? ids.a : 0;
+        r.b = good ? ids.b : 0;
+    }
+    return r;
+}
+
 template <int D>
 __device__ __forceinline__ void load_page(PageRegs<D>& r, const uint16_t* __restrict__ layer_base,
                                           int64_t page_stride, StepIds<16> ids, int32_t g, int32_t Hkv, int lane)
@@ -213,7 +228,16 @@ struct DecodeLds {
 // decode).  kAhead: pages a wavefront keeps in flight beyond the one it multiplies (1 or 2; a
 // page is 32 registers, so 2 costs the third workgroup per CU: it pays for long items on a
 // full grid, not for short ones on a small grid).
-template <int D, class Src, class E, int kAhead, int PS>
+// kCountedLoads: how a step without a page (past the end of the range, or a bad id) is handled.
+// false: its loads are skipped.  The compiler cannot count loads behind a branch, so it waits for
+// everything in flight before each multiply: every page's loads are issued early, but a
+// wavefront never computes while its own loads fly.  On a grid that fills the chip (several
+// workgroups per CU) that is the faster form (2-3% on the decode workloads): the other
+// workgroups cover the wait, and no load is wasted.  true: such a step loads page 0 instead, all
+// loads are straight-line code, and the compiler waits only for the page about to be multiplied,
+// so ONE workgroup per CU streams at 26-48 GB/s instead of 17: what a decode workgroup that
+// shares its CU with a prefill tile needs.
+template <int D, class Src, class E, int kAhead, int PS, bool kCountedLoads = false>
 __device__ __forceinline__ void decode_item(
     DecodeLds<D>& lds,
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -261,6 +285,13 @@ __device__ __forceinline__ void decode_item(
     for (int dt = 0; dt < D / 16; ++dt) st.o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     static_assert(kAhead == 1 || kAhead == 2, "one or two pages ahead");
+    auto fetch = [&](PageRegs<D>& r, const StepIds<PS>& id) {
+        if constexpr (kCountedLoads) {
+            load_page<D>(r, layer_base, page_stride, loadable<PS>(id, num_pages), g, Hkv, lane);
+        } else {
+            if (step_ok<PS>(id, num_pages)) load_page<D>(r, layer_base, page_stride, id, g, Hkv, lane);
+        }
+    };
     if constexpr (kAhead == 1) {
         // wave w streams pages page_begin + w, + w + 4, ...; the next page's loads are in
         // flight while the current page is multiplied
@@ -270,12 +301,11 @@ __device__ __forceinline__ void decode_item(
         auto ok = [&](const StepIds<PS>& id) { return step_ok<PS>(id, num_pages); };
         StepIds<PS> id_cur = id_at(pg);
         StepIds<PS> id_nxt = id_at(pg + kDecodeWaves);
-        if (ok(id_cur))
-            load_page<D>(cur, layer_base, page_stride, id_cur, g, Hkv, lane);
+        fetch(cur, id_cur);
         while (pg < page_end) {
             const int32_t pg_n = pg + kDecodeWaves;
             const StepIds<PS> id_n2 = id_at(pg_n + kDecodeWaves);
-            if (ok(id_nxt)) load_page<D>(nxt, layer_base, page_stride, id_nxt, g, Hkv, lane);
+            fetch(nxt, id_nxt);
             if (ok(id_cur))
                 process_page<D, E>(st, cur, qb, scale_log2e, pg << 4, n_keys, lane);
             cur = nxt;
@@ -291,11 +321,11 @@ __device__ __forceinline__ void decode_item(
         auto id_at = [&](int32_t p) { return step_ids<PS>(table, p, page_end, n_entries); };
         auto ok = [&](const StepIds<PS>& id) { return step_ok<PS>(id, num_pages); };
         StepIds<PS> id0 = id_at(pg), id1 = id_at(pg + kDecodeWaves), id2 = id_at(pg + 2 * kDecodeWaves);
-        if (ok(id0)) load_page<D>(b0, layer_base, page_stride, id0, g, Hkv, lane);
-        if (ok(id1)) load_page<D>(b1, layer_base, page_stride, id1, g, Hkv, lane);
+        fetch(b0, id0);
+        fetch(b1, id1);
         auto stage = [&](PageRegs<D>& use, PageRegs<D>& fill) {
             const StepIds<PS> id3 = id_at(pg + 3 * kDecodeWaves);
-            if (ok(id2)) load_page<D>(fill, layer_base, page_stride, id2, g, Hkv, lane);
+            fetch(fill, id2);
             if (ok(id0)) process_page<D, E>(st, use, qb, scale_log2e, pg << 4, n_keys, lane);
             id0 = id1; id1 = id2; id2 = id3;
             pg += kDecodeWaves;

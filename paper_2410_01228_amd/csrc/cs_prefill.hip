@@ -4,7 +4,8 @@
 
 namespace cs {
 
-// grid.x = slots * Hkv, kv head fastest; grid.y = key ranges
+// grid.x = slots * Hkv, kv head fastest (the slots from base_slot on: no sequence before it has a
+// chunk); grid.y = key ranges
 template <int D, class E, int PS>
 __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -18,13 +19,16 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     __shared__ PrefillLds<D> lds;
     const int32_t pos = blockIdx.x / Hkv;
     const int32_t g = blockIdx.x - pos * Hkv;
-    const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos] : backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos;
+    const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos]
+                                    : base_slot + (backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos);
     prefill_tile<D, E, true, PS, false>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
                        q, out, scale_log2e, range_steps, base_slot, part, g, b, blockIdx.y, gridDim.y);
 }
 
-// Merge of the key-range partials of the tiles that were cut: grid = Hkv * slots, 256
-// lanes, two lanes per query row (half of the features each).
+// Merge of the key-range partials of the tiles that were cut: grid.x = Hkv * slots, grid.y =
+// kMergeParts row groups of a tile; one lane per (query row, 4 features), so a wavefront reads
+// whole 512-byte runs of a partial's rows.
+constexpr int kMergeParts = 4;
 template <int D, class E>
 __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     int32_t Hkv, int32_t G, int32_t S, const int32_t* __restrict__ ctx_lens,
@@ -32,6 +36,8 @@ __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     int32_t range_steps, int32_t max_ranges, int32_t base_slot, const float* __restrict__ part)
 {
     constexpr int kPartRow = D + 4;
+    constexpr int kQuads = D / 4;                                  // lanes per query row
+    constexpr int kRows = kTileCols * 16 / kMergeParts;            // rows of this workgroup
     const int32_t g = blockIdx.x % Hkv, b = blockIdx.x / Hkv + base_slot;
     int32_t lo = 0, hi = S;
     while (hi - lo > 1) {
@@ -50,37 +56,31 @@ __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
     const int32_t n_ranges = (n_steps + range_steps - 1) / range_steps;
     if (n_ranges <= 1) return;                               // written directly by the tile kernel
-    const int32_t row_id = threadIdx.x >> 1, half = threadIdx.x & 1;
-    const int32_t ct = ct0 + (row_id >> 4);
-    const int32_t tb = ct / G, hh = ct - tb * G;
-    const int32_t tl = tb * 16 + (row_id & 15);
-    if (ct >= n_ct || tl >= q_len) return;
-    const float* base = part + (((int64_t)(b - base_slot) * Hkv + g) * max_ranges) * (kTileCols * 16 * kPartRow)
-                      + row_id * kPartRow;
+    const float* tile = part + (((int64_t)(b - base_slot) * Hkv + g) * max_ranges) * (kTileCols * 16 * kPartRow);
     const int64_t rstride = (int64_t)kTileCols * 16 * kPartRow;
-    float M = kNoMax;
-    for (int32_t r = 0; r < n_ranges; ++r) M = fmaxf(M, base[r * rstride + D]);
-    float L = 0.f;
-    float acc[D / 2];
-#pragma unroll
-    for (int d = 0; d < D / 2; ++d) acc[d] = 0.f;
-    for (int32_t r = 0; r < n_ranges; ++r) {
-        const float* p = base + r * rstride;
-        const float f = exp2f(p[D] - M);                     // 0 for a range the row sees nothing of
-        L += p[D + 1] * f;
-#pragma unroll
-        for (int d = 0; d < D / 2; d += 4) {
-            const f32x4 v = *(const f32x4*)(p + half * (D / 2) + d);
-            acc[d] += v[0] * f; acc[d + 1] += v[1] * f; acc[d + 2] += v[2] * f; acc[d + 3] += v[3] * f;
-        }
-    }
-    const float inv = 1.f / L;
     const int32_t Hq = Hkv * G;
-    uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + half * (D / 2);
-#pragma unroll
-    for (int d = 0; d < D / 2; d += 4) {
-        u32x2 w = { E::pack(acc[d] * inv, acc[d + 1] * inv), E::pack(acc[d + 2] * inv, acc[d + 3] * inv) };
-        *(u32x2*)(dst + d) = w;
+    for (int32_t idx = threadIdx.x; idx < kRows * kQuads; idx += kPrefillThreads) {
+        const int32_t row_id = blockIdx.y * kRows + idx / kQuads, quad = idx % kQuads;
+        const int32_t ct = ct0 + (row_id >> 4);
+        const int32_t tb = ct / G, hh = ct - tb * G;
+        const int32_t tl = tb * 16 + (row_id & 15);
+        if (ct >= n_ct || tl >= q_len) continue;
+        const float* base = tile + row_id * kPartRow;
+        float M = kNoMax;
+        for (int32_t r = 0; r < n_ranges; ++r) M = fmaxf(M, base[r * rstride + D]);
+        float L = 0.f;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        for (int32_t r = 0; r < n_ranges; ++r) {
+            const float* p = base + r * rstride;
+            const float f = exp2f(p[D] - M);                 // 0 for a range the row sees nothing of
+            L += p[D + 1] * f;
+            const f32x4 v = *(const f32x4*)(p + quad * 4);
+            acc += v * f;
+        }
+        const float inv = 1.f / L;
+        uint16_t* dst = out + ((int64_t)(t_seq + tl) * Hq + g * G + hh) * D + quad * 4;
+        u32x2 w = { E::pack(acc[0] * inv, acc[1] * inv), E::pack(acc[2] * inv, acc[3] * inv) };
+        *(u32x2*)dst = w;
     }
 }
 
@@ -93,7 +93,7 @@ static void launch_merge_as(const cs_kv_pool& pool, const cs_batch& b, const Pre
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const float* part = (const float*)workspace;
-    dim3 mgrid((uint32_t)Hkv * (uint32_t)plan.num_slots);
+    dim3 mgrid((uint32_t)Hkv * (uint32_t)plan.num_slots, kMergeParts);
     if (D == 128)
         hipLaunchKernelGGL((prefill_merge_kernel<128, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
                            b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
@@ -111,9 +111,8 @@ static int launch_prefill_as(const cs_kv_pool& pool, int32_t layer, const cs_bat
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     const float scale_log2e = scale * 1.4426950408889634f;
-    const int64_t slots64 = prefill_slot_start(b.num_tokens, b.num_seqs, G);
-    if (slots64 * Hkv > 2147483647ll || plan.max_ranges > 65535) return CS_ERR_UNSUPPORTED;
-    const uint32_t slots = plan.n_ordered > 0 ? (uint32_t)plan.n_ordered : (uint32_t)slots64;
+    if ((int64_t)plan.num_slots * Hkv > 2147483647ll || plan.max_ranges > 65535) return CS_ERR_UNSUPPORTED;
+    const uint32_t slots = plan.n_ordered > 0 ? (uint32_t)plan.n_ordered : (uint32_t)plan.num_slots;
     dim3 grid((uint32_t)Hkv * slots, (uint32_t)plan.max_ranges);
     float* part = (float*)workspace;
 #define CS_LAUNCH_PREFILL(DD, PS)                                                                                   \

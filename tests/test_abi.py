@@ -413,3 +413,39 @@ def test_workspace_query_is_remembered_but_never_stale():
     keep[0][1] = 40000
     assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 4, 2, 64) == a1
     assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 8, 2, 64) > a1     # other shape, other plan
+
+
+def test_mixed_batches_choose_where_the_decode_work_runs():
+    """A batch with both kinds of work runs as one grid with the decode work behind the tiles or
+    with a decode workgroup per CU beside them, or as two kernels (Sec. 4.2: online decode tokens
+    and offline chunks share an iteration).  The host's choice follows the two sides' weights: a
+    decode side as heavy as the chunks goes beside them, a few short decodes stay behind them; one
+    kind of work alone is never fused; the knob forces each arrangement."""
+    lib = cs.lib()
+    import random
+    rnd = random.Random(5)
+
+    def arrangement(ctx, ql, Hq, Hkv):
+        b, keep = _batch(ctx, ql, max_blocks=1 << 16)
+        return lib.cs_debug_mixed_arrangement(ctypes.byref(b), Hq, Hkv, 128)
+
+    long_decodes = [rnd.randint(2048, 32768) for _ in range(128)]
+    heavy = (long_decodes + [30720], [1] * 128 + [1024])             # 5 GB of K/V beside a 1024-token chunk on 30K keys
+    light = ([rnd.randint(512, 2048) for _ in range(8)] + [5000] * 4, [1] * 8 + [512] * 4)
+    try:
+        lib.cs_debug_set_cu_count(256)
+        assert arrangement(*heavy, 64, 8) == 2
+        assert arrangement(*light, 64, 8) == 1
+        assert arrangement(long_decodes, [1] * 128, 64, 8) == 0
+        assert arrangement([30720], [1024], 64, 8) == 0
+        for mode, want in ((0, 0), (2, 1), (3, 2)):
+            lib.cs_set_mixed_fusion(mode)
+            assert arrangement(*heavy, 64, 8) == want and arrangement(*light, 64, 8) == want
+        lib.cs_set_mixed_fusion(1)
+        # the choice is part of the remembered plan and follows the knob and the lengths
+        assert arrangement(*heavy, 64, 8) == 2
+    finally:
+        lib.cs_set_mixed_fusion(1)
+        lib.cs_debug_set_cu_count(0)
+    b, keep = _batch([5], [1])
+    assert lib.cs_debug_mixed_arrangement(ctypes.byref(b), 6, 4, 128) == cs.CS_ERR_INVALID_ARG

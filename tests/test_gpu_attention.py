@@ -289,8 +289,10 @@ def test_random_mixed_batches(seed):
     split = rnd.choice([0, 0, 64, 256])
     gain = rnd.choice([1.0, 1.0, 4.0])
     dtype = rnd.choice([torch.bfloat16, torch.bfloat16, torch.float16])
-    fuse = rnd.choice([2, 1, 0])                           # one fused grid always / when it pays / two kernels in a row
+    fuse = rnd.choice([2, 1, 0])                           # decode behind the tiles always / the host's choice / two kernels in a row
     ahead = rnd.choice([0, 1, 2])                           # decode prefetch depth: automatic, one, two pages
+    if rnd.choice([0, 1, 2]) == 0:
+        fuse = 3                                            # a decode workgroup per CU beside the tiles
     out, st, _, _ = run_step(b, 2000 + seed, q_gain=gain, split=split, dtype=dtype, fuse=fuse, ahead=ahead)
     active = [s for s in range(S) if ql[s] > 0]
     assert_attention_close(out, st.oracle_attention(active),
@@ -300,16 +302,19 @@ def test_random_mixed_batches(seed):
 @pytest.mark.parametrize("Hq,Hkv,D,split,dtype", [(8, 2, 128, 0, torch.bfloat16), (28, 4, 128, 64, torch.bfloat16),
                                                    (16, 1, 64, 32, torch.bfloat16), (8, 2, 128, 64, torch.float16)])
 def test_fused_and_separate_launches_agree(Hq, Hkv, D, split, dtype):
-    """A batch with decode tokens and chunks runs as one fused grid; with the fusion switched off
-    the same work items run as two kernels in a row.  Same arithmetic in the same order: the
-    outputs are bit-identical, and both meet the oracle."""
+    """A batch with decode tokens and chunks runs as one fused grid, the decode work behind the
+    tiles or beside them; with the fusion switched off the same work items run as two kernels in a
+    row.  Same arithmetic in the same order: the outputs are bit-identical, and all meet the
+    oracle."""
     sh = synth.Shape(Hq, Hkv, D)
     ctx = [700, 33, 0, 1500, 260, 15, 2047, 90, 5, 311]
     ql = [1, 100, 17, 1, 1, 48, 1, 0, 1, 2]
     b = synth.make_batch(sh, ctx, ql, synth.generator(77), spare=3)
     o1, st, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=2)
     o2, _, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=0)
+    o3, _, _, _ = run_step(b, 77, split=split, dtype=dtype, fuse=3)
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    assert torch.equal(o3.view(torch.int16), o2.view(torch.int16))
     active = [s for s in range(len(ql)) if ql[s] > 0]
     check = assert_attention_close if dtype == torch.bfloat16 else assert_close_f16
     check(o1, st.oracle_attention(active), "fused %d/%d/%d split %d" % (Hq, Hkv, D, split))
@@ -329,6 +334,28 @@ def test_fused_grid_with_a_sliver_of_decode_work(Hq, Hkv, D, dtype):
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
     check = assert_attention_close if dtype == torch.bfloat16 else assert_close_f16
     check(o1, st.oracle_attention(), "prefill-heavy fused %d/%d/%d" % (Hq, Hkv, D))
+
+
+@pytest.mark.parametrize("cus,split", [(2, 64), (5, 0), (8, 128), (256, 32)])
+def test_decode_workgroups_that_walk_many_pairs(cus, split):
+    """Decode beside the tiles: as many decode workgroups as the chip has CUs, each walking the
+    (work item, kv head) pairs j, 2W-1-j, 2W+j, ... one after the other through the same merge
+    buffers.  With a chip of 2, 5 or 8 CUs every workgroup walks many rounds and the last round
+    is ragged; with 256 there are fewer pairs than workgroups.  Bit-identical to two kernels in a
+    row, and both meet the oracle."""
+    sh = synth.Shape(12, 4, 128)
+    ctx = [700, 33, 260, 1500, 15, 0, 2047, 90, 5, 311, 1023, 64, 48]
+    ql = [1, 100, 1, 1, 1, 17, 1, 1, 1, 1, 1, 1, 40]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(79), spare=3)
+    cs.cs_debug_set_cu_count(cus)
+    try:
+        o1, st, _, bb = run_step(b, 79, split=split, fuse=3)
+        assert cs.cs_debug_mixed_arrangement(bb, sh.Hq, sh.Hkv, sh.D) in (0, 1, 2)
+        o2, _, _, _ = run_step(b, 79, split=split, fuse=0)
+    finally:
+        cs.cs_debug_set_cu_count(0)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    assert_attention_close(o1, st.oracle_attention(), "decode beside the tiles, %d CUs, split %d" % (cus, split))
 
 
 def test_prefill_many_short_chunks():

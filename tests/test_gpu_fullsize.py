@@ -377,6 +377,8 @@ def test_random_batches_at_model_shapes(seed):
     rnd.shuffle(order)
     ctx, ql = [ctx[i] for i in order], [ql[i] for i in order]
     mode, ahead = rnd.choice([1, 1, 2, 0]), rnd.choice([0, 0, 1, 2])
+    if rnd.choice([0, 1, 2]) == 0:
+        mode = 3
     cs.cs_set_mixed_fusion(mode)
     cs.cs_set_decode_pages_ahead(ahead)
     try:

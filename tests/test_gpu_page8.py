@@ -174,7 +174,7 @@ def test_prefill_first_row_is_v0_exactly():
         assert torch.equal(out[0, h].cpu(), st.v_new[0, h // sh.G])
 
 
-@pytest.mark.parametrize("fuse", [2, 0])
+@pytest.mark.parametrize("fuse", [2, 3, 0])
 def test_mixed_batch_fused_and_separate(fuse):
     # chunks, decode tokens and idle sequences in any order; a context long enough that the
     # prefill kernel refills its window of page addresses (every 512 keys) several times
@@ -222,6 +222,8 @@ def test_random_mixed_batches(seed):
     dtype = rnd.choice([torch.bfloat16, torch.bfloat16, torch.float16])
     fuse = rnd.choice([2, 1, 0])
     ahead = rnd.choice([0, 1, 2])
+    if rnd.choice([0, 1, 2]) == 0:
+        fuse = 3
     out, st, _, _ = run_step(b, 6000 + seed, split=split, dtype=dtype, fuse=fuse, ahead=ahead)
     active = [s for s in range(S) if ql[s] > 0]
     assert_attention_close(out, st.oracle_attention(active),
