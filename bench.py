@@ -173,7 +173,11 @@ def build(name, f16=False, page_size=16):
                           "mfma", pre_flops))
     info = {"T": T, "S": b.S, "dec_bytes": dec_bytes, "pre_flops": pre_flops, "pre_bytes": pre_bytes,
             "append_bytes": append_bytes, "pool_gb": pool.tensor.numel() * 2 / 1e9, "name": b.name,
-            "keep": keep, "layer": layer, "L": sh.L}
+            "keep": keep, "layer": layer, "L": sh.L,
+            # how the host launches this batch's attention call (only a batch with both kinds of work is fused)
+            "arrangement": ("two kernels (one kind of work, or fusion off)", "one grid, decode work behind the tiles",
+                            "one grid, a decode workgroup per CU beside the tiles")[
+                                cs.cs_debug_mixed_arrangement(bb, sh.Hq, sh.Hkv, sh.D)]}
     return b, legs, detail, info
 
 
@@ -616,6 +620,7 @@ def measure(name, steps, warmup, args, sub_batches=True):
     b, legs, detail, info = build(name, f16=args.dtype == "f16", page_size=args.page_size)
     log("workload %s: S=%d T=%d pool %.2f GB, decode bytes %.3f GB, prefill %.3f TFLOP"
         % (info["name"], info["S"], info["T"], info["pool_gb"], info["dec_bytes"] / 1e9, info["pre_flops"] / 1e12))
+    log("  attention call: " + info["arrangement"])
     sec_per_step = time_legs(legs, steps, warmup)
     if sub_batches and detail:
         time_legs(detail, steps, warmup)
@@ -655,9 +660,11 @@ def main():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f16"],
                     help="element type of the pool and the queries (f16: the fp16 attention entry point)")
     ap.add_argument("--split-tokens", type=int, default=0, help="force the decode split (0 = automatic)")
-    ap.add_argument("--separate-launches", action="store_true",
-                    help="run the prefill tiles and the decode work items of a mixed batch as two kernels in a row "
-                         "instead of one fused grid")
+    ap.add_argument("--mixed-arrangement", default="auto", choices=["auto", "separate", "behind", "beside"],
+                    help="how a batch with decode tokens and chunks is launched: the host's choice (auto), two kernels "
+                         "in a row, one grid with the decode work behind the tiles, or one grid with a decode "
+                         "workgroup per CU beside the tiles")
+    ap.add_argument("--separate-launches", action="store_true", help="the same as --mixed-arrangement separate")
     ap.add_argument("--append-sweep", action="store_true", help="also time cs_kv_append over growing token counts")
     ap.add_argument("--fit-latency-model", action="store_true",
                     help="also run the (P, C) timing grid and fit the paper's latency model to this path")
@@ -676,7 +683,9 @@ def main():
     cs.lib()                                   # fail loudly if the HIP library is not built
     torch.cuda.set_device(0)
     cs.cs_set_decode_split_tokens(args.split_tokens)
-    cs.cs_set_mixed_fusion(0 if args.separate_launches else 1)
+    if args.separate_launches:
+        args.mixed_arrangement = "separate"
+    cs.cs_set_mixed_fusion({"auto": 1, "separate": 0, "behind": 2, "beside": 3}[args.mixed_arrangement])
     if args.calibration_copy_gib > 0:
         n = int(args.calibration_copy_gib * (1 << 30)) // 16 * 16
         src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 255)
@@ -689,7 +698,7 @@ def main():
     if args.page_size != 16 and args.workload not in ("llama8b_decode", "qwen7b_mixed", "llama70b_long"):
         sys.exit("bench.py: --page-size 8 is for the workloads llama8b_decode, qwen7b_mixed and llama70b_long")
 
-    fused = not args.separate_launches
+    fused = args.mixed_arrangement != "separate"
     b, info, legs, detail, sec_per_step = measure(args.workload, args.steps, args.warmup, args)
     by_name = {l.name: l for l in legs}
     att_us = by_name["kv_append"].us + by_name["paged_attention_mixed"].us
@@ -710,7 +719,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": info["name"], "num_seqs": info["S"], "num_tokens": info["T"],
-                   "page_size": args.page_size, "layers_per_step": 1,
+                   "page_size": args.page_size, "layers_per_step": 1, "attention_launch": info["arrangement"],
                    "step": "+".join(l.name for l in legs)},
         "roofline": roofline,
         "legs": {l.name: leg_record(l, args.workload, args.dtype, args.page_size, fused) for l in legs + detail},
@@ -736,6 +745,7 @@ def main():
             on = {l.name: l for l in olegs}
             result["workloads"][oinfo["name"]] = {
                 "num_seqs": oinfo["S"], "num_tokens": oinfo["T"], "steps": o_steps, "warmup": o_warm,
+                "attention_launch": oinfo["arrangement"],
                 "tokens_per_s": round(oinfo["T"] / ((on["kv_append"].us + on["paged_attention_mixed"].us) * 1e-6), 1),
                 "ms_per_step": round(osec * 1e3, 4),
                 "legs": {l.name: leg_record(l, name, args.dtype, args.page_size, fused) for l in olegs + odetail}}

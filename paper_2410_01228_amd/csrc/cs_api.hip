@@ -306,22 +306,93 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
 // one grid with the decode pairs behind the tiles, or as one grid with a decode workgroup per CU
 // beside the tiles.  mode: cs_set_mixed_fusion's (0 never fuse, 1 choose, 2 always behind, 3
 // always beside).
-//
-// The choice between "behind" and "beside" comes from a small simulation of both grids over the
-// chip's 2 * CUs workgroup slots, in microseconds.  A tile workgroup of n steps lasts (n + 8) * c
-// (c = 0.88 us per 32-key step at head dim 128 for a workgroup that shares its CU); workgroups
-// take the earliest free slot in launch order.  Behind: the decode bytes flow at 6.5 TB/s times
-// min(1, free slots / (1.5 CUs)) into the slots the tiles have left for good.  Beside: one slot
-// per CU is the decode workgroup's until all bytes have passed at 6.5 TB/s, a tile next to it
-// runs 1.1 times longer.  Over 72 mixes of two model shapes, taking the faster of the two by this
-// model is on average 0.6% slower than taking the faster by measurement (always behind: 5.0%,
-// always beside: 3.0%); the merges of cut tiles and cut sequences cost the same either way.
 struct FusePlan {
     int32_t arrangement;       // 0 two kernels, 1 decode behind the tiles, 2 decode beside the tiles
     bool prio;                 // tiles alternate their issue priority (decode side small)
     int32_t persistent_wgs;    // arrangement 2: decode workgroups (one per CU)
 };
 
+// The tile workgroups of a fused grid played through the chip's workgroup slots (two per CU), in
+// microseconds.  work[i]: what workgroup i takes while another tile shares its CU; it runs
+// kSoloTile of that while the CU's other slot is empty and kBesideDecode of it beside a decode
+// workgroup.  The dispatcher gives the first `cus` workgroups a CU each, the next `cus` the
+// second slot of those CUs, and every later one the slot that frees first.  decode_until > 0:
+// slot 0 of every CU is a decode workgroup's until then.  Returns when the last tile ends;
+// free_at (two entries per CU) receives when each slot was last released.
+constexpr double kSoloTile = 0.78, kBesideDecode = 1.1;
+static double play_tiles(const std::vector<float>& work, int32_t cus, double decode_until, std::vector<double>& free_at) {
+    struct Cu { int8_t kind[2]; double rem[2]; double last; uint32_t ver; };     // kind: 0 empty, 1 tile, 2 decode
+    struct Event { double t; int32_t cu, slot; uint32_t ver; };
+    auto later = [](const Event& a, const Event& b) { return a.t > b.t; };
+    std::vector<Cu> cu((size_t)cus, Cu{{0, 0}, {0, 0}, 0, 0});
+    std::vector<Event> ev;
+    free_at.assign(2 * (size_t)cus, 0.0);
+    size_t next = 0;
+    auto rate = [&](const Cu& c, int s) {
+        const int8_t other = c.kind[1 - s];
+        return other == 1 ? 1.0 : other == 2 ? 1.0 / kBesideDecode : 1.0 / kSoloTile;
+    };
+    auto advance = [&](Cu& c, double t) {
+        for (int s = 0; s < 2; ++s)
+            if (c.kind[s] == 1) c.rem[s] -= (t - c.last) * rate(c, s);
+        c.last = t;
+    };
+    auto take_next = [&](Cu& c, int s) {
+        if (next < work.size()) { c.kind[s] = 1; c.rem[s] = work[next++]; }
+    };
+    auto announce = [&](int32_t i, double t) {               // the ends of CU i's tiles at today's rates
+        Cu& c = cu[(size_t)i];
+        ++c.ver;
+        for (int s = 0; s < 2; ++s)
+            if (c.kind[s] == 1) {
+                ev.push_back(Event{t + std::max(c.rem[s], 0.0) / rate(c, s), i, s, c.ver});
+                std::push_heap(ev.begin(), ev.end(), later);
+            }
+    };
+    if (decode_until > 0) {
+        for (Cu& c : cu) c.kind[0] = 2;
+        ev.push_back(Event{decode_until, -1, 0, 0});
+    }
+    for (int s = 0; s < 2; ++s)
+        for (Cu& c : cu)
+            if (c.kind[s] == 0) take_next(c, s);
+    for (int32_t i = 0; i < cus; ++i) announce(i, 0.0);
+    double end = 0;
+    while (!ev.empty()) {
+        std::pop_heap(ev.begin(), ev.end(), later);
+        const Event e = ev.back();
+        ev.pop_back();
+        if (e.cu < 0) {                                       // the decode workgroups retire
+            for (int32_t i = 0; i < cus; ++i) {
+                Cu& c = cu[(size_t)i];
+                advance(c, e.t);
+                c.kind[0] = 0;
+                free_at[2 * (size_t)i] = e.t;
+                take_next(c, 0);
+                announce(i, e.t);
+            }
+            continue;
+        }
+        Cu& c = cu[(size_t)e.cu];
+        if (e.ver != c.ver) continue;                         // overtaken by a change on that CU
+        advance(c, e.t);
+        c.kind[e.slot] = 0;
+        free_at[2 * (size_t)e.cu + e.slot] = e.t;
+        end = std::max(end, e.t);
+        take_next(c, e.slot);
+        announce(e.cu, e.t);
+    }
+    return end;
+}
+
+// The choice between "behind" and "beside" comes from playing both grids (play_tiles).  A tile
+// workgroup of n steps takes (n + 8) * 0.88 us (a 32-key step at head dim 128 beside another
+// tile).  Behind: the decode bytes flow at 6.5 TB/s times min(1, free slots / (1.56 CUs)) into
+// the slots the tiles have left for good.  Beside: one slot per CU is a decode workgroup's until
+// all bytes have passed at 6.5 TB/s.  Over 72 mixes of two model shapes, taking the faster of the
+// two by this model is on average 0.3% slower than taking the faster by measurement (always
+// behind: 5.0%, always beside: 3.0%); the merges of cut tiles and cut sequences cost the same
+// either way.
 static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, const PrefillPlan& p, int32_t Hq, int32_t Hkv,
                             int32_t D, int32_t mode) {
     FusePlan f = {0, false, 0};
@@ -344,62 +415,52 @@ static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, const Prefil
     f.arrangement = (mode == 2 || t_decode <= 10.0 * t_prefill) ? 1 : 0;
     f.prio = t_decode < 0.3 * t_prefill;
     const int32_t cus = device_cus();
-    if (mode == 2 || (mode == 1 && D != 128)) return f;   // (head dim 64 fits three workgroups per CU: not measured beside)
+    // (head dim 64 fits three workgroups per CU, both kinds already share CUs behind the tiles,
+    // and beside wins on some mixes and loses on others: the choice there is not modelled)
+    if (mode == 2 || (mode == 1 && D != 128)) return f;
     bool beside = mode == 3;
-    if (mode == 1) {
-        // steps of every tile slot, in the fused grid's launch order
-        std::vector<int32_t> slot_steps((size_t)p.num_slots, 0);
-        for (int32_t s = 0; s < b->num_seqs; ++s) {
-            const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
-            if (ql <= 1) continue;
-            const int32_t n_ct = ((ql + 15) >> 4) * G;
-            const int64_t slot0 = prefill_slot_start(b->h_cu_q_lens[s], s, G) - p.base_slot;
-            for (int32_t ct0 = 0; ct0 < n_ct; ct0 += kTileCols) {
-                const int32_t tb_max = (std::min(ct0 + kTileCols, n_ct) - 1) / G;
-                const int32_t n_keys = b->h_ctx_lens[s] + std::min(ql, (tb_max + 1) * 16);
-                slot_steps[(size_t)(slot0 + ct0 / kTileCols)] = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
-            }
-        }
-        const double c_step = 0.88, t_dec = decode_bytes / 6.5e6;           // microseconds
-        const size_t n_slots = 2 * (size_t)cus;
-        // list scheduling of the tile workgroups over slots that become available at avail[]
-        auto schedule = [&](std::vector<double>& avail, double stretch) {
-            std::make_heap(avail.begin(), avail.end(), std::greater<double>());
-            double end = 0;
-            for (int32_t r = 0; r < p.max_ranges; ++r)
-                for (int32_t pos = 0; pos < p.num_slots; ++pos) {
-                    const int32_t steps = slot_steps[(size_t)(p.backwards ? p.num_slots - 1 - pos : pos)];
-                    const int32_t n = std::min(steps, (r + 1) * p.range_steps) - r * p.range_steps;
-                    if (n <= 0) continue;
-                    for (int32_t g = 0; g < Hkv; ++g) {
-                        std::pop_heap(avail.begin(), avail.end(), std::greater<double>());
-                        const double t = avail.back() + (n + 8) * c_step * stretch;
-                        avail.back() = t;
-                        end = std::max(end, t);
-                        std::push_heap(avail.begin(), avail.end(), std::greater<double>());
-                    }
-                }
-            return end;
-        };
+    // (a decode side under 0.3 of the prefill side stays behind tiles that alternate their
+    // priority: measured 5-8% better than beside on such mixes, which the model calls even)
+    if (mode == 1 && !f.prio) {
         const int64_t tile_wgs = (int64_t)p.num_slots * Hkv * p.max_ranges;
         if (tile_wgs > 65536) {
             beside = t_decode >= 0.05 * t_prefill;     // many rounds of tiles: beside always overlaps
         } else {
-            std::vector<double> avail(n_slots, 0.0);
-            schedule(avail, 1.0);
-            std::sort(avail.begin(), avail.end());       // when each slot is free for good
+            // steps of every tile slot, then the workgroups in the fused grid's launch order
+            std::vector<int32_t> slot_steps((size_t)p.num_slots, 0);
+            for (int32_t s = 0; s < b->num_seqs; ++s) {
+                const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+                if (ql <= 1) continue;
+                const int32_t n_ct = ((ql + 15) >> 4) * G;
+                const int64_t slot0 = prefill_slot_start(b->h_cu_q_lens[s], s, G) - p.base_slot;
+                for (int32_t ct0 = 0; ct0 < n_ct; ct0 += kTileCols) {
+                    const int32_t tb_max = (std::min(ct0 + kTileCols, n_ct) - 1) / G;
+                    const int32_t n_keys = b->h_ctx_lens[s] + std::min(ql, (tb_max + 1) * 16);
+                    slot_steps[(size_t)(slot0 + ct0 / kTileCols)] = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
+                }
+            }
+            const double us_per_step = 0.88, t_dec = decode_bytes / 6.5e6;      // microseconds
+            std::vector<float> work;
+            work.reserve((size_t)tile_wgs);
+            for (int32_t r = 0; r < p.max_ranges; ++r)
+                for (int32_t pos = 0; pos < p.num_slots; ++pos) {
+                    const int32_t steps = slot_steps[(size_t)(p.backwards ? p.num_slots - 1 - pos : pos)];
+                    const int32_t n = std::min(steps, (r + 1) * p.range_steps) - r * p.range_steps;
+                    if (n > 0) work.insert(work.end(), (size_t)Hkv, (float)((n + 8) * us_per_step));
+                }
+            std::vector<double> free_at;
+            play_tiles(work, cus, 0.0, free_at);
+            std::sort(free_at.begin(), free_at.end());
             double t = 0, left = t_dec, t_behind = 0;
-            const double sat = 1.5 * cus;
+            const double sat = 1.56 * cus;
             for (size_t i = 0; ; ++i) {
                 const double rate = std::min(1.0, (double)i / sat);          // i slots are free
-                const double next = i < n_slots ? avail[i] : 1.0e300;
+                const double next = i < free_at.size() ? free_at[i] : 1.0e300;
                 if (rate > 0 && t + left / rate <= next) { t_behind = t + left / rate; break; }
                 left -= rate * (next - t);
                 t = next;
             }
-            std::vector<double> avail2(n_slots, 0.0);
-            for (size_t i = 0; i < (size_t)cus; ++i) avail2[i] = t_dec;
-            const double t_beside = std::max(schedule(avail2, 1.1), t_dec);
+            const double t_beside = std::max(play_tiles(work, cus, t_dec, free_at), t_dec);
             beside = t_beside < t_behind;
         }
     }
