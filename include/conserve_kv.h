@@ -11,7 +11,7 @@
  *     calls never synchronise and never allocate or free device memory.  State kept between
  *     calls: the host-side cs_page_map object at the end of this file; the measurement knobs
  *     cs_set_decode_split_tokens / cs_set_decode_pages_ahead / cs_set_mixed_fusion /
- *     cs_debug_set_cu_count, which are process-wide, change launch plans and workspace sizes,
+ *     cs_debug_set_cu_count / cs_debug_set_tail_cut, which are process-wide, change launch plans and workspace sizes,
  *     and are meant for benchmarks and tests only (a serving process leaves them alone); and,
  *     invisible to the caller, each thread's memo of the last launch plans it made and each
  *     device's compute-unit count, asked once;
@@ -397,6 +397,21 @@ void cs_set_mixed_fusion(int32_t mode);
  * of work), 1 decode behind the tiles, 2 decode beside the tiles; CS_ERR_INVALID_ARG on bad
  * arguments.  No device work. */
 int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
+
+/* Host-only view of the key-range cut of the batch's prefill tiles, for tests: returns the number
+ * of tile slots in launch order (a slot is 8 column tiles of 16 query rows of one kv head group;
+ * slots of sequences without a chunk are empty), *first_cut the launch position from which tiles
+ * are cut (0: every tile that is long enough; beside the tiles the host cuts only the last
+ * round's), *ranges the ranges of the longest cut tile (1: nothing is cut).  CS_ERR_INVALID_ARG
+ * on bad arguments.  No device work. */
+int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
+                                int32_t* first_cut, int32_t* ranges);
+
+/* Tuning knob for measurements and tests: in a fused mixed launch, leave the tiles of the launch
+ * positions before `whole_tiles` whole and cut those from it on into `ranges` key ranges (of the
+ * longest tile's steps / ranges), whatever the host's model says; whole_tiles < 0 or ranges < 1:
+ * the host decides again.  Process-wide; changes launch plans and workspace sizes. */
+void cs_debug_set_tail_cut(int32_t whole_tiles, int32_t ranges);
 
 const char* cs_status_string(int status);
 /* Text of the last HIP error seen by this thread inside the library ("" if none). */

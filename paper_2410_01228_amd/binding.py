@@ -127,6 +127,9 @@ def lib():
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
         L.cs_debug_mixed_arrangement.restype, L.cs_debug_mixed_arrangement.argtypes = i32, [BP, i32, i32, i32]
+        L.cs_debug_set_tail_cut.restype, L.cs_debug_set_tail_cut.argtypes = None, [i32, i32]
+        L.cs_debug_mixed_tail_cut.restype = i32
+        L.cs_debug_mixed_tail_cut.argtypes = [BP, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.cs_set_decode_pages_ahead.restype, L.cs_set_decode_pages_ahead.argtypes = None, [i32]
         L.cs_debug_prefill_order.restype = ctypes.c_int32
         L.cs_debug_prefill_order.argtypes = [BP, i32, i32, i32, ctypes.POINTER(ctypes.c_int32), i32]
@@ -146,7 +149,7 @@ EXPORTS = [
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
     "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_run_layers_workspace_bytes", "cs_debug_set_cu_count", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
-    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_status_string", "cs_last_hip_error",
+    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_debug_mixed_tail_cut", "cs_debug_set_tail_cut", "cs_status_string", "cs_last_hip_error",
 ]
 
 
@@ -469,6 +472,21 @@ def cs_debug_mixed_arrangement(batch: "Batch", Hq: int, Hkv: int, D: int) -> int
     if rc < 0:
         raise CsError(rc, "cs_debug_mixed_arrangement")
     return rc
+
+
+def cs_debug_set_tail_cut(whole_tiles: int, ranges: int):
+    """Force the tail cut of fused mixed launches (whole_tiles < 0: the host decides again)."""
+    lib().cs_debug_set_tail_cut(int(whole_tiles), int(ranges))
+
+
+def cs_debug_mixed_tail_cut(batch: "Batch", Hq: int, Hkv: int, D: int):
+    """(tile slots in launch order, launch position from which tiles are cut, ranges of the longest
+    cut tile) -- host only."""
+    first, ranges = ctypes.c_int32(0), ctypes.c_int32(0)
+    n = lib().cs_debug_mixed_tail_cut(ctypes.byref(batch.c), Hq, Hkv, D, ctypes.byref(first), ctypes.byref(ranges))
+    if n < 0:
+        raise CsError(n, "cs_debug_mixed_tail_cut")
+    return n, first.value, ranges.value
 
 
 def cs_set_decode_split_tokens(tokens: int):

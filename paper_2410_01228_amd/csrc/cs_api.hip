@@ -17,6 +17,7 @@ static std::atomic<int32_t> g_forced_split{0};
 static std::atomic<int32_t> g_fuse_mixed{1};
 static std::atomic<int32_t> g_forced_ahead{0};
 static std::atomic<int32_t> g_forced_cus{0};
+static std::atomic<int32_t> g_forced_tail_whole{-1}, g_forced_tail_ranges{0};    // cs_debug_set_tail_cut
 
 // Compute units of the current device, asked once per device.  The launch plans size their
 // grids by it.  A host without a device (a plan query in a CPU-only test) plans for 256.
@@ -191,7 +192,7 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     PrefillPlan p = {};
     const int32_t G = Hq / Hkv;
     int64_t total_steps = 0, tiles = 0;
-    int32_t max_steps = 0, first = -1;
+    int32_t max_steps = 0, first = -1, last = -1;
     struct Tile { int32_t steps, slot; };
     Tile tile_list[kMaxSlotOrder];
     int32_t n_listed = 0;
@@ -199,6 +200,7 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
         const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
         if (ql <= 1) continue;
         if (first < 0) first = s;
+        last = s;
         const int32_t C = b->h_ctx_lens[s];
         const int32_t n_ct = ((ql + 15) >> 4) * G;
         for (int32_t ct0 = 0; ct0 < n_ct; ct0 += kTileCols) {
@@ -216,7 +218,8 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
     p.max_ranges = 1;
     if (tiles == 0) return p;
     p.base_slot = (int32_t)prefill_slot_start(b->h_cu_q_lens[first], first, G);
-    p.num_slots = (int32_t)(prefill_slot_start(b->num_tokens, b->num_seqs, G) - p.base_slot);
+    // (the slots of the sequences before the first chunk and behind the last one are empty)
+    p.num_slots = (int32_t)(prefill_slot_start(b->h_cu_q_lens[last + 1], last + 1, G) - p.base_slot);
     const int64_t wgs = tiles * Hkv;
 
     // The chip: `cus` compute units, two workgroup slots each.  (The counts in the comments below
@@ -318,9 +321,11 @@ struct FusePlan {
 // workgroup.  The dispatcher gives the first `cus` workgroups a CU each, the next `cus` the
 // second slot of those CUs, and every later one the slot that frees first.  decode_until > 0:
 // slot 0 of every CU is a decode workgroup's until then.  Returns when the last tile ends;
-// free_at (two entries per CU) receives when each slot was last released.
+// free_at (two entries per CU) receives when each slot was last released, started (optional)
+// when each workgroup began.
 constexpr double kSoloTile = 0.78, kBesideDecode = 1.1;
-static double play_tiles(const std::vector<float>& work, int32_t cus, double decode_until, std::vector<double>& free_at) {
+static double play_tiles(const std::vector<float>& work, int32_t cus, double decode_until, std::vector<double>& free_at,
+                         std::vector<float>* started = nullptr) {
     struct Cu { int8_t kind[2]; double rem[2]; double last; uint32_t ver; };     // kind: 0 empty, 1 tile, 2 decode
     struct Event { double t; int32_t cu, slot; uint32_t ver; };
     auto later = [](const Event& a, const Event& b) { return a.t > b.t; };
@@ -337,8 +342,14 @@ static double play_tiles(const std::vector<float>& work, int32_t cus, double dec
             if (c.kind[s] == 1) c.rem[s] -= (t - c.last) * rate(c, s);
         c.last = t;
     };
+    double now = 0;
+    if (started) started->assign(work.size(), 0.f);
     auto take_next = [&](Cu& c, int s) {
-        if (next < work.size()) { c.kind[s] = 1; c.rem[s] = work[next++]; }
+        if (next < work.size()) {
+            if (started) (*started)[next] = (float)now;
+            c.kind[s] = 1;
+            c.rem[s] = work[next++];
+        }
     };
     auto announce = [&](int32_t i, double t) {               // the ends of CU i's tiles at today's rates
         Cu& c = cu[(size_t)i];
@@ -362,6 +373,7 @@ static double play_tiles(const std::vector<float>& work, int32_t cus, double dec
         std::pop_heap(ev.begin(), ev.end(), later);
         const Event e = ev.back();
         ev.pop_back();
+        now = e.t;
         if (e.cu < 0) {                                       // the decode workgroups retire
             for (int32_t i = 0; i < cus; ++i) {
                 Cu& c = cu[(size_t)i];
@@ -393,8 +405,15 @@ static double play_tiles(const std::vector<float>& work, int32_t cus, double dec
 // two by this model is on average 0.3% slower than taking the faster by measurement (always
 // behind: 5.0%, always beside: 3.0%); the merges of cut tiles and cut sequences cost the same
 // either way.
-static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, const PrefillPlan& p, int32_t Hq, int32_t Hkv,
-                            int32_t D, int32_t mode) {
+//
+// Beside the tiles, the tiles of the last round are cut (p is changed): a tile that starts when
+// the decode side is about done runs alone on its CU, one wavefront per SIMD, while the slot the
+// decode workgroup has left stays empty.  The launch positions from the first such tile on are
+// cut into two or three key ranges, so that the pieces fill both slots; taken when the model
+// promises 6% of the whole call after the cost of the partials (it overrates what cutting gains
+// beside a decode load, so the bar is not lower).
+static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, PrefillPlan& p, int32_t Hq, int32_t Hkv,
+                                     int32_t D, int32_t mode) {
     FusePlan f = {0, false, 0};
     if (d.num_prefill == 0 || d.num_decode == 0 || !d.in_args || mode == 0) return f;
     const int32_t G = Hq / Hkv;
@@ -419,12 +438,13 @@ static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, const Prefil
     // and beside wins on some mixes and loses on others: the choice there is not modelled)
     if (mode == 2 || (mode == 1 && D != 128)) return f;
     bool beside = mode == 3;
+    const int64_t tile_wgs = (int64_t)p.num_slots * Hkv * p.max_ranges;
+    const double us_per_step = 0.88, t_dec = decode_bytes / 6.5e6;      // microseconds
     // (a decode side under 0.3 of the prefill side stays behind tiles that alternate their
     // priority: measured 5-8% better than beside on such mixes, which the model calls even)
-    if (mode == 1 && !f.prio) {
-        const int64_t tile_wgs = (int64_t)p.num_slots * Hkv * p.max_ranges;
+    if ((mode == 1 && !f.prio) || mode == 3) {
         if (tile_wgs > 65536) {
-            beside = t_decode >= 0.05 * t_prefill;     // many rounds of tiles: beside always overlaps
+            beside = beside || t_decode >= 0.05 * t_prefill;     // many rounds of tiles: beside always overlaps
         } else {
             // steps of every tile slot, then the workgroups in the fused grid's launch order
             std::vector<int32_t> slot_steps((size_t)p.num_slots, 0);
@@ -439,35 +459,99 @@ static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, const Prefil
                     slot_steps[(size_t)(slot0 + ct0 / kTileCols)] = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
                 }
             }
-            const double us_per_step = 0.88, t_dec = decode_bytes / 6.5e6;      // microseconds
+            auto steps_at = [&](int32_t pos) { return slot_steps[(size_t)(p.backwards ? p.num_slots - 1 - pos : pos)]; };
+            // the grid's tile workgroups in launch order: whole tiles up to position `whole`, then,
+            // range-major, the ranges of `range_steps` steps of the tiles behind them
             std::vector<float> work;
-            work.reserve((size_t)tile_wgs);
-            for (int32_t r = 0; r < p.max_ranges; ++r)
-                for (int32_t pos = 0; pos < p.num_slots; ++pos) {
-                    const int32_t steps = slot_steps[(size_t)(p.backwards ? p.num_slots - 1 - pos : pos)];
-                    const int32_t n = std::min(steps, (r + 1) * p.range_steps) - r * p.range_steps;
-                    if (n > 0) work.insert(work.end(), (size_t)Hkv, (float)((n + 8) * us_per_step));
-                }
+            std::vector<int32_t> pos_of;
+            auto list_work = [&](int32_t whole, int32_t range_steps, int32_t ranges) {
+                work.clear();
+                pos_of.clear();
+                for (int32_t pos = 0; pos < whole; ++pos)
+                    if (steps_at(pos) > 0) {
+                        work.insert(work.end(), (size_t)Hkv, (float)((steps_at(pos) + 8) * us_per_step));
+                        pos_of.insert(pos_of.end(), (size_t)Hkv, pos);
+                    }
+                for (int32_t r = 0; r < ranges; ++r)
+                    for (int32_t pos = whole; pos < p.num_slots; ++pos) {
+                        const int32_t n = std::min(steps_at(pos), (r + 1) * range_steps) - r * range_steps;
+                        if (n > 0) {
+                            work.insert(work.end(), (size_t)Hkv, (float)((n + 8) * us_per_step));
+                            pos_of.insert(pos_of.end(), (size_t)Hkv, pos);
+                        }
+                    }
+            };
+            list_work(0, p.range_steps, p.max_ranges);
             std::vector<double> free_at;
-            play_tiles(work, cus, 0.0, free_at);
-            std::sort(free_at.begin(), free_at.end());
-            double t = 0, left = t_dec, t_behind = 0;
-            const double sat = 1.56 * cus;
-            for (size_t i = 0; ; ++i) {
-                const double rate = std::min(1.0, (double)i / sat);          // i slots are free
-                const double next = i < free_at.size() ? free_at[i] : 1.0e300;
-                if (rate > 0 && t + left / rate <= next) { t_behind = t + left / rate; break; }
-                left -= rate * (next - t);
-                t = next;
+            std::vector<float> started;
+            if (mode == 1) {
+                play_tiles(work, cus, 0.0, free_at);
+                std::sort(free_at.begin(), free_at.end());
+                double t = 0, left = t_dec, t_behind = 0;
+                const double sat = 1.56 * cus;
+                for (size_t i = 0; ; ++i) {
+                    const double rate = std::min(1.0, (double)i / sat);          // i slots are free
+                    const double next = i < free_at.size() ? free_at[i] : 1.0e300;
+                    if (rate > 0 && t + left / rate <= next) { t_behind = t + left / rate; break; }
+                    left -= rate * (next - t);
+                    t = next;
+                }
+                const double t_beside = std::max(play_tiles(work, cus, t_dec, free_at, &started), t_dec);
+                beside = t_beside < t_behind;
             }
-            const double t_beside = std::max(play_tiles(work, cus, t_dec, free_at), t_dec);
-            beside = t_beside < t_behind;
+            if (beside && p.max_ranges == 1 && !work.empty() && g_forced_tail_whole.load() != -2) {
+                // the tiles of the last round, cut: from the first tile that starts when the
+                // decode side is at least 0.85 done
+                const double t_whole = std::max(play_tiles(work, cus, t_dec, free_at, &started), t_dec);
+                size_t first = 0;
+                while (first < work.size() && started[first] < 0.85 * t_dec) ++first;
+                if (first > 0 && first < work.size()) {
+                    const int32_t whole = pos_of[first];
+                    int32_t tail_steps = 0;
+                    for (int32_t pos = whole; pos < p.num_slots; ++pos) tail_steps = std::max(tail_steps, steps_at(pos));
+                    double best = 0.94 * t_whole;
+                    for (int32_t r = 2; r <= 3 && tail_steps / r >= 32; ++r) {
+                        const int32_t rs = (tail_steps + r - 1) / r, ranges = (tail_steps + rs - 1) / rs;
+                        list_work(whole, rs, ranges);
+                        const double part_bytes = (double)(p.num_slots - whole) * Hkv * ranges * kTileCols * 16 * (D + 4) * 4.0;
+                        const double t_cut = std::max(play_tiles(work, cus, t_dec, free_at), t_dec) + 10.0 + 2.0 * part_bytes / 5.0e6;
+                        if (t_cut < best) {
+                            best = t_cut;
+                            p.cut_first_pos = whole;
+                            p.range_steps = rs;
+                            p.max_ranges = ranges;
+                            p.bytes = (size_t)part_bytes;
+                        }
+                    }
+                }
+            }
         }
     }
     if (beside) {
         f.arrangement = 2;
         f.prio = false;
         f.persistent_wgs = cus;
+    }
+    return f;
+}
+
+static FusePlan plan_fusion(const cs_batch* b, const DecodePlan& d, PrefillPlan& p, int32_t Hq, int32_t Hkv,
+                            int32_t D, int32_t mode) {
+    const FusePlan f = plan_fusion_by_model(b, d, p, Hq, Hkv, D, mode);
+    const int32_t forced_whole = g_forced_tail_whole.load(), forced_ranges = g_forced_tail_ranges.load();
+    if (forced_whole >= 0 && forced_ranges >= 1 && f.arrangement != 0) {
+        // measurement and test knob: cut the launch positions from forced_whole on into forced_ranges
+        p = plan_prefill(b, Hq, Hkv, D);
+        p.n_ordered = 0;
+        p.cut_first_pos = std::min(forced_whole, p.num_slots);
+        int32_t tail_steps = 1;
+        for (int32_t s = 0; s < b->num_seqs; ++s) {           // (the longest tile of all: an upper bound of the tail's)
+            const int32_t ql = b->h_cu_q_lens[s + 1] - b->h_cu_q_lens[s];
+            if (ql > 1) tail_steps = std::max(tail_steps, (b->h_ctx_lens[s] + ql + kKeysPerStep - 1) / kKeysPerStep);
+        }
+        p.range_steps = (tail_steps + forced_ranges - 1) / forced_ranges;
+        p.max_ranges = p.cut_first_pos < p.num_slots ? (tail_steps + p.range_steps - 1) / p.range_steps : 1;
+        p.bytes = p.max_ranges > 1 ? (size_t)(p.num_slots - p.cut_first_pos) * Hkv * p.max_ranges * kTileCols * 16 * (D + 4) * sizeof(float) : 0;
     }
     return f;
 }
@@ -537,7 +621,7 @@ struct Plans {
 };
 struct PlanMemo {
     bool valid = false;
-    int32_t S = 0, T = 0, Hq = 0, Hkv = 0, D = 0, split = 0, ahead = 0, cus = 0, fuse = 0;
+    int32_t S = 0, T = 0, Hq = 0, Hkv = 0, D = 0, split = 0, ahead = 0, cus = 0, fuse = 0, tail_whole = -1, tail_ranges = 0;
     std::vector<int32_t> ctx, cu;
     Plans plans;
 };
@@ -545,16 +629,16 @@ static const Plans& plans_for(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_
     static thread_local PlanMemo memo[2];
     static thread_local int next = 0;
     const int32_t S = b->num_seqs, split = g_forced_split.load(), ahead = g_forced_ahead.load(), cus = device_cus();
-    const int32_t fuse = g_fuse_mixed.load();
+    const int32_t fuse = g_fuse_mixed.load(), tail_whole = g_forced_tail_whole.load(), tail_ranges = g_forced_tail_ranges.load();
     for (PlanMemo& m : memo)
-        if (m.valid && m.fuse == fuse && m.S == S && m.T == b->num_tokens && m.Hq == Hq && m.Hkv == Hkv && m.D == D && m.split == split &&
+        if (m.valid && m.fuse == fuse && m.tail_whole == tail_whole && m.tail_ranges == tail_ranges && m.S == S && m.T == b->num_tokens && m.Hq == Hq && m.Hkv == Hkv && m.D == D && m.split == split &&
             m.ahead == ahead && m.cus == cus && memcmp(m.ctx.data(), b->h_ctx_lens, sizeof(int32_t) * S) == 0 &&
             memcmp(m.cu.data(), b->h_cu_q_lens, sizeof(int32_t) * (S + 1)) == 0)
             return m.plans;
     PlanMemo& m = memo[next];
     next ^= 1;
     m.valid = false;
-    m.S = S; m.T = b->num_tokens; m.Hq = Hq; m.Hkv = Hkv; m.D = D; m.split = split; m.ahead = ahead; m.cus = cus; m.fuse = fuse;
+    m.S = S; m.T = b->num_tokens; m.Hq = Hq; m.Hkv = Hkv; m.D = D; m.split = split; m.ahead = ahead; m.cus = cus; m.fuse = fuse; m.tail_whole = tail_whole; m.tail_ranges = tail_ranges;
     m.ctx.assign(b->h_ctx_lens, b->h_ctx_lens + S);
     m.cu.assign(b->h_cu_q_lens, b->h_cu_q_lens + S + 1);
     m.plans.d = plan_decode(b, Hkv, D);
@@ -870,6 +954,20 @@ int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t Hq, int32_t Hk
     if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return CS_ERR_INVALID_ARG;
     if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return CS_ERR_INVALID_ARG;
     return plans_for(batch, Hq, Hkv, D).f.arrangement;
+}
+
+int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D, int32_t* first_cut, int32_t* ranges) {
+    if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return CS_ERR_INVALID_ARG;
+    if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return CS_ERR_INVALID_ARG;
+    const PrefillPlan& p = plans_for(batch, Hq, Hkv, D).p;
+    if (first_cut) *first_cut = p.cut_first_pos;
+    if (ranges) *ranges = p.max_ranges;
+    return p.num_slots;
+}
+
+void cs_debug_set_tail_cut(int32_t whole_tiles, int32_t ranges) {
+    g_forced_tail_whole.store(whole_tiles >= 0 && ranges >= 1 ? whole_tiles : whole_tiles == -2 ? -2 : -1);   // (-2: no cut by the model either)
+    g_forced_tail_ranges.store(whole_tiles >= 0 && ranges >= 1 ? ranges : 0);
 }
 
 void cs_set_mixed_fusion(int32_t mode) {

@@ -113,6 +113,7 @@ struct PrefillPlan {
     bool    backwards;         // where no table is used: grid position p takes slot (slots - 1 - p)
     int32_t range_steps;       // 32-key steps per key range (>= the longest tile: no split)
     int32_t max_ranges;        // grid depth: ranges of the longest tile
+    int32_t cut_first_pos;     // launch positions from this one on are cut (the fused grid's tail; 0: every tile longer than range_steps)
     int32_t base_slot;         // first workgroup slot that can belong to a prefill sequence (set whenever there is a chunk)
     int32_t num_slots;         // slots from base_slot on: the grid's extent; partials are indexed by slot - base_slot
     size_t  bytes;             // workspace for the partials (0 when nothing is cut)

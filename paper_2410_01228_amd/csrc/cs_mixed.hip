@@ -27,8 +27,10 @@ union MixedLds {
 };
 
 // Workgroups [dec_first, dec_first + dec_wgs) are decode workgroups, the others tiles (numbered
-// without the gap).  Tiles: range-major from tile slot base_slot on, like the prefill kernel's
-// own grid.  Decode workgroup j takes the pairs j, 2*dec_wgs-1-j, 2*dec_wgs+j, ... of the
+// without the gap).  Tiles, in launch positions from tile slot base_slot on: first the whole
+// tiles of positions 0 .. cut_first_pos-1, then, range-major like the prefill kernel's own grid,
+// the key ranges of the positions behind them (cut_first_pos == 0: every tile longer than
+// range_steps is cut; == num_slots with max_ranges == 1: none is).  Decode workgroup j takes the pairs j, 2*dec_wgs-1-j, 2*dec_wgs+j, ... of the
 // n_decode (item, kv head) pairs: the items are sorted longest first, so walking the rounds back
 // and forth evens the sums; with dec_wgs == n_decode that is one pair each.
 template <int D, class E, bool kPhasePriority, int PS>
@@ -38,20 +40,32 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
-    int32_t range_steps, int32_t base_slot, int32_t max_ranges, float* __restrict__ prefill_part,
-    uint32_t wgs_per_range, uint32_t dec_first, uint32_t dec_wgs, uint32_t n_decode, int32_t backwards,
+    int32_t range_steps, int32_t base_slot, int32_t num_slots, int32_t cut_first_pos, int32_t max_ranges,
+    float* __restrict__ prefill_part, uint32_t dec_first, uint32_t dec_wgs, uint32_t n_decode, int32_t backwards,
     const ItemsInArgs items, float* __restrict__ part_o, float* __restrict__ part_ml)
 {
     __shared__ MixedLds<D> lds;
     if (blockIdx.x < dec_first || blockIdx.x >= dec_first + dec_wgs) {
         const uint32_t ti = blockIdx.x < dec_first ? blockIdx.x : blockIdx.x - dec_wgs;
-        const uint32_t range = ti / wgs_per_range, rem = ti - range * wgs_per_range;
-        const int32_t pos = rem / Hkv;
-        const int32_t g = rem - pos * Hkv;
-        const int32_t b = base_slot + (backwards ? (int32_t)(wgs_per_range / Hkv) - 1 - pos : pos);   // longest tiles first
+        const uint32_t wgs_whole = (uint32_t)cut_first_pos * Hkv, wgs_per_range = (uint32_t)(num_slots - cut_first_pos) * Hkv;
+        // a whole tile: one range longer than any tile (and small enough to add a tile's steps to)
+        int32_t pos, g, range = 0, steps_per_range = 1 << 30;
+        float* part_tile = nullptr;
+        if (ti < wgs_whole) {
+            pos = ti / Hkv;
+            g = ti - pos * Hkv;
+        } else {
+            const uint32_t u = ti - wgs_whole;
+            range = u / wgs_per_range;
+            const uint32_t rem = u - range * wgs_per_range;
+            pos = cut_first_pos + rem / Hkv;
+            g = rem - (rem / Hkv) * Hkv;
+            steps_per_range = range_steps;
+            part_tile = partials_of<D>(prefill_part, pos - cut_first_pos, Hkv, g, max_ranges);
+        }
+        const int32_t b = base_slot + (backwards ? num_slots - 1 - pos : pos);   // backwards: longest tiles first
         prefill_tile<D, E, kPhasePriority, PS, true>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
-                           ctx_lens, cu_q_lens, q, out, scale_log2e, range_steps, base_slot, prefill_part, g, b,
-                           (int32_t)range, max_ranges);
+                           ctx_lens, cu_q_lens, q, out, scale_log2e, steps_per_range, part_tile, g, b, range);
     } else {
         const uint32_t j = blockIdx.x - dec_first;
         for (uint32_t base = 0, round = 0; base < n_decode; base += dec_wgs, ++round) {
@@ -76,8 +90,8 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
     const float scale_log2e = scale * 1.4426950408889634f;
-    const int64_t per_range = (int64_t)pplan.num_slots * Hkv;
-    const int64_t n_prefill = per_range * pplan.max_ranges, n_decode = (int64_t)dplan.total_items * Hkv;
+    const int64_t n_prefill = ((int64_t)pplan.cut_first_pos + (int64_t)(pplan.num_slots - pplan.cut_first_pos) * pplan.max_ranges) * Hkv;
+    const int64_t n_decode = (int64_t)dplan.total_items * Hkv;
     // decode beside the tiles: a few workgroups first; behind the tiles: one per pair, last
     const int64_t dec_wgs = persistent_wgs > 0 ? std::min<int64_t>(persistent_wgs, n_decode) : n_decode;
     const int64_t dec_first = persistent_wgs > 0 ? 0 : n_prefill;
@@ -90,8 +104,8 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
     hipLaunchKernelGGL((mixed_kernel<DD, E, PRIO, PS>), grid, dim3(kPrefillThreads), 0, st, layer_base, pool.page_stride, \
                        pool.num_pages, Hkv, G, b.num_seqs, b.block_tables, b.max_blocks_per_seq, b.ctx_lens,    \
                        b.cu_q_lens, (const uint16_t*)q, (uint16_t*)out, scale_log2e, pplan.range_steps,         \
-                       pplan.base_slot, pplan.max_ranges, (float*)prefill_ws, (uint32_t)per_range,              \
-                       (uint32_t)dec_first, (uint32_t)dec_wgs, (uint32_t)n_decode, (int32_t)pplan.backwards,    \
+                       pplan.base_slot, pplan.num_slots, pplan.cut_first_pos, pplan.max_ranges,                 \
+                       (float*)prefill_ws, (uint32_t)dec_first, (uint32_t)dec_wgs, (uint32_t)n_decode, (int32_t)pplan.backwards,    \
                        dplan.arg_items, part_o, part_ml);
 #define CS_LAUNCH_MIXED(DD, PRIO)                                                                            \
     if (pool.page_size == 16) { CS_LAUNCH_MIXED_P(DD, PRIO, 16) } else { CS_LAUNCH_MIXED_P(DD, PRIO, 8) }

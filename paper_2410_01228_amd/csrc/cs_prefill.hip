@@ -21,24 +21,29 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t g = blockIdx.x - pos * Hkv;
     const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos]
                                     : base_slot + (backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos);
+    // (with key ranges the grid has no order table: cut position = slot position)
     prefill_tile<D, E, true, PS, false>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
-                       q, out, scale_log2e, range_steps, base_slot, part, g, b, blockIdx.y, gridDim.y);
+                       q, out, scale_log2e, range_steps, partials_of<D>(part, b - base_slot, Hkv, g, gridDim.y), g, b,
+                       blockIdx.y);
 }
 
-// Merge of the key-range partials of the tiles that were cut: grid.x = Hkv * slots, grid.y =
-// kMergeParts row groups of a tile; one lane per (query row, 4 features), so a wavefront reads
-// whole 512-byte runs of a partial's rows.
+// Merge of the key-range partials of the tiles that were cut: grid.x = Hkv * cut tiles (launch
+// positions cut_first_pos .. num_slots-1, the same numbering as the kernel that wrote them),
+// grid.y = kMergeParts row groups of a tile; one lane per (query row, 4 features), so a
+// wavefront reads whole 512-byte runs of a partial's rows.
 constexpr int kMergeParts = 4;
 template <int D, class E>
 __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     int32_t Hkv, int32_t G, int32_t S, const int32_t* __restrict__ ctx_lens,
     const int32_t* __restrict__ cu_q_lens, uint16_t* __restrict__ out,
-    int32_t range_steps, int32_t max_ranges, int32_t base_slot, const float* __restrict__ part)
+    int32_t range_steps, int32_t max_ranges, int32_t base_slot, int32_t num_slots, int32_t cut_first_pos,
+    int32_t backwards, const float* __restrict__ part)
 {
     constexpr int kPartRow = D + 4;
     constexpr int kQuads = D / 4;                                  // lanes per query row
     constexpr int kRows = kTileCols * 16 / kMergeParts;            // rows of this workgroup
-    const int32_t g = blockIdx.x % Hkv, b = blockIdx.x / Hkv + base_slot;
+    const int32_t g = blockIdx.x % Hkv, cut_pos = blockIdx.x / Hkv, pos = cut_first_pos + cut_pos;
+    const int32_t b = base_slot + (backwards ? num_slots - 1 - pos : pos);
     int32_t lo = 0, hi = S;
     while (hi - lo > 1) {
         const int32_t mid = (lo + hi) >> 1;
@@ -56,7 +61,7 @@ __global__ __launch_bounds__(kPrefillThreads) void prefill_merge_kernel(
     const int32_t n_steps = (n_keys + kKeysPerStep - 1) / kKeysPerStep;
     const int32_t n_ranges = (n_steps + range_steps - 1) / range_steps;
     if (n_ranges <= 1) return;                               // written directly by the tile kernel
-    const float* tile = part + (((int64_t)(b - base_slot) * Hkv + g) * max_ranges) * (kTileCols * 16 * kPartRow);
+    const float* tile = partials_of<D>(const_cast<float*>(part), cut_pos, Hkv, g, max_ranges);
     const int64_t rstride = (int64_t)kTileCols * 16 * kPartRow;
     const int32_t Hq = Hkv * G;
     for (int32_t idx = threadIdx.x; idx < kRows * kQuads; idx += kPrefillThreads) {
@@ -93,15 +98,15 @@ static void launch_merge_as(const cs_kv_pool& pool, const cs_batch& b, const Pre
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const float* part = (const float*)workspace;
-    dim3 mgrid((uint32_t)Hkv * (uint32_t)plan.num_slots, kMergeParts);
+    dim3 mgrid((uint32_t)Hkv * (uint32_t)(plan.num_slots - plan.cut_first_pos), kMergeParts);
     if (D == 128)
         hipLaunchKernelGGL((prefill_merge_kernel<128, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
                            b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
-                           plan.base_slot, part);
+                           plan.base_slot, plan.num_slots, plan.cut_first_pos, (int32_t)plan.backwards, part);
     else
         hipLaunchKernelGGL((prefill_merge_kernel<64, E>), mgrid, dim3(kPrefillThreads), 0, st, Hkv, G, b.num_seqs,
                            b.ctx_lens, b.cu_q_lens, (uint16_t*)out, plan.range_steps, plan.max_ranges,
-                           plan.base_slot, part);
+                           plan.base_slot, plan.num_slots, plan.cut_first_pos, (int32_t)plan.backwards, part);
 }
 
 template <class E>

@@ -106,6 +106,15 @@ __device__ __forceinline__ float max8(const float (&x)[8]) {
 }
 
 
+// Floats of one key-range partial: kTileCols * 16 query rows of D outputs, max, sum and padding.
+template <int D> constexpr int64_t kPartialFloats = (int64_t)kTileCols * 16 * (D + 4);
+// The partials of the cut tile in cut position `cut_pos` (0 = the first cut tile in launch order),
+// kv head g: max_ranges partials in a row.
+template <int D>
+__device__ __forceinline__ float* partials_of(float* part, int32_t cut_pos, int32_t Hkv, int32_t g, int32_t max_ranges) {
+    return part + ((int64_t)cut_pos * Hkv + g) * max_ranges * kPartialFloats<D>;
+}
+
 // LDS of one prefill workgroup: the ring of K and of V steps.
 template <int D>
 struct PrefillLds {
@@ -113,9 +122,11 @@ struct PrefillLds {
     u32x4 v[kRing][4 * D];
 };
 
-// The work of one prefill workgroup: the tile in slot b, kv head g, key range `range` of
-// `n_ranges_grid` (a tile whose keys need more than range_steps steps is cut into ranges, each
-// leaving a partial).  `lds` is the workgroup's own.  kPhasePriority: the wavefront alternates
+// The work of one prefill workgroup: the tile in slot b, kv head g, key range `range` (a tile
+// whose keys need more than range_steps steps is cut into ranges, each leaving a partial in
+// part_tile[range], the caller's block of partials for this tile and kv head; range_steps at
+// least the tile's steps: the tile is whole and writes the output itself).  `lds` is the
+// workgroup's own.  kPhasePriority: the wavefront alternates
 // its issue priority between the halves of an iteration (for grids whose other wavefronts are
 // mostly tiles too; beside a decode load of equal weight it costs more than it gains).
 template <int D, class E, bool kPhasePriority, int PS, bool kLaneAddr16>
@@ -126,8 +137,8 @@ __device__ __forceinline__ void prefill_tile(
     const int32_t* __restrict__ block_tables, int32_t max_blocks,
     const int32_t* __restrict__ ctx_lens, const int32_t* __restrict__ cu_q_lens,
     const uint16_t* __restrict__ q, uint16_t* __restrict__ out, float scale_log2e,
-    int32_t range_steps, int32_t base_slot, float* __restrict__ part,
-    int32_t g, int32_t b, int32_t range, int32_t n_ranges_grid)
+    int32_t range_steps, float* __restrict__ part_tile,
+    int32_t g, int32_t b, int32_t range)
 {
     constexpr int kUnits = D * 2;                     // 16-byte units per K (or V) block of a page
     constexpr int kStepUnits = 2 * kUnits;            // K (or V) units of one step (two pages)
@@ -564,7 +575,8 @@ __device__ __forceinline__ void prefill_tile(
         }
     } else {
         // partial of this key range: unnormalised output, running max and sum per query row
-        float* wg = part + (((int64_t)(b - base_slot) * Hkv + g) * n_ranges_grid + range) * (kTileCols * 16 * kPartRow);
+        if (part_tile == nullptr) return;                 // (a cut tile always has a block: a planning error must not write)
+        float* wg = part_tile + (int64_t)range * (kTileCols * 16 * kPartRow);
 #pragma unroll
         for (int c = 0; c < kNCT; ++c) {
             float* row = wg + ((wave * kNCT + c) * 16 + (lane & 15)) * kPartRow;

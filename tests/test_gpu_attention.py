@@ -358,6 +358,32 @@ def test_decode_workgroups_that_walk_many_pairs(cus, split):
     assert_attention_close(o1, st.oracle_attention(), "decode beside the tiles, %d CUs, split %d" % (cus, split))
 
 
+@pytest.mark.parametrize("mode,whole,ranges,backwards_tiles", [(3, 3, 2, False), (3, 5, 3, False), (2, 2, 2, False),
+                                                               (3, 0, 2, False), (3, 1000, 4, False), (3, 9, 2, True)])
+def test_fused_grid_with_only_its_last_tiles_cut(mode, whole, ranges, backwards_tiles):
+    """In the fused grid the host may leave the first tiles of the launch order whole and cut only
+    those behind them into key ranges (the last round's, which would otherwise run alone on their
+    CUs).  Forced here at every kind of boundary: a cut that starts inside a chunk, after the last
+    tile (nothing cut), at the first (all cut), and in a grid walked backwards (more tiles than
+    workgroup slots on a small chip).  Whole tiles write their rows themselves, cut tiles through
+    their partials and the merge: every row must meet the oracle, whichever way it went."""
+    sh = synth.Shape(12, 4, 128)
+    ctx = [700, 2300, 1500, 15, 3100, 260, 4000]
+    ql = [1, 200, 1, 1, 130, 1, 96]
+    b = synth.make_batch(sh, ctx, ql, synth.generator(83), spare=3)
+    cs.cs_debug_set_tail_cut(whole, ranges)
+    if backwards_tiles:
+        cs.cs_debug_set_cu_count(2)
+    try:
+        out, st, _, bb = run_step(b, 83, fuse=mode)
+        n_slots, first_cut, n_ranges = cs.cs_debug_mixed_tail_cut(bb, sh.Hq, sh.Hkv, sh.D)
+        assert first_cut == min(whole, n_slots) and n_ranges == (ranges if whole < n_slots else 1)
+    finally:
+        cs.cs_debug_set_tail_cut(-1, 0)
+        cs.cs_debug_set_cu_count(0)
+    assert_attention_close(out, st.oracle_attention(), "tail cut: mode %d, whole %d, %d ranges" % (mode, whole, ranges))
+
+
 def test_prefill_many_short_chunks():
     """More workgroup slots than one grid dimension holds (60 000 sequences: two-token chunks and
     decode tokens interleaved): the slot index rides in grid.x together with the kv head."""
