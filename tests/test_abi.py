@@ -449,3 +449,45 @@ def test_mixed_batches_choose_where_the_decode_work_runs():
         lib.cs_debug_set_cu_count(0)
     b, keep = _batch([5], [1])
     assert lib.cs_debug_mixed_arrangement(ctypes.byref(b), 6, 4, 128) == cs.CS_ERR_INVALID_ARG
+
+
+def test_tiles_of_the_last_round_are_cut_beside_a_decode_load():
+    """Beside the decode workgroups a CU has one slot for tiles, so 512 equal tile workgroups run
+    as two rounds of 256, and the second round starts when the decode side is about done: the host
+    cuts exactly those tiles (launch positions 32..63 of 64 at 8 kv heads) in two, and the
+    workspace holds partials for the cut tiles only.  The knob forces other cuts or none."""
+    lib = cs.lib()
+    from paper_2410_01228_amd import synth
+    w = synth.config_llama70b_long()          # 128 decodes of 2K..32K keys beside a 1024-token chunk on 30K keys
+    b, keep = _batch(w.ctx_lens.tolist(), w.q_lens.tolist(), max_blocks=1 << 16)
+    first, ranges = ctypes.c_int32(-1), ctypes.c_int32(-1)
+
+    def cut():
+        n = lib.cs_debug_mixed_tail_cut(ctypes.byref(b), 64, 8, 128, ctypes.byref(first), ctypes.byref(ranges))
+        return n, first.value, ranges.value
+
+    block = 8 * 16 * 132 * 4                                   # one partial: 128 query rows of 128 + 4 floats
+    try:
+        lib.cs_debug_set_cu_count(256)
+        assert lib.cs_debug_mixed_arrangement(ctypes.byref(b), 64, 8, 128) == 2
+        n, f, r = cut()
+        assert 64 <= n <= 66 and f == 32 and r == 2
+        ws_cut = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128)
+        lib.cs_debug_set_tail_cut(-2, 0)                       # no cut by the model
+        assert cut()[1:] == (0, 1)
+        ws_whole = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128)
+        assert ws_cut - ws_whole == (n - 32) * 8 * 2 * block
+        lib.cs_debug_set_tail_cut(10, 3)
+        assert cut()[1:] == (10, 3)
+        assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128) - ws_whole == (n - 10) * 8 * 3 * block
+        lib.cs_debug_set_tail_cut(1000, 3)                     # behind the last tile: nothing is cut
+        assert cut()[1:] == (n, 1)
+        lib.cs_debug_set_tail_cut(-1, 0)
+        assert cut()[1:] == (32, 2)
+        # behind the tiles nothing of the kind happens
+        lib.cs_set_mixed_fusion(2)
+        assert cut()[1:] == (0, 1)
+    finally:
+        lib.cs_set_mixed_fusion(1)
+        lib.cs_debug_set_tail_cut(-1, 0)
+        lib.cs_debug_set_cu_count(0)
