@@ -320,7 +320,10 @@ struct FusePlan {
 // kSoloTile of that while the CU's other slot is empty and kBesideDecode of it beside a decode
 // workgroup.  The dispatcher gives the first `cus` workgroups a CU each, the next `cus` the
 // second slot of those CUs, and every later one the slot that frees first.  decode_until > 0:
-// slot 0 of every CU is a decode workgroup's until then.  Returns when the last tile ends;
+// slot 0 of every CU is a decode workgroup's until then.  (The caller plays TILES, not
+// workgroups: the workgroups of a tile's kv heads are equally long and start together, so a tile
+// is one unit on a group of num_kv_heads CUs, and a long grid costs the host an eighth of the
+// events.)  Returns when the last tile ends;
 // free_at (two entries per CU) receives when each slot was last released, started (optional)
 // when each workgroup began.
 constexpr double kSoloTile = 0.78, kBesideDecode = 1.1;
@@ -438,13 +441,17 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
     // and beside wins on some mixes and loses on others: the choice there is not modelled)
     if (mode == 2 || (mode == 1 && D != 128)) return f;
     bool beside = mode == 3;
-    const int64_t tile_wgs = (int64_t)p.num_slots * Hkv * p.max_ranges;
+    const int64_t tile_units = (int64_t)p.num_slots * p.max_ranges;       // tiles x ranges: what the model plays
+    const int32_t groups = std::max(1, cus / Hkv);                         // CU groups of one CU per kv head
     const double us_per_step = 0.88, t_dec = decode_bytes / 6.5e6;      // microseconds
     // (a decode side under 0.3 of the prefill side stays behind tiles that alternate their
     // priority: measured 5-8% better than beside on such mixes, which the model calls even)
     if ((mode == 1 && !f.prio) || mode == 3) {
-        if (tile_wgs > 65536) {
-            beside = beside || t_decode >= 0.05 * t_prefill;     // many rounds of tiles: beside always overlaps
+        if (tile_units > 8192) {
+            // more than 16 rounds of tiles: how the rounds end no longer matters, and beside wins
+            // wherever the decode side is at least half the prefill side (mixes of 2-4 rounds:
+            // beside from about 0.45 on)
+            beside = beside || t_decode >= 0.5 * t_prefill;
         } else {
             // steps of every tile slot, then the workgroups in the fused grid's launch order
             std::vector<int32_t> slot_steps((size_t)p.num_slots, 0);
@@ -469,40 +476,41 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
                 pos_of.clear();
                 for (int32_t pos = 0; pos < whole; ++pos)
                     if (steps_at(pos) > 0) {
-                        work.insert(work.end(), (size_t)Hkv, (float)((steps_at(pos) + 8) * us_per_step));
-                        pos_of.insert(pos_of.end(), (size_t)Hkv, pos);
+                        work.push_back((float)((steps_at(pos) + 8) * us_per_step));
+                        pos_of.push_back(pos);
                     }
                 for (int32_t r = 0; r < ranges; ++r)
                     for (int32_t pos = whole; pos < p.num_slots; ++pos) {
                         const int32_t n = std::min(steps_at(pos), (r + 1) * range_steps) - r * range_steps;
                         if (n > 0) {
-                            work.insert(work.end(), (size_t)Hkv, (float)((n + 8) * us_per_step));
-                            pos_of.insert(pos_of.end(), (size_t)Hkv, pos);
+                            work.push_back((float)((n + 8) * us_per_step));
+                            pos_of.push_back(pos);
                         }
                     }
             };
             list_work(0, p.range_steps, p.max_ranges);
             std::vector<double> free_at;
             std::vector<float> started;
+            double t_whole = 0;                                  // beside, as planned so far
             if (mode == 1) {
-                play_tiles(work, cus, 0.0, free_at);
+                play_tiles(work, groups, 0.0, free_at);
                 std::sort(free_at.begin(), free_at.end());
                 double t = 0, left = t_dec, t_behind = 0;
-                const double sat = 1.56 * cus;
+                const double sat = 1.56 * groups;
                 for (size_t i = 0; ; ++i) {
-                    const double rate = std::min(1.0, (double)i / sat);          // i slots are free
+                    const double rate = std::min(1.0, (double)i / sat);          // i slots (of every CU of a group) are free
                     const double next = i < free_at.size() ? free_at[i] : 1.0e300;
                     if (rate > 0 && t + left / rate <= next) { t_behind = t + left / rate; break; }
                     left -= rate * (next - t);
                     t = next;
                 }
-                const double t_beside = std::max(play_tiles(work, cus, t_dec, free_at, &started), t_dec);
-                beside = t_beside < t_behind;
+                t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
+                beside = t_whole < t_behind;
             }
             if (beside && p.max_ranges == 1 && !work.empty() && g_forced_tail_whole.load() != -2) {
                 // the tiles of the last round, cut: from the first tile that starts when the
                 // decode side is at least 0.85 done
-                const double t_whole = std::max(play_tiles(work, cus, t_dec, free_at, &started), t_dec);
+                if (mode != 1) t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
                 size_t first = 0;
                 while (first < work.size() && started[first] < 0.85 * t_dec) ++first;
                 if (first > 0 && first < work.size()) {
@@ -514,7 +522,7 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
                         const int32_t rs = (tail_steps + r - 1) / r, ranges = (tail_steps + rs - 1) / rs;
                         list_work(whole, rs, ranges);
                         const double part_bytes = (double)(p.num_slots - whole) * Hkv * ranges * kTileCols * 16 * (D + 4) * 4.0;
-                        const double t_cut = std::max(play_tiles(work, cus, t_dec, free_at), t_dec) + 10.0 + 2.0 * part_bytes / 5.0e6;
+                        const double t_cut = std::max(play_tiles(work, groups, t_dec, free_at), t_dec) + 10.0 + 2.0 * part_bytes / 5.0e6;
                         if (t_cut < best) {
                             best = t_cut;
                             p.cut_first_pos = whole;
