@@ -318,14 +318,15 @@ struct FusePlan {
 // The tile workgroups of a fused grid played through the chip's workgroup slots (two per CU), in
 // microseconds.  work[i]: what workgroup i takes while another tile shares its CU; it runs
 // kSoloTile of that while the CU's other slot is empty and kBesideDecode of it beside a decode
-// workgroup.  The dispatcher gives the first `cus` workgroups a CU each, the next `cus` the
-// second slot of those CUs, and every later one the slot that frees first.  decode_until > 0:
-// slot 0 of every CU is a decode workgroup's until then.  (The caller plays TILES, not
-// workgroups: the workgroups of a tile's kv heads are equally long and start together, so a tile
-// is one unit on a group of num_kv_heads CUs, and a long grid costs the host an eighth of the
-// events.)  Returns when the last tile ends;
-// free_at (two entries per CU) receives when each slot was last released, started (optional)
-// when each workgroup began.
+// workgroup (fitted to the arrangements' measured order over many mixes, not to timelines: by
+// those a tile beside a decode workgroup takes 1.3-1.4 of its paired time).  The dispatcher
+// gives the first `cus` workgroups a CU each, the next `cus` the second slot of those CUs, and
+// every later one the slot that frees first.  decode_until > 0: slot 0 of every CU is a decode
+// workgroup's until then.  (The caller plays TILES, not workgroups: the workgroups of a tile's
+// kv heads are equally long and start together, so a tile is one unit on a group of
+// num_kv_heads CUs, and a long grid costs the host an eighth of the events.)  Returns when the
+// last tile ends; free_at (two entries per CU) receives when each slot was last released,
+// started (optional) when each workgroup began.
 constexpr double kSoloTile = 0.78, kBesideDecode = 1.1;
 static double play_tiles(const std::vector<float>& work, int32_t cus, double decode_until, std::vector<double>& free_at,
                          std::vector<float>* started = nullptr) {
@@ -404,10 +405,10 @@ static double play_tiles(const std::vector<float>& work, int32_t cus, double dec
 // workgroup of n steps takes (n + 8) * 0.88 us (a 32-key step at head dim 128 beside another
 // tile).  Behind: the decode bytes flow at 6.5 TB/s times min(1, free slots / (1.56 CUs)) into
 // the slots the tiles have left for good.  Beside: one slot per CU is a decode workgroup's until
-// all bytes have passed at 6.5 TB/s.  Over 72 mixes of two model shapes, taking the faster of the
-// two by this model is on average 0.3% slower than taking the faster by measurement (always
-// behind: 5.0%, always beside: 3.0%); the merges of cut tiles and cut sequences cost the same
-// either way.
+// all bytes have passed at 6.5 TB/s.  Over 196 mixes of four model shapes, the arrangement this
+// model takes is on average 0.0-0.7% (per shape) slower than the fastest of the three by
+// measurement, 8% at worst (always behind: 3-8% on average, always beside: 2-6%); the merges of
+// cut tiles and cut sequences cost the same either way.
 //
 // Beside the tiles, the tiles of the last round are cut (p is changed): a tile that starts when
 // the decode side is about done runs alone on its CU, one wavefront per SIMD, while the slot the
