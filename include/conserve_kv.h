@@ -407,6 +407,14 @@ int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t num_q_heads, i
 int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
                                 int32_t* first_cut, int32_t* ranges);
 
+/* The host's model of a fused grid's tile workgroups, for tests (no device work): n workgroups
+ * that take work_us[i] microseconds each beside another tile, 0.78 of that alone on their CU
+ * and 1.1 of it beside a decode workgroup, are played in order through `cus` CUs of two
+ * workgroup slots each (the first `cus` get a CU each, the next `cus` the second slot of those
+ * CUs, later ones the slot that frees first); with decode_until_us > 0 one slot of every CU is a
+ * decode workgroup's until then.  Returns when the last workgroup ends, or -1 on bad arguments. */
+double cs_debug_play_tiles(const float* work_us, int32_t n, int32_t cus, double decode_until_us);
+
 /* Tuning knob for measurements and tests: in a fused mixed launch, leave the tiles of the launch
  * positions before `whole_tiles` whole and cut those from it on into `ranges` key ranges (of the
  * longest tile's steps / ranges), whatever the host's model says; whole_tiles < 0 or ranges < 1:

@@ -128,6 +128,8 @@ def lib():
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
         L.cs_debug_mixed_arrangement.restype, L.cs_debug_mixed_arrangement.argtypes = i32, [BP, i32, i32, i32]
         L.cs_debug_set_tail_cut.restype, L.cs_debug_set_tail_cut.argtypes = None, [i32, i32]
+        L.cs_debug_play_tiles.restype = ctypes.c_double
+        L.cs_debug_play_tiles.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, ctypes.c_double]
         L.cs_debug_mixed_tail_cut.restype = i32
         L.cs_debug_mixed_tail_cut.argtypes = [BP, i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.cs_set_decode_pages_ahead.restype, L.cs_set_decode_pages_ahead.argtypes = None, [i32]
@@ -149,7 +151,7 @@ EXPORTS = [
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
     "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_run_layers_workspace_bytes", "cs_debug_set_cu_count", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
-    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_debug_mixed_tail_cut", "cs_debug_set_tail_cut", "cs_status_string", "cs_last_hip_error",
+    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_debug_mixed_tail_cut", "cs_debug_set_tail_cut", "cs_debug_play_tiles", "cs_status_string", "cs_last_hip_error",
 ]
 
 
@@ -472,6 +474,13 @@ def cs_debug_mixed_arrangement(batch: "Batch", Hq: int, Hkv: int, D: int) -> int
     if rc < 0:
         raise CsError(rc, "cs_debug_mixed_arrangement")
     return rc
+
+
+def cs_debug_play_tiles(work_us, cus: int, decode_until_us: float = 0.0) -> float:
+    """When the last of the tile workgroups (work_us: microseconds each, beside another tile) ends
+    in the host's slot model -- host only."""
+    arr = (ctypes.c_float * len(work_us))(*work_us)
+    return lib().cs_debug_play_tiles(arr, len(work_us), int(cus), float(decode_until_us))
 
 
 def cs_debug_set_tail_cut(whole_tiles: int, ranges: int):

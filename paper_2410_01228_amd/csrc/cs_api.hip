@@ -974,6 +974,13 @@ int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t Hq, int32_t Hkv, 
     return p.num_slots;
 }
 
+double cs_debug_play_tiles(const float* work_us, int32_t n, int32_t cus, double decode_until_us) {
+    if (!work_us || n < 0 || cus <= 0) return -1.0;
+    std::vector<float> work(work_us, work_us + n);
+    std::vector<double> free_at;
+    return play_tiles(work, cus, decode_until_us, free_at);
+}
+
 void cs_debug_set_tail_cut(int32_t whole_tiles, int32_t ranges) {
     g_forced_tail_whole.store(whole_tiles >= 0 && ranges >= 1 ? whole_tiles : whole_tiles == -2 ? -2 : -1);   // (-2: no cut by the model either)
     g_forced_tail_ranges.store(whole_tiles >= 0 && ranges >= 1 ? ranges : 0);

@@ -491,3 +491,42 @@ def test_tiles_of_the_last_round_are_cut_beside_a_decode_load():
         lib.cs_set_mixed_fusion(1)
         lib.cs_debug_set_tail_cut(-1, 0)
         lib.cs_debug_set_cu_count(0)
+
+
+def test_slot_model_of_the_fused_grid():
+    """The model the host chooses a mixed batch's arrangement by, on cases worked out by hand
+    (times in microseconds; a tile alone on its CU takes 0.78 of its paired time, beside a decode
+    workgroup 1.1 of it)."""
+    play = cs.cs_debug_play_tiles
+    close = lambda a, b: abs(a - b) <= 1e-3 * max(1.0, abs(b))
+    assert play([], 4) == 0.0
+    assert close(play([100.0], 4), 78.0)                              # one tile, a CU to itself
+    assert close(play([100.0] * 4, 4), 78.0)                          # one per CU
+    assert close(play([100.0] * 8, 4), 100.0)                         # two per CU, paired all the way
+    # five tiles on four CUs: CU 0 holds two (paired, 100), the others one each (78)
+    assert close(play([100.0] * 5, 4), 100.0)
+    # a short partner: 40 us paired, then the long tile is alone: 40 + 60 * 0.78
+    assert close(play([100.0, 40.0], 1), 40.0 + 60.0 * 0.78)
+    # three tiles on one CU: 100 and 40 paired for 40, then 100' moves in beside the first (60 left, paired):
+    # the first ends at 100, the third has 40 left and is alone: 100 + 40 * 0.78
+    assert close(play([100.0, 40.0, 100.0], 1), 100.0 + 40.0 * 0.78)
+    # beside a decode workgroup that stays 50 us: 50 / 1.1 done, the rest alone at 0.78
+    assert close(play([100.0], 1, 50.0), 50.0 + (100.0 - 50.0 / 1.1) * 0.78)
+    # ... that outlasts the tile: 110
+    assert close(play([100.0], 1, 500.0), 110.0)
+    # two tiles, one slot until the decode side leaves at 110: the first ends at 110, the second runs alone
+    assert close(play([100.0, 100.0], 1, 110.0), 110.0 + 78.0)
+    # the decode side leaves while the first tile runs: the second moves in beside it
+    t = play([100.0, 100.0], 1, 55.0)                                   # first: 50 done at 55, 50 left paired -> 105
+    assert close(t, 105.0 + 50.0 * 0.78)                                # second: 50 done at 105, 50 left alone
+    # work is conserved: never faster than every slot busy at the best rate, never slower than one slot at the worst
+    import random
+    rnd = random.Random(3)
+    for _ in range(50):
+        cus = rnd.choice([1, 2, 7, 32])
+        work = [rnd.uniform(5, 300) for _ in range(rnd.randint(1, 200))]
+        dec = rnd.choice([0.0, rnd.uniform(1, 2000)])
+        t = play(work, cus, dec)
+        assert t >= max(work) * 0.78 * (1 - 1e-5) and t >= sum(work) / (2 * cus) * 0.78 * (1 - 1e-5)
+        assert t <= (dec + sum(work) * 1.1 / cus + max(work) * 1.1) * (1 + 1e-5)
+    assert play([1.0], 0) == -1.0 and cs.lib().cs_debug_play_tiles(None, 1, 4, 0.0) == -1.0
