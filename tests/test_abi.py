@@ -493,6 +493,47 @@ def test_tiles_of_the_last_round_are_cut_beside_a_decode_load():
         lib.cs_debug_set_cu_count(0)
 
 
+def test_every_cut_the_host_plans_fits_the_workspace_it_asks_for():
+    """The tile workgroups trust the launch plan: a cut tile in launch position p writes its range's
+    partial into block ((p - first_cut) * kv heads + kv head) * ranges + range of the workspace.
+    Over random mixed batches, model shapes, CU counts, arrangements and forced cuts, the positions
+    that are cut lie inside the launch and the workspace the host asks for holds every such block
+    (Sec. 4.2: chunks of any length beside decode tokens)."""
+    lib = cs.lib()
+    import random
+    rnd = random.Random(20)
+    first, ranges = ctypes.c_int32(-1), ctypes.c_int32(-1)
+    checked = cuts = 0
+    try:
+        for trial in range(60):
+            Hq, Hkv = rnd.choice(((64, 8), (28, 4), (40, 8), (32, 8)))
+            n_pre, n_dec = rnd.randint(1, 6), rnd.randint(1, 200)
+            ctx = [rnd.randint(0, 40000) for _ in range(n_pre)] + [rnd.randint(1, 33000) for _ in range(n_dec)]
+            ql = [rnd.choice((17, 256, 512, 1024, 2048)) for _ in range(n_pre)] + [1] * n_dec
+            order = list(range(len(ctx)))
+            rnd.shuffle(order)
+            b, keep = _batch([ctx[i] for i in order], [ql[i] for i in order], max_blocks=1 << 16)
+            lib.cs_debug_set_cu_count(rnd.choice((8, 64, 256, 304)))
+            for mode in (1, 2, 3):
+                lib.cs_set_mixed_fusion(mode)
+                for knob in ((-1, 0), (rnd.randint(0, 40), rnd.randint(2, 3)), (0, 2), (10 ** 6, 3)):
+                    lib.cs_debug_set_tail_cut(*knob)
+                    n = lib.cs_debug_mixed_tail_cut(ctypes.byref(b), Hq, Hkv, 128, ctypes.byref(first), ctypes.byref(ranges))
+                    ws = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), Hq, Hkv, 128)
+                    assert n >= 1 and 0 <= first.value <= n and 1 <= ranges.value, (trial, mode, knob, n, first.value, ranges.value)
+                    assert ws >= 0
+                    if ranges.value > 1:
+                        blocks = (n - first.value) * Hkv * ranges.value
+                        assert blocks > 0 and ws >= blocks * 8 * 16 * 132 * 4, (trial, mode, knob, n, first.value, ranges.value, ws)
+                        cuts += 1
+                    checked += 1
+    finally:
+        lib.cs_set_mixed_fusion(1)
+        lib.cs_debug_set_tail_cut(-1, 0)
+        lib.cs_debug_set_cu_count(0)
+    assert checked == 60 * 12 and cuts > 100, (checked, cuts)
+
+
 def test_slot_model_of_the_fused_grid():
     """The model the host chooses a mixed batch's arrangement by, on cases worked out by hand
     (times in microseconds; a tile alone on its CU takes 0.78 of its paired time, beside a decode
