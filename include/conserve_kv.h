@@ -402,8 +402,8 @@ int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t num_q_heads, i
  * of tile slots in launch order (a slot is 8 column tiles of 16 query rows of one kv head group;
  * slots of sequences without a chunk are empty), *first_cut the launch position from which tiles
  * are cut (0: every tile that is long enough; beside the tiles the host cuts only the last
- * round's), *ranges the ranges of the longest cut tile (1: nothing is cut).  CS_ERR_INVALID_ARG
- * on bad arguments.  No device work. */
+ * round's), *ranges the ranges of the longest cut tile (1: nothing is cut; a batch without chunks
+ * has 0 slots and 1 range).  CS_ERR_INVALID_ARG on bad arguments.  No device work. */
 int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim,
                                 int32_t* first_cut, int32_t* ranges);
 

@@ -970,7 +970,7 @@ int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t Hq, int32_t Hkv, 
     if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return CS_ERR_INVALID_ARG;
     const PrefillPlan& p = plans_for(batch, Hq, Hkv, D).p;
     if (first_cut) *first_cut = p.cut_first_pos;
-    if (ranges) *ranges = p.max_ranges;
+    if (ranges) *ranges = p.max_ranges > 0 ? p.max_ranges : 1;     // (a batch without chunks has no plan: 0 slots, nothing cut)
     return p.num_slots;
 }
 

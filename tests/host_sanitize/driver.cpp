@@ -4,6 +4,7 @@
 // Prints "ok <count>" and exits 0; any sanitizer report makes the process exit non-zero.
 #include <cstdint>
 #include <cstdio>
+#include <algorithm>
 #include <cstdlib>
 #include <random>
 #include <vector>
@@ -45,6 +46,10 @@ int main() {
         }
         cs_batch b = make_batch(ctx, cu, max_need);
         cs_debug_set_cu_count(round % 3 == 0 ? 0 : round % 3 == 1 ? 128 : 512);
+        // where a mixed batch's decode work runs, and forced cuts of the last tiles, change the plan
+        cs_set_mixed_fusion((int32_t)(rng() % 4));
+        if (round % 4 == 1) cs_debug_set_tail_cut((int32_t)(rng() % 50), 2 + (int32_t)(rng() % 2));
+        else cs_debug_set_tail_cut(-1, 0);
         const size_t need = cs_paged_attention_workspace_bytes(&b, sh[0], sh[1], sh[2]);
         CHECK(cs_paged_attention_workspace_bytes(&b, sh[0], sh[1], sh[2]) == need);      // remembered, same answer
         int32_t split = 0;
@@ -55,6 +60,13 @@ int main() {
         CHECK(ahead == 1 || ahead == 2);
         const int32_t n_ord = cs_debug_prefill_order(&b, sh[0], sh[1], sh[2], order.data(), (int32_t)order.size());
         CHECK(n_ord >= 0 && n_ord <= 512);
+        int32_t first_cut = -1, ranges = -1;
+        const int32_t n_slots = cs_debug_mixed_tail_cut(&b, sh[0], sh[1], sh[2], &first_cut, &ranges);
+        CHECK(n_slots == CS_ERR_INVALID_ARG || (n_slots >= 0 && first_cut >= 0 && first_cut <= n_slots && ranges >= 1));
+        if (n_slots > 0 && ranges > 1)
+            CHECK(need >= (size_t)(n_slots - first_cut) * sh[1] * ranges * (8 * 16 * (sh[2] + 4) * sizeof(float)));
+        const int32_t arrangement = cs_debug_mixed_arrangement(&b, sh[0], sh[1], sh[2]);
+        CHECK(arrangement == CS_ERR_INVALID_ARG || (arrangement >= 0 && arrangement <= 2));
         const int32_t n_on = (int32_t)(rng() % (S + 1));
         CHECK(cs_run_layers_workspace_bytes(&b, n_on, sh[0], sh[1], sh[2]) >= need);
         // the attention call itself with a workspace one byte short: refused on the host
@@ -69,6 +81,20 @@ int main() {
         checks += 8;
     }
     cs_debug_set_cu_count(0);
+    cs_set_mixed_fusion(1);
+    cs_debug_set_tail_cut(-1, 0);
+    // ---- the slot model of the fused grid: any work list ends, no earlier than its longest piece alone ----
+    for (int round = 0; round < 200; ++round) {
+        const int32_t n = 1 + (int32_t)(rng() % 700), cus = 1 + (int32_t)(rng() % 300);
+        std::vector<float> work(n);
+        float longest = 0.f;
+        for (auto& w : work) { w = (float)(rng() % 100000) * 0.01f; longest = std::max(longest, w); }
+        const double until = rng() % 2 ? 0.0 : (double)(rng() % 2000);
+        const double end = cs_debug_play_tiles(work.data(), n, cus, until);
+        CHECK(end >= 0.78 * longest - 1e-3);
+        CHECK(cs_debug_play_tiles(work.data(), n, 0, until) == -1.0);
+        ++checks;
+    }
     // ---- the page map against a plain model ----
     const int32_t G = 500, H = 300;
     cs_page_map* m = cs_page_map_create(G, H);
