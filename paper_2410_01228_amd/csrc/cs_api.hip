@@ -311,7 +311,7 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
 // always beside).
 struct FusePlan {
     int32_t arrangement;       // 0 two kernels, 1 decode behind the tiles, 2 decode beside the tiles
-    bool prio;                 // tiles alternate their issue priority (decode side small)
+    bool prio;                 // tiles alternate their issue priority (beside; behind when the decode side is small)
     int32_t persistent_wgs;    // arrangement 2: decode workgroups (one per CU)
 };
 
@@ -433,8 +433,8 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
     // Behind the tiles, unless the prefill side is a sliver: with a small chunk beside a long
     // decode (decode time over ten times the prefill time) two kernels in a row are as fast or a
     // little faster.  Where the decode side is the smaller one (under 0.3 of the prefill time)
-    // the tiles alternate their issue priority as the prefill kernel's do; beside a decode load
-    // of equal weight that costs more than it gains.
+    // the tiles alternate their issue priority as the prefill kernel's do; with a decode load of
+    // equal weight behind them that costs more than it gains.
     f.arrangement = (mode == 2 || t_decode <= 10.0 * t_prefill) ? 1 : 0;
     f.prio = t_decode < 0.3 * t_prefill;
     const int32_t cus = device_cus();
@@ -537,8 +537,11 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
         }
     }
     if (beside) {
+        // (beside, the tiles alternate their priority whatever the weights: two tiles share a CU
+        // once its decode workgroup is done, and until then it costs nothing -- measured -1.5% on
+        // average over 196 mixes of four model shapes, -4% with chunks on 30K keys, +3% at worst)
         f.arrangement = 2;
-        f.prio = false;
+        f.prio = true;
         f.persistent_wgs = cus;
     }
     return f;

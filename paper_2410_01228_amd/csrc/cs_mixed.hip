@@ -12,7 +12,7 @@
 //    not hold a slot per CU while the tiles need both.
 // Both kinds of workgroup have 4 wavefronts and share one LDS allocation (a union of the two
 // layouts), so two of them fit a CU in any combination.  kPhasePriority (see prefill_tile) is
-// set by the host when the decode side is the small one.
+// set by the host beside the tiles, and behind them when the decode side is the small one.
 #include "cs_prefill_impl.h"
 #include "cs_decode_impl.h"
 

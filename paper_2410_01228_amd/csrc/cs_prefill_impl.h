@@ -128,7 +128,8 @@ struct PrefillLds {
 // least the tile's steps: the tile is whole and writes the output itself).  `lds` is the
 // workgroup's own.  kPhasePriority: the wavefront alternates
 // its issue priority between the halves of an iteration (for grids whose other wavefronts are
-// mostly tiles too; beside a decode load of equal weight it costs more than it gains).
+// mostly tiles too, or become so once a decode workgroup per CU is done; with decode work of
+// equal weight queued behind the tiles it costs more than it gains).
 template <int D, class E, bool kPhasePriority, int PS, bool kLaneAddr16>
 __device__ __forceinline__ void prefill_tile(
     PrefillLds<D>& lds,
