@@ -398,6 +398,14 @@ void cs_set_mixed_fusion(int32_t mode);
  * arguments.  No device work. */
 int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
 
+/* Host-only view of one more choice of a fused launch, for tests: the higher of the two issue
+ * priorities its tile wavefronts alternate between -- 0: they stay at the default (also when the
+ * call is not fused); 1: beside a decode workgroup per CU, and behind tiles that far outweigh the
+ * decode work; 2 (always above the decode wavefronts, which stay at 0): beside, where the host's
+ * model has the tiles outlast the decode stream by less than 0.8 of its length.
+ * CS_ERR_INVALID_ARG on bad arguments.  No device work. */
+int32_t cs_debug_mixed_tile_priority(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
+
 /* Host-only view of the key-range cut of the batch's prefill tiles, for tests: returns the number
  * of tile slots in launch order (a slot is 8 column tiles of 16 query rows of one kv head group;
  * slots of sequences without a chunk are empty), *first_cut the launch position from which tiles

@@ -127,6 +127,7 @@ def lib():
         L.cs_set_decode_split_tokens.restype, L.cs_set_decode_split_tokens.argtypes = None, [i32]
         L.cs_set_mixed_fusion.restype, L.cs_set_mixed_fusion.argtypes = None, [i32]
         L.cs_debug_mixed_arrangement.restype, L.cs_debug_mixed_arrangement.argtypes = i32, [BP, i32, i32, i32]
+        L.cs_debug_mixed_tile_priority.restype, L.cs_debug_mixed_tile_priority.argtypes = i32, [BP, i32, i32, i32]
         L.cs_debug_set_tail_cut.restype, L.cs_debug_set_tail_cut.argtypes = None, [i32, i32]
         L.cs_debug_play_tiles.restype = ctypes.c_double
         L.cs_debug_play_tiles.argtypes = [ctypes.POINTER(ctypes.c_float), i32, i32, ctypes.c_double]
@@ -151,7 +152,7 @@ EXPORTS = [
     "cs_kv_ckpt_load", "cs_kv_ckpt_save_run", "cs_kv_ckpt_load_run", "cs_page_map_create", "cs_page_map_destroy",
     "cs_page_map_host_of", "cs_page_map_gpu_of", "cs_page_map_free_host_pages", "cs_page_map_checkpoint",
     "cs_page_map_evict", "cs_page_map_bind", "cs_page_map_drop", "cs_run_layers", "cs_run_layers_f16", "cs_run_layers_workspace_bytes", "cs_debug_set_cu_count", "cs_debug_copy", "cs_debug_decode_items", "cs_debug_decode_pages_ahead", "cs_debug_prefill_order",
-    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_debug_mixed_tail_cut", "cs_debug_set_tail_cut", "cs_debug_play_tiles", "cs_status_string", "cs_last_hip_error",
+    "cs_set_decode_split_tokens", "cs_set_decode_pages_ahead", "cs_set_mixed_fusion", "cs_debug_mixed_arrangement", "cs_debug_mixed_tile_priority", "cs_debug_mixed_tail_cut", "cs_debug_set_tail_cut", "cs_debug_play_tiles", "cs_status_string", "cs_last_hip_error",
 ]
 
 
@@ -473,6 +474,14 @@ def cs_debug_mixed_arrangement(batch: "Batch", Hq: int, Hkv: int, D: int) -> int
     rc = lib().cs_debug_mixed_arrangement(ctypes.byref(batch.c), Hq, Hkv, D)
     if rc < 0:
         raise CsError(rc, "cs_debug_mixed_arrangement")
+    return rc
+
+
+def cs_debug_mixed_tile_priority(batch: "Batch", Hq: int, Hkv: int, D: int) -> int:
+    """The higher of the two issue priorities a fused launch's tile wavefronts alternate between (0: none) -- host only."""
+    rc = lib().cs_debug_mixed_tile_priority(ctypes.byref(batch.c), Hq, Hkv, D)
+    if rc < 0:
+        raise CsError(rc, "cs_debug_mixed_tile_priority")
     return rc
 
 

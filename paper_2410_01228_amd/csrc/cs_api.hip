@@ -311,7 +311,7 @@ PrefillPlan plan_prefill(const cs_batch* b, int32_t Hq, int32_t Hkv, int32_t D) 
 // always beside).
 struct FusePlan {
     int32_t arrangement;       // 0 two kernels, 1 decode behind the tiles, 2 decode beside the tiles
-    bool prio;                 // tiles alternate their issue priority (beside; behind when the decode side is small)
+    int32_t prio;              // 0, or the higher of the two issue priorities the tiles alternate between (1, 2)
     int32_t persistent_wgs;    // arrangement 2: decode workgroups (one per CU)
 };
 
@@ -436,12 +436,13 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
     // the tiles alternate their issue priority as the prefill kernel's do; with a decode load of
     // equal weight behind them that costs more than it gains.
     f.arrangement = (mode == 2 || t_decode <= 10.0 * t_prefill) ? 1 : 0;
-    f.prio = t_decode < 0.3 * t_prefill;
+    f.prio = t_decode < 0.3 * t_prefill ? 1 : 0;
     const int32_t cus = device_cus();
     // (head dim 64 fits three workgroups per CU, both kinds already share CUs behind the tiles,
     // and beside wins on some mixes and loses on others: the choice there is not modelled)
     if (mode == 2 || (mode == 1 && D != 128)) return f;
     bool beside = mode == 3;
+    double t_beside = 0;                                               // the model's time of that arrangement as planned (0: not played)
     const int64_t tile_units = (int64_t)p.num_slots * p.max_ranges;       // tiles x ranges: what the model plays
     const int32_t groups = std::max(1, cus / Hkv);                         // CU groups of one CU per kv head
     const double us_per_step = 0.88, t_dec = decode_bytes / 6.5e6;      // microseconds
@@ -508,10 +509,11 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
                 t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
                 beside = t_whole < t_behind;
             }
+            if (beside && mode != 1 && !work.empty()) t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
+            t_beside = t_whole;
             if (beside && p.max_ranges == 1 && !work.empty() && g_forced_tail_whole.load() != -2) {
                 // the tiles of the last round, cut: from the first tile that starts when the
                 // decode side is at least 0.85 done
-                if (mode != 1) t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
                 size_t first = 0;
                 while (first < work.size() && started[first] < 0.85 * t_dec) ++first;
                 if (first > 0 && first < work.size()) {
@@ -526,6 +528,7 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
                         const double t_cut = std::max(play_tiles(work, groups, t_dec, free_at), t_dec) + 10.0 + 2.0 * part_bytes / 5.0e6;
                         if (t_cut < best) {
                             best = t_cut;
+                            t_beside = t_cut;
                             p.cut_first_pos = whole;
                             p.range_steps = rs;
                             p.max_ranges = ranges;
@@ -537,11 +540,16 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
         }
     }
     if (beside) {
-        // (beside, the tiles alternate their priority whatever the weights: two tiles share a CU
-        // once its decode workgroup is done, and until then it costs nothing -- measured -1.5% on
-        // average over 196 mixes of four model shapes, -4% with chunks on 30K keys, +3% at worst)
+        // Beside, the tiles alternate their priority whatever the weights: two tiles share a CU
+        // once its decode workgroup is done, and until then it costs nothing (measured -1.5% on
+        // average over 196 mixes of four model shapes, -4% with chunks on 30K keys, +3% at worst).
+        // Where the model has the tiles outlast the decode stream, but by less than 0.8 of its
+        // length, both of their priorities lie above the decode wavefronts': over 256 mixes that
+        // is worth 3-5% on average in that band (12% at best, 3% lost at worst) and costs 2-3%
+        // on either side of it -- a stream that ends last must not be held up, and beside a
+        // short one the tiles mostly share their CUs with each other.
         f.arrangement = 2;
-        f.prio = true;
+        f.prio = t_beside > t_dec && t_beside < 1.8 * t_dec ? 2 : 1;
         f.persistent_wgs = cus;
     }
     return f;
@@ -966,6 +974,13 @@ int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t Hq, int32_t Hk
     if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return CS_ERR_INVALID_ARG;
     if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return CS_ERR_INVALID_ARG;
     return plans_for(batch, Hq, Hkv, D).f.arrangement;
+}
+
+int32_t cs_debug_mixed_tile_priority(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D) {
+    if (attention_shape_ok(Hq, Hkv, D) != CS_OK) return CS_ERR_INVALID_ARG;
+    if (validate_batch(nullptr, batch) != CS_OK || batch->num_seqs == 0) return CS_ERR_INVALID_ARG;
+    const Plans& plans = plans_for(batch, Hq, Hkv, D);
+    return plans.f.arrangement == 0 ? 0 : plans.f.prio;
 }
 
 int32_t cs_debug_mixed_tail_cut(const cs_batch* batch, int32_t Hq, int32_t Hkv, int32_t D, int32_t* first_cut, int32_t* ranges) {

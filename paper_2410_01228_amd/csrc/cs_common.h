@@ -131,10 +131,11 @@ int launch_prefill_merge(const cs_kv_pool& pool, const cs_batch& b, const Prefil
 // count: one per CU), each walking several pairs, the tiles beside them.  Needs the item list
 // in the kernel arguments (dplan.in_args).  Tiles cut into key ranges bring one workgroup per
 // range; the caller merges their partials (launch_prefill_merge) and the cut decode sequences
-// (launch_decode with merge_only) afterwards.
+// (launch_decode with merge_only) afterwards.  tile_priority: 0, or the higher of the two issue
+// priorities the tile wavefronts alternate between (1 or 2; decode wavefronts stay at 0).
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
                  void* decode_workspace_base, void* prefill_workspace, hipStream_t st, bool f16,
-                 bool phase_priority, int32_t persistent_wgs);
+                 int32_t tile_priority, int32_t persistent_wgs);
 
 }  // namespace cs

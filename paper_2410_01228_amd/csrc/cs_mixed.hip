@@ -11,8 +11,8 @@
 //    slots idle until the longest tile is done).  Better when the decode side is small: it does
 //    not hold a slot per CU while the tiles need both.
 // Both kinds of workgroup have 4 wavefronts and share one LDS allocation (a union of the two
-// layouts), so two of them fit a CU in any combination.  kPhasePriority (see prefill_tile) is
-// set by the host beside the tiles, and behind them when the decode side is the small one.
+// layouts), so two of them fit a CU in any combination.  kPriority (see prefill_tile) is
+// chosen by the host: 1 or 2 beside the tiles, 1 behind them when the decode side is the small one.
 #include "cs_prefill_impl.h"
 #include "cs_decode_impl.h"
 
@@ -33,7 +33,7 @@ union MixedLds {
 // range_steps is cut; == num_slots with max_ranges == 1: none is).  Decode workgroup j takes the pairs j, 2*dec_wgs-1-j, 2*dec_wgs+j, ... of the
 // n_decode (item, kv head) pairs: the items are sorted longest first, so walking the rounds back
 // and forth evens the sums; with dec_wgs == n_decode that is one pair each.
-template <int D, class E, bool kPhasePriority, int PS>
+template <int D, class E, int kPriority, int PS>
 __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
     int32_t Hkv, int32_t G, int32_t S,
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
             part_tile = partials_of<D>(prefill_part, pos - cut_first_pos, Hkv, g, max_ranges);
         }
         const int32_t b = base_slot + (backwards ? num_slots - 1 - pos : pos);   // backwards: longest tiles first
-        prefill_tile<D, E, kPhasePriority, PS, true>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
+        prefill_tile<D, E, kPriority, PS, true>(lds.prefill, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks,
                            ctx_lens, cu_q_lens, q, out, scale_log2e, steps_per_range, part_tile, g, b, range);
     } else {
         const uint32_t j = blockIdx.x - dec_first;
@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void mixed_kernel(
 template <class E>
 static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                            const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                           void* decode_ws, void* prefill_ws, hipStream_t st, bool prio, int32_t persistent_wgs)
+                           void* decode_ws, void* prefill_ws, hipStream_t st, int32_t prio, int32_t persistent_wgs)
 {
     const int32_t Hkv = pool.num_kv_heads, D = pool.head_dim, G = Hq / Hkv;
     const uint16_t* layer_base = (const uint16_t*)pool.base + (int64_t)layer * pool.layer_stride;
@@ -109,8 +109,8 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
                        dplan.arg_items, part_o, part_ml);
 #define CS_LAUNCH_MIXED(DD, PRIO)                                                                            \
     if (pool.page_size == 16) { CS_LAUNCH_MIXED_P(DD, PRIO, 16) } else { CS_LAUNCH_MIXED_P(DD, PRIO, 8) }
-    if (D == 128) { if (prio) { CS_LAUNCH_MIXED(128, true) } else { CS_LAUNCH_MIXED(128, false) } }
-    else          { if (prio) { CS_LAUNCH_MIXED(64, true) } else { CS_LAUNCH_MIXED(64, false) } }
+    if (D == 128) { if (prio == 2) { CS_LAUNCH_MIXED(128, 2) } else if (prio == 1) { CS_LAUNCH_MIXED(128, 1) } else { CS_LAUNCH_MIXED(128, 0) } }
+    else          { if (prio == 2) { CS_LAUNCH_MIXED(64, 2) } else if (prio == 1) { CS_LAUNCH_MIXED(64, 1) } else { CS_LAUNCH_MIXED(64, 0) } }
 #undef CS_LAUNCH_MIXED
 #undef CS_LAUNCH_MIXED_P
     return check_launch("mixed kernel");
@@ -118,7 +118,7 @@ static int launch_mixed_as(const cs_kv_pool& pool, int32_t layer, const cs_batch
 
 int launch_mixed(const cs_kv_pool& pool, int32_t layer, const cs_batch& b, const DecodePlan& dplan,
                  const PrefillPlan& pplan, const void* q, void* out, int32_t Hq, float scale,
-                 void* decode_ws, void* prefill_ws, hipStream_t st, bool f16, bool prio, int32_t persistent_wgs)
+                 void* decode_ws, void* prefill_ws, hipStream_t st, bool f16, int32_t prio, int32_t persistent_wgs)
 {
     return f16 ? launch_mixed_as<F16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st, prio, persistent_wgs)
                : launch_mixed_as<Bf16>(pool, layer, b, dplan, pplan, q, out, Hq, scale, decode_ws, prefill_ws, st, prio, persistent_wgs);

@@ -22,7 +22,7 @@ __global__ __launch_bounds__(kPrefillThreads, 2) void prefill_kernel(
     const int32_t b = n_ordered > 0 ? (int32_t)order.slot[pos]
                                     : base_slot + (backwards ? (int32_t)(gridDim.x / Hkv) - 1 - pos : pos);
     // (with key ranges the grid has no order table: cut position = slot position)
-    prefill_tile<D, E, true, PS, false>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
+    prefill_tile<D, E, 1, PS, false>(lds, layer_base, page_stride, num_pages, Hkv, G, S, block_tables, max_blocks, ctx_lens, cu_q_lens,
                        q, out, scale_log2e, range_steps, partials_of<D>(part, b - base_slot, Hkv, g, gridDim.y), g, b,
                        blockIdx.y);
 }

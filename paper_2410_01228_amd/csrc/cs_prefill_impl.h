@@ -126,11 +126,12 @@ struct PrefillLds {
 // whose keys need more than range_steps steps is cut into ranges, each leaving a partial in
 // part_tile[range], the caller's block of partials for this tile and kv head; range_steps at
 // least the tile's steps: the tile is whole and writes the output itself).  `lds` is the
-// workgroup's own.  kPhasePriority: the wavefront alternates
-// its issue priority between the halves of an iteration (for grids whose other wavefronts are
-// mostly tiles too, or become so once a decode workgroup per CU is done; with decode work of
-// equal weight queued behind the tiles it costs more than it gains).
-template <int D, class E, bool kPhasePriority, int PS, bool kLaneAddr16>
+// workgroup's own.  kPriority > 0: the wavefront alternates its issue priority between the
+// halves of an iteration, kPriority - 1 in the score half and kPriority in the P.V half (1: for
+// grids whose other wavefronts are mostly tiles too, or become so once a decode workgroup per CU
+// is done; 2: the same and always above decode wavefronts, which stay at 0; with decode work of
+// equal weight queued behind the tiles either costs more than it gains).
+template <int D, class E, int kPriority, int PS, bool kLaneAddr16>
 __device__ __forceinline__ void prefill_tile(
     PrefillLds<D>& lds,
     const uint16_t* __restrict__ layer_base, int64_t page_stride, int32_t num_pages,
@@ -462,7 +463,7 @@ __device__ __forceinline__ void prefill_tile(
         // a SIMD (one of each resident workgroup) then settle one half apart: the one in its P.V
         // half gets the matrix pipe whenever it asks, the exp / convert work of the other fills
         // the issue slots in between (measured: 7-9% on every shape).
-        if (kPhasePriority) __builtin_amdgcn_s_setprio(0);
+        if (kPriority) __builtin_amdgcn_s_setprio(kPriority - 1);
         dma_step(i + kRing - 1, pg_next);
         pg_next = step_pages(i + kRing);               // consumed by the next iteration
 
@@ -514,7 +515,7 @@ __device__ __forceinline__ void prefill_tile(
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
 
-        if (kPhasePriority) __builtin_amdgcn_s_setprio(1);
+        if (kPriority) __builtin_amdgcn_s_setprio(kPriority);
         if (!kLast) load_k(i + 2);
 #pragma unroll
         for (int c = 0; c < kNCT; ++c)
@@ -553,7 +554,7 @@ __device__ __forceinline__ void prefill_tile(
             for (int j = 0; j < 8; ++j) x[c][j] = xb[c][j];
     }
     iteration(std::true_type{}, std::true_type{}, i, x, xb);
-    if (kPhasePriority) __builtin_amdgcn_s_setprio(0);
+    if (kPriority) __builtin_amdgcn_s_setprio(0);
     wait_vmcnt<0>();                                   // no copy may outlive the workgroup's LDS
 
     // ---- store: lane holds 4 consecutive features of one query row per tile ----

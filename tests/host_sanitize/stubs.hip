@@ -22,6 +22,6 @@ int launch_prefill(const cs_kv_pool&, int32_t, const cs_batch&, const PrefillPla
                    hipStream_t, bool) { reached("prefill"); }
 int launch_prefill_merge(const cs_kv_pool&, const cs_batch&, const PrefillPlan&, void*, int32_t, void*, hipStream_t, bool) { reached("prefill merge"); }
 int launch_mixed(const cs_kv_pool&, int32_t, const cs_batch&, const DecodePlan&, const PrefillPlan&, const void*, void*, int32_t, float,
-                 void*, void*, hipStream_t, bool, bool, int32_t) { reached("mixed"); }
+                 void*, void*, hipStream_t, bool, int32_t, int32_t) { reached("mixed"); }
 
 }  // namespace cs

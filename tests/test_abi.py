@@ -451,6 +451,44 @@ def test_mixed_batches_choose_where_the_decode_work_runs():
     assert lib.cs_debug_mixed_arrangement(ctypes.byref(b), 6, 4, 128) == cs.CS_ERR_INVALID_ARG
 
 
+def test_tile_wavefronts_take_their_issue_priorities_from_the_two_sides_weights():
+    """Tiles beside a decode workgroup per CU alternate their issue priority between the halves of
+    an iteration; where the host's model has them outlast the decode stream by less than 0.8 of
+    its length, both levels lie above the decode wavefronts' (Sec. 4.2: the two kinds of work of
+    an iteration finish together at best).  Behind the tiles the priorities alternate only when the
+    decode side is small, and a call that is not fused has none."""
+    lib = cs.lib()
+    import random
+    rnd = random.Random(5)
+
+    def priority(ctx, ql, Hq=64, Hkv=8):
+        b, keep = _batch(ctx, ql, max_blocks=1 << 16)
+        return lib.cs_debug_mixed_tile_priority(ctypes.byref(b), Hq, Hkv, 128)
+
+    long_decodes = [rnd.randint(2048, 32768) for _ in range(128)]
+    try:
+        lib.cs_debug_set_cu_count(256)
+        # 5 GB of K/V beside a 1024-token chunk on 30K keys: the tiles end about 0.7 of the stream's length after it
+        assert priority(long_decodes + [30720], [1] * 128 + [1024]) == 2
+        # the same stream beside a small chunk: the stream ends last and is not held up
+        assert priority(long_decodes + [4096], [1] * 128 + [256]) == 1
+        # a short stream beside long tiles, forced beside them: the tiles mostly share CUs with each other
+        lib.cs_set_mixed_fusion(3)
+        assert priority([rnd.randint(512, 2048) for _ in range(16)] + [30000], [1] * 16 + [2048]) == 1
+        lib.cs_set_mixed_fusion(1)
+        # behind the tiles: alternating when the decode side is small, none when the two weigh the same
+        assert priority([rnd.randint(512, 2048) for _ in range(8)] + [5000] * 4, [1] * 8 + [512] * 4) == 1
+        lib.cs_set_mixed_fusion(2)
+        assert priority(long_decodes + [30720], [1] * 128 + [1024]) == 0
+        lib.cs_set_mixed_fusion(0)
+        assert priority(long_decodes + [30720], [1] * 128 + [1024]) == 0
+    finally:
+        lib.cs_set_mixed_fusion(1)
+        lib.cs_debug_set_cu_count(0)
+    b, keep = _batch([5], [1])
+    assert lib.cs_debug_mixed_tile_priority(ctypes.byref(b), 6, 4, 128) == cs.CS_ERR_INVALID_ARG
+
+
 def test_tiles_of_the_last_round_are_cut_beside_a_decode_load():
     """Beside the decode workgroups a CU has one slot for tiles, so 512 equal tile workgroups run
     as two rounds of 256, and the second round starts when the decode side is about done: the host
