@@ -507,7 +507,9 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
                     t = next;
                 }
                 t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
-                beside = t_whole < t_behind;
+                // (the model's constants were fitted before the tiles took their priorities beside a
+                // decode load, which make that arrangement about 2% faster than it says)
+                beside = 0.98 * t_whole < t_behind;
             }
             if (beside && mode != 1 && !work.empty()) t_whole = std::max(play_tiles(work, groups, t_dec, free_at, &started), t_dec);
             t_beside = t_whole;
