@@ -402,7 +402,7 @@ int32_t cs_debug_mixed_arrangement(const cs_batch* batch, int32_t num_q_heads, i
  * priorities its tile wavefronts alternate between -- 0: they stay at the default (also when the
  * call is not fused); 1: beside a decode workgroup per CU, and behind tiles that far outweigh the
  * decode work; 2 (always above the decode wavefronts, which stay at 0): beside, where the host's
- * model has the tiles outlast the decode stream by less than 0.8 of its length.
+ * model has the tiles outlast the decode stream by less than its own length.
  * CS_ERR_INVALID_ARG on bad arguments.  No device work. */
 int32_t cs_debug_mixed_tile_priority(const cs_batch* batch, int32_t num_q_heads, int32_t num_kv_heads, int32_t head_dim);
 

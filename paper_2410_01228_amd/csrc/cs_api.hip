@@ -522,20 +522,27 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
                     const int32_t whole = pos_of[first];
                     int32_t tail_steps = 0;
                     for (int32_t pos = whole; pos < p.num_slots; ++pos) tail_steps = std::max(tail_steps, steps_at(pos));
-                    double best = 0.94 * t_whole;
-                    for (int32_t r = 2; r <= 3 && tail_steps / r >= 32; ++r) {
+                    // Two or three ranges of at least 128 steps each: cuts of shorter tiles were
+                    // promised 6-14% by this model and lost 3-6% (the start-up of one more
+                    // workgroup and its partial weigh more than the model has them).  Three ranges
+                    // are taken over two unless the model has them 6% behind: measured over the
+                    // long-tile mixes they are 2% ahead where it calls them 2-5% behind.
+                    double t_r[4] = {0, 0, 0, 0};
+                    for (int32_t r = 2; r <= 3 && tail_steps / r >= 128; ++r) {
                         const int32_t rs = (tail_steps + r - 1) / r, ranges = (tail_steps + rs - 1) / rs;
                         list_work(whole, rs, ranges);
                         const double part_bytes = (double)(p.num_slots - whole) * Hkv * ranges * kTileCols * 16 * (D + 4) * 4.0;
-                        const double t_cut = std::max(play_tiles(work, groups, t_dec, free_at), t_dec) + 10.0 + 2.0 * part_bytes / 5.0e6;
-                        if (t_cut < best) {
-                            best = t_cut;
-                            t_beside = t_cut;
-                            p.cut_first_pos = whole;
-                            p.range_steps = rs;
-                            p.max_ranges = ranges;
-                            p.bytes = (size_t)part_bytes;
-                        }
+                        t_r[r] = std::max(play_tiles(work, groups, t_dec, free_at), t_dec) + 10.0 + 2.0 * part_bytes / 5.0e6;
+                    }
+                    const double bar = 0.94 * t_whole;
+                    const int32_t r = t_r[3] > 0 && t_r[3] < bar && t_r[3] <= 1.06 * t_r[2] ? 3 : 2;
+                    if (t_r[r] > 0 && t_r[r] < bar) {
+                        const int32_t rs = (tail_steps + r - 1) / r, ranges = (tail_steps + rs - 1) / rs;
+                        t_beside = t_r[r];
+                        p.cut_first_pos = whole;
+                        p.range_steps = rs;
+                        p.max_ranges = ranges;
+                        p.bytes = (size_t)((double)(p.num_slots - whole) * Hkv * ranges * kTileCols * 16 * (D + 4) * 4.0);
                     }
                 }
             }
@@ -545,13 +552,13 @@ static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, Pre
         // Beside, the tiles alternate their priority whatever the weights: two tiles share a CU
         // once its decode workgroup is done, and until then it costs nothing (measured -1.5% on
         // average over 196 mixes of four model shapes, -4% with chunks on 30K keys, +3% at worst).
-        // Where the model has the tiles outlast the decode stream, but by less than 0.8 of its
+        // Where the model has the tiles outlast the decode stream, but by less than its own
         // length, both of their priorities lie above the decode wavefronts': over 256 mixes that
         // is worth 3-5% on average in that band (12% at best, 3% lost at worst) and costs 2-3%
         // on either side of it -- a stream that ends last must not be held up, and beside a
         // short one the tiles mostly share their CUs with each other.
         f.arrangement = 2;
-        f.prio = t_beside > t_dec && t_beside < 1.8 * t_dec ? 2 : 1;
+        f.prio = t_beside > t_dec && t_beside < 2.0 * t_dec ? 2 : 1;
         f.persistent_wgs = cus;
     }
     return f;

@@ -453,8 +453,8 @@ def test_mixed_batches_choose_where_the_decode_work_runs():
 
 def test_tile_wavefronts_take_their_issue_priorities_from_the_two_sides_weights():
     """Tiles beside a decode workgroup per CU alternate their issue priority between the halves of
-    an iteration; where the host's model has them outlast the decode stream by less than 0.8 of
-    its length, both levels lie above the decode wavefronts' (Sec. 4.2: the two kinds of work of
+    an iteration; where the host's model has them outlast the decode stream by less than its
+    own length, both levels lie above the decode wavefronts' (Sec. 4.2: the two kinds of work of
     an iteration finish together at best).  Behind the tiles the priorities alternate only when the
     decode side is small, and a call that is not fused has none."""
     lib = cs.lib()
@@ -492,7 +492,7 @@ def test_tile_wavefronts_take_their_issue_priorities_from_the_two_sides_weights(
 def test_tiles_of_the_last_round_are_cut_beside_a_decode_load():
     """Beside the decode workgroups a CU has one slot for tiles, so 512 equal tile workgroups run
     as two rounds of 256, and the second round starts when the decode side is about done: the host
-    cuts exactly those tiles (launch positions 32..63 of 64 at 8 kv heads) in two, and the
+    cuts exactly those tiles (launch positions 32..63 of 64 at 8 kv heads) in three, and the
     workspace holds partials for the cut tiles only.  The knob forces other cuts or none."""
     lib = cs.lib()
     from paper_2410_01228_amd import synth
@@ -509,19 +509,19 @@ def test_tiles_of_the_last_round_are_cut_beside_a_decode_load():
         lib.cs_debug_set_cu_count(256)
         assert lib.cs_debug_mixed_arrangement(ctypes.byref(b), 64, 8, 128) == 2
         n, f, r = cut()
-        assert 64 <= n <= 66 and f == 32 and r == 2
+        assert 64 <= n <= 66 and f == 32 and r == 3
         ws_cut = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128)
         lib.cs_debug_set_tail_cut(-2, 0)                       # no cut by the model
         assert cut()[1:] == (0, 1)
         ws_whole = lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128)
-        assert ws_cut - ws_whole == (n - 32) * 8 * 2 * block
-        lib.cs_debug_set_tail_cut(10, 3)
-        assert cut()[1:] == (10, 3)
-        assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128) - ws_whole == (n - 10) * 8 * 3 * block
+        assert ws_cut - ws_whole == (n - 32) * 8 * 3 * block
+        lib.cs_debug_set_tail_cut(10, 2)
+        assert cut()[1:] == (10, 2)
+        assert lib.cs_paged_attention_workspace_bytes(ctypes.byref(b), 64, 8, 128) - ws_whole == (n - 10) * 8 * 2 * block
         lib.cs_debug_set_tail_cut(1000, 3)                     # behind the last tile: nothing is cut
         assert cut()[1:] == (n, 1)
         lib.cs_debug_set_tail_cut(-1, 0)
-        assert cut()[1:] == (32, 2)
+        assert cut()[1:] == (32, 3)
         # behind the tiles nothing of the kind happens
         lib.cs_set_mixed_fusion(2)
         assert cut()[1:] == (0, 1)
