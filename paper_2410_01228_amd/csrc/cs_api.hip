@@ -418,7 +418,7 @@ static double play_tiles(const std::vector<float>& work, int32_t cus, double dec
 // beside a decode load, so the bar is not lower).
 static FusePlan plan_fusion_by_model(const cs_batch* b, const DecodePlan& d, PrefillPlan& p, int32_t Hq, int32_t Hkv,
                                      int32_t D, int32_t mode) {
-    FusePlan f = {0, false, 0};
+    FusePlan f = {0, 0, 0};
     if (d.num_prefill == 0 || d.num_decode == 0 || !d.in_args || mode == 0) return f;
     const int32_t G = Hq / Hkv;
     double pairs = 0;
